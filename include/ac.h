@@ -1,0 +1,165 @@
+/*
+ * ac.h - C ABI of the MI355X (gfx950) dense tensor library.
+ *
+ * The operations are the ones arxiv 2505.18574 (Autocomp) optimises on its
+ * accelerators: int8 GEMM and convolution with the int8 accelerator's bias /
+ * scale-down / saturate / ReLU output stage (Section 5.1, Appendix B), the
+ * large GEMM of the GPU study (Appendix A, Table 5) in bf16 with fp32
+ * accumulation, and the batched fine-grained fp32 linear algebra of the
+ * TinyMPC study (Section 5.1.3, Appendix D.2).
+ *
+ * Conventions shared by every entry point
+ *  - Every data pointer is a DEVICE pointer into memory owned by the caller.
+ *    The library allocates nothing, frees nothing, keeps no state between
+ *    calls and never synchronises: work is enqueued on `stream` (a
+ *    hipStream_t passed as void*; NULL = the default stream) and the call
+ *    returns once the kernels are launched.
+ *  - All matrices are row-major.  Leading dimensions (lda, ...) are in
+ *    ELEMENTS and may exceed the row length.
+ *  - An output must not share its base address with an input
+ *    (AC_ERR_ALIAS); partially overlapping buffers are undefined.
+ *  - Arguments are validated on the host before anything is launched; on any
+ *    error a negative ac_status is returned and no work is enqueued.
+ *    No C++ exception crosses this boundary.
+ *  - Zero-sized problems (M, N or batch == 0) return AC_OK without a launch.
+ */
+#ifndef AC_H_
+#define AC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t ac_status;
+
+enum {
+  AC_OK = 0,
+  AC_ERR_NULL = -1,      /* a required pointer is NULL                              */
+  AC_ERR_SHAPE = -2,     /* a negative size, or a size outside the supported range  */
+  AC_ERR_STRIDE = -3,    /* a leading dimension smaller than the row length         */
+  AC_ERR_SHIFT = -4,     /* shift outside 0..31                                     */
+  AC_ERR_ACT = -5,       /* unknown activation                                      */
+  AC_ERR_ALIAS = -6,     /* an output has the same base address as an input         */
+  AC_ERR_WORKSPACE = -7, /* workspace pointer/size inconsistent                     */
+  AC_ERR_LAUNCH = -8     /* the HIP runtime refused the launch                      */
+};
+
+/* Activations of the output stage (Appendix B, Fig. 13: the `act` field of
+ * config_ex).  The normalisation-type activations listed there are not part
+ * of this library. */
+enum { AC_ACT_NONE = 0, AC_ACT_RELU = 1 };
+
+/*
+ * int8 GEMM with the int8 accelerator's output stage.
+ *
+ *   acc[i][j] = sum_k A[i][k] * B[k][j] + bias(i, j)           exact, int32
+ *   C[i][j]   = act( sat8( rne_rshift(acc[i][j], shift) ) )    int8
+ *
+ * The contraction is the matrix product of Section 2 (Fig. 2) on the
+ * A[M][K], B[K][N], C[M][N] operands of the paper's GEMM kernels
+ * (Appendix D.1).  The bias enters through the accumulator ("C = A * B +
+ * bias", Appendix B Fig. 13); the int8 result is the scaled-down read of the
+ * accumulator with the configured activation (Appendix B Fig. 14, bit 29).
+ * rne_rshift(v, s) is v / 2^s rounded to the nearest integer with halves to
+ * the even neighbour; sat8 clamps to [-128, 127]; act is AC_ACT_NONE or
+ * AC_ACT_RELU.  The result is defined when every exact sum fits in int32.
+ *
+ *   A     device, int8,  M x K, row stride lda >= K
+ *   B     device, int8,  K x N, row stride ldb >= N
+ *   bias  device, int32; NULL = no bias; bias_ld == 0: a row of N values added
+ *         to every row of the product; bias_ld >= N: an M x N matrix with that
+ *         row stride
+ *   C     device, int8,  M x N, row stride ldc >= N (written, never read)
+ *   K == 0 gives C = stage(bias).
+ *   workspace / workspace_bytes: optional device scratch of at least
+ *         ac_gemm_i8_workspace_bytes(M, N, K) bytes, 16-byte aligned, which
+ *         lets the library split the K range of shapes with few output tiles
+ *         over more compute units; its contents on entry and exit are
+ *         unspecified and concurrent calls must not share it.  NULL / 0 is
+ *         always accepted (no split).  A non-NULL workspace that is too small
+ *         or misaligned gives AC_ERR_WORKSPACE.
+ */
+ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                     const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                     int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace with which ac_gemm_i8 may split K for this shape
+ * (0 when it would not split).  Pure host arithmetic. */
+size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+/*
+ * int8 2-D convolution (the convolution workload of Section 5.1.2) computed
+ * as an implicit GEMM with M = Nb*OH*OW, N = Cout, K = KH*KW*Cin, followed by
+ * the same output stage as ac_gemm_i8:
+ *
+ *   out[n][oh][ow][co] = stage( bias[co] + sum_{kh,kw,ci}
+ *        in[n][oh*stride - pad + kh][ow*stride - pad + kw][ci] * w[kh][kw][ci][co] )
+ *
+ * Taps outside the image read as zero.  OH = (H + 2*pad - KH) / stride + 1
+ * (integer division), OW likewise.
+ *
+ *   in    device, int8, [Nb][H][W][Cin]      (dense NHWC)
+ *   w     device, int8, [KH][KW][Cin][Cout]  (dense; the K x N matrix of the GEMM)
+ *   bias  device, int32, [Cout], or NULL
+ *   out   device, int8, [Nb][OH][OW][Cout]   (dense NHWC; written, never read)
+ *   stride >= 1, pad >= 0, KH <= H + 2*pad, KW <= W + 2*pad, else AC_ERR_SHAPE.
+ *   workspace: as for ac_gemm_i8 with the implicit-GEMM shape.
+ */
+ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, int8_t* out,
+                       int32_t Nb, int32_t H, int32_t W, int32_t Cin, int32_t Cout,
+                       int32_t KH, int32_t KW, int32_t stride, int32_t pad,
+                       int32_t shift, int32_t act,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * bf16 GEMM with fp32 accumulation and fp32 output (the square GEMM of
+ * Appendix A Table 5, at the reduced input precision Section 5.3 reports as
+ * the route to the matrix units):
+ *
+ *   C = alpha * (A . B) + beta * C
+ *
+ *   A  device, bf16 bit patterns (uint16), M x K, row stride lda >= K
+ *   B  device, bf16 bit patterns,          K x N, row stride ldb >= N
+ *   C  device, fp32, M x N, row stride ldc >= N; read only when beta != 0
+ *      (with beta == 0 it may hold anything, NaN included)
+ *   K == 0 gives C = beta * C.
+ * Products are exact in fp32; sums are accumulated in fp32 in an unspecified
+ * order.
+ */
+ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
+                       float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                       float alpha, float beta, void* stream);
+
+/*
+ * Batched small fp32 linear algebra (the fine-grained workload of Section
+ * 5.1.3: small dense products chained with matrix-vector products and
+ * element-wise adds), for each item b independently:
+ *
+ *   C_b = A_b . B_b                 (n x n)
+ *   y_b = C_b . x_b + d_b           (uses the unrounded-in-between fp32 C_b)
+ *
+ *   A, B  device, fp32, [batch][n][n] dense
+ *   C     device, fp32, [batch][n][n], or NULL to skip storing the product
+ *   x     device, fp32, [batch][n], or NULL to skip the matrix-vector stage
+ *   d     device, fp32, [batch][n], or NULL for no add
+ *   y     device, fp32, [batch][n]; required iff x != NULL
+ *   1 <= n <= 16; at least one of C, y must be requested.
+ */
+ac_status ac_batched_gemm_f32(const float* A, const float* B, float* C,
+                              const float* x, const float* d, float* y,
+                              int32_t n, int64_t batch, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* ac_status_string(ac_status status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t ac_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AC_H_ */

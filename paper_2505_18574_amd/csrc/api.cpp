@@ -1,0 +1,142 @@
+// C ABI of the library (include/ac.h): argument validation on the host, then a
+// launch on the caller's stream.  Nothing here allocates, frees or synchronises.
+#include "../../include/ac.h"
+#include "common.hpp"
+
+#include <limits.h>
+
+namespace {
+
+bool fits_i32(int64_t v) { return v >= 0 && v <= INT_MAX; }
+
+ac_status check_stage(int32_t shift, int32_t act) {
+  if (shift < 0 || shift > 31) return AC_ERR_SHIFT;
+  if (act != AC_ACT_NONE && act != AC_ACT_RELU) return AC_ERR_ACT;
+  return AC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ac_status_string(ac_status status) {
+  switch (status) {
+    case AC_OK: return "ok";
+    case AC_ERR_NULL: return "a required pointer is NULL";
+    case AC_ERR_SHAPE: return "a size is negative or outside the supported range";
+    case AC_ERR_STRIDE: return "a leading dimension is smaller than the row length";
+    case AC_ERR_SHIFT: return "shift must be in 0..31";
+    case AC_ERR_ACT: return "unknown activation";
+    case AC_ERR_ALIAS: return "an output has the same base address as an input";
+    case AC_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case AC_ERR_LAUNCH: return "the HIP runtime refused the launch";
+    default: return "unknown status";
+  }
+}
+
+int32_t ac_version(void) { return 100; }
+
+size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K) {
+  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  const ac::I8Plan plan = ac::plan_gemm_i8(M, N, K, true);
+  if (plan.splits <= 1) return 0;
+  const size_t tiles = (size_t)((M + plan.tile - 1) / plan.tile) * (size_t)((N + plan.tile - 1) / plan.tile);
+  // int32 partial sums for every slice, then one arrival counter per output tile
+  return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t) + tiles * sizeof(uint32_t);
+}
+
+ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                     const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                     int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (ac_status s = check_stage(shift, act)) return s;
+  if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
+  if (bias && bias_ld != 0 && bias_ld < N) return AC_ERR_STRIDE;
+  if (bias_ld < 0) return AC_ERR_STRIDE;
+  if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;
+  if (workspace && (((uintptr_t)workspace & 15) != 0 || workspace_bytes < ac_gemm_i8_workspace_bytes(M, N, K)))
+    return AC_ERR_WORKSPACE;
+  if (M == 0 || N == 0) return AC_OK;
+  if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
+  if ((const void*)C == (const void*)A || (const void*)C == (const void*)B || (const void*)C == (const void*)bias)
+    return AC_ERR_ALIAS;
+
+  ac::GemmParams p = {};
+  p.A = A; p.B = B; p.C = C; p.bias = bias;
+  p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.bias_ld = bias_ld;
+  p.M = M; p.N = N; p.K = K; p.shift = shift; p.act = act;
+  p.splits = 1;
+  p.partial = (int32_t*)workspace;
+  return ac::launch_gemm_i8(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
+ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, int8_t* out,
+                       int32_t Nb, int32_t H, int32_t W, int32_t Cin, int32_t Cout,
+                       int32_t KH, int32_t KW, int32_t stride, int32_t pad,
+                       int32_t shift, int32_t act,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (Nb < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0 || KH < 1 || KW < 1 || stride < 1 || pad < 0) return AC_ERR_SHAPE;
+  if (ac_status s = check_stage(shift, act)) return s;
+  if ((int64_t)KH > (int64_t)H + 2 * (int64_t)pad || (int64_t)KW > (int64_t)W + 2 * (int64_t)pad) return AC_ERR_SHAPE;
+  if (H > 32767 - pad || W > 32767 - pad) return AC_ERR_SHAPE;  // image coordinates are kept in 16 bits
+  const int64_t OH = ((int64_t)H + 2 * pad - KH) / stride + 1, OW = ((int64_t)W + 2 * pad - KW) / stride + 1;
+  const int64_t M = (int64_t)Nb * OH * OW, K = (int64_t)KH * KW * Cin;
+  const int64_t in_elems = (int64_t)Nb * H * W * Cin;
+  // the kernel indexes the image and the implicit GEMM with 32-bit offsets
+  if (!fits_i32(M) || !fits_i32(K) || !fits_i32(in_elems + (int64_t)KH * W * Cin)) return AC_ERR_SHAPE;
+  if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;
+  if (workspace && (((uintptr_t)workspace & 15) != 0 ||
+                    workspace_bytes < ac_gemm_i8_workspace_bytes((int32_t)M, Cout, (int32_t)K)))
+    return AC_ERR_WORKSPACE;
+  if (M == 0 || Cout == 0) return AC_OK;
+  if (!out || (K > 0 && (!in || !w))) return AC_ERR_NULL;
+  if ((const void*)out == (const void*)in || (const void*)out == (const void*)w || (const void*)out == (const void*)bias)
+    return AC_ERR_ALIAS;
+
+  ac::GemmParams p = {};
+  p.A = in; p.B = w; p.C = out; p.bias = bias;
+  p.lda = 0; p.ldb = Cout; p.ldc = Cout; p.bias_ld = 0;
+  p.M = (int32_t)M; p.N = Cout; p.K = (int32_t)K; p.shift = shift; p.act = act;
+  p.H = H; p.W = W; p.Cin = Cin; p.KW = KW; p.OH = (int32_t)OH; p.OW = (int32_t)OW; p.stride = stride; p.pad = pad;
+  p.splits = 1;
+  p.partial = (int32_t*)workspace;
+  return ac::launch_conv2d_i8(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
+ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
+                       float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                       float alpha, float beta, void* stream) {
+  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
+  if (M == 0 || N == 0) return AC_OK;
+  if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
+  if ((const void*)C == (const void*)A || (const void*)C == (const void*)B) return AC_ERR_ALIAS;
+
+  ac::GemmParams p = {};
+  p.A = A; p.B = B; p.C = C;
+  p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  p.M = M; p.N = N; p.K = K; p.alpha = alpha; p.beta = beta;
+  p.splits = 1;
+  return ac::launch_gemm_bf16(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
+ac_status ac_batched_gemm_f32(const float* A, const float* B, float* C,
+                              const float* x, const float* d, float* y,
+                              int32_t n, int64_t batch, void* stream) {
+  if (n < 1 || n > 16 || batch < 0) return AC_ERR_SHAPE;
+  if (batch == 0) return AC_OK;
+  if (!A || !B) return AC_ERR_NULL;
+  if (!C && !x) return AC_ERR_NULL;       // nothing requested
+  if ((x != nullptr) != (y != nullptr)) return AC_ERR_NULL;
+  if (d && !x) return AC_ERR_NULL;
+  const void* ins[4] = {A, B, x, d};
+  for (const void* q : ins)
+    if (q && ((const void*)C == q || (const void*)y == q)) return AC_ERR_ALIAS;
+  if (C && (const void*)C == (const void*)y) return AC_ERR_ALIAS;
+
+  ac::BatchedParams p = {A, B, C, x, d, y, n, batch};
+  return ac::launch_batched_f32(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
+}  // extern "C"

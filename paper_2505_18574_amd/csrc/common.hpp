@@ -1,0 +1,61 @@
+// Shared host/device declarations of the gfx950 kernels: vector types, the
+// problem descriptors the host fills in, and the launcher prototypes that the
+// C-ABI layer (api.cpp) calls.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ac {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+// One descriptor serves the int8 GEMM, the int8 implicit-GEMM convolution and
+// the bf16 GEMM: all three are C[M][N] = epilogue(A[M][K] . B[K][N]).
+struct GemmParams {
+  const void* A;        // GEMM: M x K row-major.  Convolution: the NHWC input image.
+  const void* B;        // K x N row-major (convolution: [KH][KW][Cin][Cout])
+  void* C;              // M x N row-major
+  const int32_t* bias;  // int8 paths only; may be null
+  int64_t lda, ldb, ldc, bias_ld;  // in elements; bias_ld == 0 broadcasts one row
+  int32_t M, N, K;
+  int32_t shift, act;   // int8 output stage
+  float alpha, beta;    // bf16 epilogue
+  // convolution geometry (implicit GEMM: m -> (n, oh, ow), k -> (kh, kw, ci))
+  int32_t H, W, Cin, KW, OH, OW, stride, pad;
+  // split-K (int8): number of K slices and the int32 partial-sum workspace
+  int32_t splits;
+  int32_t* partial;     // [splits][M][N] int32 when splits > 1
+  uint32_t* counters;   // one arrival counter per output tile when splits > 1
+};
+
+struct BatchedParams {
+  const float* A;
+  const float* B;
+  float* C;        // may be null
+  const float* x;  // may be null
+  const float* d;  // may be null
+  float* y;        // non-null iff x is
+  int32_t n;
+  int64_t batch;
+};
+
+hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream);
+hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream);
+hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream);
+hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream);
+
+// Tile choice made by the int8 launcher for a shape; shared with the workspace query.
+struct I8Plan {
+  int tile;    // 64, 128 or 256 (square block tile)
+  int splits;  // K slices (1 = no split)
+};
+I8Plan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace);
+
+}  // namespace ac

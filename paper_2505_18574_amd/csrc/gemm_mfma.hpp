@@ -1,0 +1,379 @@
+// Tiled MFMA GEMM for gfx950 (CDNA4), shared by the int8 GEMM, the int8
+// implicit-GEMM convolution and the bf16 GEMM.
+//
+// One workgroup owns a BM x BN tile of C.  Per K step of 128 bytes of A-row:
+//   global (16 B per lane, coalesced) -> registers -> LDS (double buffered)
+//   LDS -> MFMA operands: A rows by ds_read_b128 (K is contiguous in A);
+//   B columns by the gfx950 transposing LDS reads (ds_read_b64_tr_b8/_b16),
+//   because B is K x N row-major and the matrix unit wants K contiguous per lane.
+//   32x32 MFMA tiles (i32_32x32x32_i8 / f32_32x32x16_bf16), accumulators in registers.
+// The two MFMA source operands are swapped (B^T tile as the row operand, A tile
+// as the column operand) so that each lane ends up holding 4 consecutive n of one
+// row m: the epilogue can then requantise in registers and store 4 packed int8
+// (or a float4) without an LDS transpose.
+#pragma once
+#include "common.hpp"
+
+namespace ac {
+
+#define AC_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+struct TypeI8 {
+  static constexpr int EB = 1;  // element bytes
+  using accv = v16i;
+  static __device__ __forceinline__ accv zero() {
+    accv z;
+#pragma unroll
+    for (int r = 0; r < 16; r++) z[r] = 0;
+    return z;
+  }
+  static __device__ __forceinline__ accv mfma(v4i rowop, v4i colop, accv c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(rowop, colop, c, 0, 0, 0);
+  }
+  // 16 consecutive k (bytes) of one B column, gathered from K-major LDS rows.
+  // Within a 16-lane group lane i supplies the address of 8 bytes of row i/2 and
+  // receives 8 k-values of column i.
+  static __device__ __forceinline__ v4i read_col(const unsigned char* tile, int stride, int k0, int ncol_bytes, int lane) {
+    int i = lane & 15;
+    const unsigned char* p = tile + (k0 + (i >> 1)) * stride + ncol_bytes + 8 * (i & 1);
+    v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(AC_LDS(v2i, p));
+    v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(AC_LDS(v2i, p + 8 * stride));
+    return (v4i){lo[0], lo[1], hi[0], hi[1]};
+  }
+};
+
+struct TypeBF16 {
+  static constexpr int EB = 2;
+  using accv = v16f;
+  static __device__ __forceinline__ accv zero() {
+    accv z;
+#pragma unroll
+    for (int r = 0; r < 16; r++) z[r] = 0.f;
+    return z;
+  }
+  static __device__ __forceinline__ accv mfma(v4i rowop, v4i colop, accv c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, rowop), __builtin_bit_cast(v8bf, colop), c, 0, 0, 0);
+  }
+  // 8 consecutive k of one B column: lane i of a 16-lane group addresses 4
+  // elements of row i/4 and receives 4 k-values of column i.
+  static __device__ __forceinline__ v4i read_col(const unsigned char* tile, int stride, int k0, int ncol_bytes, int lane) {
+    int i = lane & 15;
+    const unsigned char* p = tile + (k0 + (i >> 2)) * stride + ncol_bytes + 8 * (i & 3);
+    v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(AC_LDS(v4s, p));
+    v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(AC_LDS(v4s, p + 4 * stride));
+    v2i l2 = __builtin_bit_cast(v2i, lo), h2 = __builtin_bit_cast(v2i, hi);
+    return (v4i){l2[0], l2[1], h2[0], h2[1]};
+  }
+};
+
+// 16 bytes from p, of which only the first `valid` (may be <= 0 or >= 16) exist.
+static __device__ __forceinline__ v4i load16_bytes(const unsigned char* p, int valid) {
+  unsigned int w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 16; e++)
+    if (e < valid) w[e >> 2] |= (unsigned int)p[e] << (8 * (e & 3));
+  return (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+}
+
+template <bool ALIGNED>
+static __device__ __forceinline__ v4i load16(const unsigned char* p, int valid) {
+  if (valid <= 0) return (v4i){0, 0, 0, 0};
+  if (ALIGNED && valid >= 16) return *(const v4i*)p;
+  return load16_bytes(p, valid);
+}
+
+// XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each
+// with its own L2), so workgroup b runs on XCD b % 8.  Give every XCD one
+// contiguous run of logical tile ids, and lay those ids out in bands of GROUP_M
+// tile-rows so that a run is a compact rectangle sharing A rows and B columns.
+static __device__ __forceinline__ void tile_coords(int b, int nblocks, int tiles_m, int tiles_n, int& tm, int& tn) {
+  constexpr int XCDS = 8, GROUP_M = 4;
+  int q = nblocks / XCDS, r = nblocks % XCDS;
+  int xcd = b % XCDS, idx = b / XCDS;
+  int id = xcd * q + (xcd < r ? xcd : r) + idx;
+  int group_size = GROUP_M * tiles_n;
+  int group = id / group_size;
+  int first_m = group * GROUP_M;
+  int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+  int in_group = id - group * group_size;
+  tm = first_m + in_group % gsz;
+  tn = in_group / gsz;
+}
+
+// Epilogue policies -----------------------------------------------------------
+// Each receives, for one lane, 4 accumulators of row m at columns n .. n+3.
+
+// int8 output stage: bias, v / 2^shift to nearest (halves to even), saturate, ReLU.
+struct EpilogueI8 {
+  static __device__ __forceinline__ int requant(int v, int shift, int act) {
+    int fl = v >> shift;
+    unsigned int rem = (unsigned int)v & ((1u << shift) - 1u);
+    unsigned int half = shift > 0 ? (1u << (shift - 1)) : 0u;
+    int inc = (shift > 0) && (rem > half || (rem == half && (fl & 1)));
+    int q = fl + inc;
+    q = q > 127 ? 127 : q;
+    q = q < -128 ? -128 : q;
+    if (act) q = q < 0 ? 0 : q;
+    return q;
+  }
+  template <bool VEC>
+  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a) {
+    if (m >= p.M || n >= p.N) return;
+    int8_t* C = (int8_t*)p.C;
+    int v[4];
+    const bool full = n + 3 < p.N;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      int b = 0;
+      if (p.bias && (full || n + e < p.N)) b = p.bias_ld == 0 ? p.bias[n + e] : p.bias[(int64_t)m * p.bias_ld + n + e];
+      v[e] = requant(a[e] + b, p.shift, p.act);
+    }
+    int8_t* dst = C + (int64_t)m * p.ldc + n;
+    if (VEC && full) {
+      unsigned int w = (unsigned int)(v[0] & 0xff) | ((unsigned int)(v[1] & 0xff) << 8) | ((unsigned int)(v[2] & 0xff) << 16) | ((unsigned int)(v[3] & 0xff) << 24);
+      *(unsigned int*)dst = w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+        if (n + e < p.N) dst[e] = (int8_t)v[e];
+    }
+  }
+};
+
+// fp32 output: C = alpha * acc + beta * C (C read only when beta != 0).
+struct EpilogueF32 {
+  template <bool VEC>
+  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a) {
+    if (m >= p.M || n >= p.N) return;
+    float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
+    const bool full = n + 3 < p.N;
+    if (VEC && full) {
+      v4f o = {p.alpha * a[0], p.alpha * a[1], p.alpha * a[2], p.alpha * a[3]};
+      if (p.beta != 0.f) {
+        v4f c = *(const v4f*)dst;
+        o += p.beta * c;
+      }
+      *(v4f*)dst = o;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+        if (n + e < p.N) {
+          float o = p.alpha * a[e];
+          if (p.beta != 0.f) o += p.beta * dst[e];
+          dst[e] = o;
+        }
+    }
+  }
+};
+
+// A-operand addressing ----------------------------------------------------------
+// AMODE 0: A is an M x K matrix.  AMODE 1: A(m, k) is gathered from an NHWC image
+// (m -> (image, oh, ow), k -> (kh, kw, ci)), zero outside the image.
+template <int AMODE>
+struct ARow;
+
+template <>
+struct ARow<0> {
+  const unsigned char* ptr;  // start of the row, null when the row is outside M
+  __device__ __forceinline__ void init(const GemmParams& p, int m, int EB) {
+    ptr = m < p.M ? (const unsigned char*)p.A + (int64_t)m * p.lda * EB : nullptr;
+  }
+};
+
+template <>
+struct ARow<1> {
+  int base;  // element offset of (image, ih0, iw0, 0); may be negative-side of the image, only used when in range
+  short ih0, iw0;
+  bool ok;
+  __device__ __forceinline__ void init(const GemmParams& p, int m, int) {
+    ok = m < p.M;
+    int mm = ok ? m : 0;
+    int ow = mm % p.OW;
+    int t = mm / p.OW;
+    int oh = t % p.OH;
+    int img = t / p.OH;
+    ih0 = (short)(oh * p.stride - p.pad);
+    iw0 = (short)(ow * p.stride - p.pad);
+    base = ((img * p.H + ih0) * p.W + iw0) * p.Cin;
+  }
+};
+
+template <class T, int BM, int BN, int WAVES_M, int WAVES_N>
+struct TileGeometry {
+  static constexpr int EB = T::EB;
+  static constexpr int KTB = 128;            // bytes of K per A row per step
+  static constexpr int BK = KTB / EB;        // elements of K per step
+  static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
+  static constexpr int A_STRIDE = KTB + 16;  // padded LDS row: conflict-free b128 reads
+  static constexpr int B_STRIDE = BN * EB + 16;
+  static constexpr int A_BYTES = BM * A_STRIDE;
+  static constexpr int B_BYTES = BK * B_STRIDE;
+  static constexpr int STAGE = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int A_ROWS_PER_PASS = THREADS / 8;
+  static constexpr int A_IT = BM / A_ROWS_PER_PASS;
+  static constexpr int B_CPR = BN * EB / 16;  // 16-byte chunks per B row
+  static constexpr int B_ROWS_PER_PASS = THREADS / B_CPR;
+  static constexpr int B_IT = BK / B_ROWS_PER_PASS;
+  static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  static constexpr int TM = WTM / 32, TN = WTN / 32;
+  static_assert(BM % A_ROWS_PER_PASS == 0 && A_IT >= 1, "A tile / thread mismatch");
+  static_assert(THREADS % B_CPR == 0 && BK % B_ROWS_PER_PASS == 0 && B_IT >= 1, "B tile / thread mismatch");
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+};
+
+template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, bool ALIGNED>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_mfma_kernel(const GemmParams p, const int tiles_m, const int tiles_n) {
+  using G = TileGeometry<T, BM, BN, WAVES_M, WAVES_N>;
+  constexpr int EB = G::EB;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  int tm, tn;
+  tile_coords(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  typename T::accv acc[G::TM][G::TN];
+#pragma unroll
+  for (int i = 0; i < G::TM; i++)
+#pragma unroll
+    for (int j = 0; j < G::TN; j++) acc[i][j] = T::zero();
+
+  // ---- per-thread staging assignment
+  const int a_cc = t & 7, a_r0 = t >> 3;
+  const int b_cc = t % G::B_CPR, b_r0 = t / G::B_CPR;
+  ARow<AMODE> arow[G::A_IT];
+#pragma unroll
+  for (int i = 0; i < G::A_IT; i++) arow[i].init(p, m0 + a_r0 + i * G::A_ROWS_PER_PASS, EB);
+  const int kbytes = p.K * EB;               // valid bytes per A row
+  const int nbytes = p.N * EB;               // valid bytes per B row
+  const int b_col = n0 * EB + b_cc * 16;     // byte column of this thread's B chunks
+  const unsigned char* Bp = (const unsigned char*)p.B;
+
+  v4i ra[G::A_IT], rb[G::B_IT];
+
+  auto gload = [&](int kt) {
+    const int ka = kt * G::KTB + a_cc * 16;  // byte offset along K of this thread's A chunks
+    if constexpr (AMODE == 0) {
+#pragma unroll
+      for (int i = 0; i < G::A_IT; i++) {
+        const unsigned char* rp = arow[i].ptr;
+        ra[i] = rp ? load16<ALIGNED>(rp + ka, kbytes - ka) : (v4i){0, 0, 0, 0};
+      }
+    } else {
+      const unsigned char* in = (const unsigned char*)p.A;
+      if constexpr (ALIGNED) {  // Cin % 16 == 0: a chunk never straddles a kernel tap
+        int tap = ka / p.Cin, ci = ka - tap * p.Cin;
+        int kh = tap / p.KW, kw = tap - kh * p.KW;
+        int koff = (kh * p.W + kw) * p.Cin + ci;
+#pragma unroll
+        for (int i = 0; i < G::A_IT; i++) {
+          const ARow<1>& r = arow[i];
+          int ih = r.ih0 + kh, iw = r.iw0 + kw;
+          bool ok = r.ok && ka < kbytes && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+          ra[i] = ok ? *(const v4i*)(in + r.base + koff) : (v4i){0, 0, 0, 0};
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < G::A_IT; i++) {
+          const ARow<1>& r = arow[i];
+          unsigned int w[4] = {0u, 0u, 0u, 0u};
+          for (int e = 0; e < 16; e++) {
+            int k = ka + e;
+            if (r.ok && k < kbytes) {
+              int tap = k / p.Cin, ci = k - tap * p.Cin;
+              int kh = tap / p.KW, kw = tap - kh * p.KW;
+              int ih = r.ih0 + kh, iw = r.iw0 + kw;
+              if ((unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
+                w[e >> 2] |= (unsigned int)in[r.base + (kh * p.W + kw) * p.Cin + ci] << (8 * (e & 3));
+            }
+          }
+          ra[i] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < G::B_IT; i++) {
+      int k = kt * G::BK + b_r0 + i * G::B_ROWS_PER_PASS;
+      rb[i] = k < p.K ? load16<ALIGNED>(Bp + ((int64_t)k * p.ldb) * EB + b_col, nbytes - b_col) : (v4i){0, 0, 0, 0};
+    }
+  };
+
+  auto lstore = [&](int buf) {
+    unsigned char* As = smem + buf * G::STAGE;
+    unsigned char* Bs = As + G::A_BYTES;
+#pragma unroll
+    for (int i = 0; i < G::A_IT; i++) *(v4i*)(As + (a_r0 + i * G::A_ROWS_PER_PASS) * G::A_STRIDE + a_cc * 16) = ra[i];
+#pragma unroll
+    for (int i = 0; i < G::B_IT; i++) *(v4i*)(Bs + (b_r0 + i * G::B_ROWS_PER_PASS) * G::B_STRIDE + b_cc * 16) = rb[i];
+  };
+
+  auto compute = [&](int buf) {
+    const unsigned char* As = smem + buf * G::STAGE;
+    const unsigned char* Bs = As + G::A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) {  // 4 MFMA K-steps of 32 bytes per tile
+      v4i af[G::TM], bf[G::TN];
+      const int kb = ks * 32 + (lane >> 5) * 16;  // this lane's 16 bytes of K
+#pragma unroll
+      for (int i = 0; i < G::TM; i++) af[i] = *(const v4i*)(As + (wm * G::WTM + i * 32 + (lane & 31)) * G::A_STRIDE + kb);
+#pragma unroll
+      for (int j = 0; j < G::TN; j++)
+        bf[j] = T::read_col(Bs, G::B_STRIDE, kb / EB, (wn * G::WTN + j * 32 + 16 * ((lane >> 4) & 1)) * EB, lane);
+#pragma unroll
+      for (int i = 0; i < G::TM; i++)
+#pragma unroll
+        for (int j = 0; j < G::TN; j++) acc[i][j] = T::mfma(bf[j], af[i], acc[i][j]);
+    }
+  };
+
+  const int nkt = (kbytes + G::KTB - 1) / G::KTB;
+  if (nkt > 0) {
+    gload(0);
+    lstore(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nkt; kt++) {
+    const bool more = kt + 1 < nkt;
+    if (more) gload(kt + 1);
+    compute(kt & 1);
+    if (more) lstore((kt + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane holds, per 32x32 tile and per q, row m and columns n..n+3
+  const bool vec = ALIGNED;  // host guarantees C alignment / ldc divisibility when ALIGNED
+#pragma unroll
+  for (int i = 0; i < G::TM; i++) {
+    const int m = m0 + wm * G::WTM + i * 32 + (lane & 31);
+#pragma unroll
+    for (int j = 0; j < G::TN; j++) {
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int n = n0 + wn * G::WTN + j * 32 + 8 * q + 4 * (lane >> 5);
+        decltype(acc[i][j][0] + 0) a4[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        if (vec) EPI::template store4<true>(p, m, n, a4);
+        else EPI::template store4<false>(p, m, n, a4);
+      }
+    }
+  }
+}
+
+// Host-side launcher for one instantiation.
+template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, bool ALIGNED>
+static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
+  using G = TileGeometry<T, BM, BN, WAVES_M, WAVES_N>;
+  auto kern = gemm_mfma_kernel<T, EPI, BM, BN, WAVES_M, WAVES_N, AMODE, ALIGNED>;
+  static bool configured = false;  // raising the dynamic-LDS limit is idempotent
+  if (!configured && G::LDS_BYTES > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(G::THREADS), G::LDS_BYTES, stream, p, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+}  // namespace ac

@@ -1,0 +1,185 @@
+"""Thin binding over the C ABI of ``libac_mi355x.so`` (see ``include/ac.h``).
+
+Argument marshalling only: every function takes device tensors (PyTorch-ROCm is
+used for device memory and streams, nothing else), passes their addresses,
+leading dimensions and sizes to the entry point of the same name, and raises
+``AcError`` on a non-zero status.  There is no CPU fallback: if the HIP library
+has not been built, loading fails with an ImportError.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libac_mi355x.so")
+
+AC_OK = 0
+AC_ERR_NULL, AC_ERR_SHAPE, AC_ERR_STRIDE, AC_ERR_SHIFT = -1, -2, -3, -4
+AC_ERR_ACT, AC_ERR_ALIAS, AC_ERR_WORKSPACE, AC_ERR_LAUNCH = -5, -6, -7, -8
+AC_ACT_NONE, AC_ACT_RELU = 0, 1
+
+# every symbol include/ac.h declares
+EXPORTS = ("ac_gemm_i8", "ac_gemm_i8_workspace_bytes", "ac_conv2d_i8", "ac_gemm_bf16", "ac_batched_gemm_f32",
+           "ac_status_string", "ac_version")
+
+_lib = None
+
+
+class AcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library, with argument types declared."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2505_18574_amd.build` "
+                "(or __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t, ctypes.c_float
+        L.ac_gemm_i8.restype = i32
+        L.ac_gemm_i8.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.ac_gemm_i8_workspace_bytes.restype = sz
+        L.ac_gemm_i8_workspace_bytes.argtypes = [i32, i32, i32]
+        L.ac_conv2d_i8.restype = i32
+        L.ac_conv2d_i8.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.ac_gemm_bf16.restype = i32
+        L.ac_gemm_bf16.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, f32, f32, vp]
+        L.ac_batched_gemm_f32.restype = i32
+        L.ac_batched_gemm_f32.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, vp]
+        L.ac_status_string.restype = ctypes.c_char_p
+        L.ac_status_string.argtypes = [i32]
+        L.ac_version.restype = i32
+        L.ac_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().ac_status_string(int(status)).decode()
+
+
+ac_status_string = status_string
+
+
+def ac_version() -> int:
+    return int(lib().ac_version())
+
+
+def ac_gemm_i8_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().ac_gemm_i8_workspace_bytes(M, N, K))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check2d(t, dtype, name):
+    if t.dtype != dtype or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or not t.is_cuda:
+        raise ValueError(f"{name}: expected a 2-D row-major device tensor of {dtype}")
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _ptr(workspace), workspace.numel() * workspace.element_size()
+
+
+def ac_gemm_i8(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, workspace=None, stream=None):
+    """C[M,N] int8 = stage(A[M,K] . B[K,N] + bias); bias is None, (N,) or (M,N) int32.  Returns C."""
+    _check2d(A, torch.int8, "A")
+    _check2d(B, torch.int8, "B")
+    _check2d(C, torch.int8, "C")
+    M, K = A.shape
+    N = B.shape[1]
+    if B.shape[0] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    bias_ld = 0
+    if bias is not None:
+        if bias.dtype != torch.int32 or not bias.is_cuda:
+            raise ValueError("bias: expected int32 device tensor")
+        if bias.dim() == 2:
+            if tuple(bias.shape) != (M, N) or bias.stride(1) != 1:
+                raise ValueError("bias matrix must be M x N row-major")
+            bias_ld = bias.stride(0)
+        elif tuple(bias.shape) != (N,) or (N > 1 and bias.stride(0) != 1):
+            raise ValueError("bias vector must have N contiguous entries")
+    wp, wb = _ws(workspace)
+    st = lib().ac_gemm_i8(_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(bias), bias_ld, _ptr(C), C.stride(0),
+                          M, N, K, shift, act, wp, wb, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_gemm_i8")
+    return C
+
+
+def ac_conv2d_i8(x, w, bias, out, stride: int, pad: int, shift: int, act: int = AC_ACT_NONE, workspace=None, stream=None):
+    """out[Nb,OH,OW,Cout] int8 = stage(conv(x[Nb,H,W,Cin], w[KH,KW,Cin,Cout]) + bias[Cout]).  Returns out."""
+    for t, name in ((x, "x"), (w, "w"), (out, "out")):
+        if t.dtype != torch.int8 or t.dim() != 4 or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError(f"{name}: expected a dense 4-D int8 device tensor")
+    Nb, H, W, Cin = x.shape
+    KH, KW, Cin2, Cout = w.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    if bias is not None and (bias.dtype != torch.int32 or tuple(bias.shape) != (Cout,) or not bias.is_contiguous()):
+        raise ValueError("bias: expected (Cout,) int32")
+    OH = (H + 2 * pad - KH) // stride + 1
+    OW = (W + 2 * pad - KW) // stride + 1
+    if tuple(out.shape) != (Nb, OH, OW, Cout):
+        raise ValueError(f"out: expected shape {(Nb, OH, OW, Cout)}")
+    wp, wb = _ws(workspace)
+    st = lib().ac_conv2d_i8(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), Nb, H, W, Cin, Cout, KH, KW, stride, pad,
+                            shift, act, wp, wb, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_conv2d_i8")
+    return out
+
+
+def ac_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, stream=None):
+    """C[M,N] fp32 = alpha * A[M,K] . B[K,N] + beta * C; A, B are bf16 (torch.bfloat16, or int16/uint16 bit patterns)."""
+    ok = (torch.bfloat16, torch.int16, torch.uint16)
+    for t, name in ((A, "A"), (B, "B")):
+        if t.dtype not in ok or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or not t.is_cuda:
+            raise ValueError(f"{name}: expected a 2-D row-major bf16 device tensor")
+    _check2d(C, torch.float32, "C")
+    M, K = A.shape
+    N = B.shape[1]
+    if B.shape[0] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    st = lib().ac_gemm_bf16(_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(C), C.stride(0), M, N, K,
+                            float(alpha), float(beta), _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_gemm_bf16")
+    return C
+
+
+def ac_batched_gemm_f32(A, B, C=None, x=None, d=None, y=None, stream=None):
+    """Per item: C = A . B (n x n), y = C . x + d.  A, B, C: [batch,n,n]; x, d, y: [batch,n]; fp32 dense."""
+    for t, name in ((A, "A"), (B, "B"), (C, "C"), (x, "x"), (d, "d"), (y, "y")):
+        if t is not None and (t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda):
+            raise ValueError(f"{name}: expected a dense fp32 device tensor")
+    batch, n, n2 = A.shape
+    if n != n2 or tuple(B.shape) != (batch, n, n):
+        raise ValueError("A, B must be [batch, n, n]")
+    if C is not None and tuple(C.shape) != (batch, n, n):
+        raise ValueError("C must be [batch, n, n]")
+    for t, name in ((x, "x"), (d, "d"), (y, "y")):
+        if t is not None and tuple(t.shape) != (batch, n):
+            raise ValueError(f"{name} must be [batch, n]")
+    st = lib().ac_batched_gemm_f32(_ptr(A), _ptr(B), _ptr(C), _ptr(x), _ptr(d), _ptr(y), n, batch, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_batched_gemm_f32")
+    return C, y

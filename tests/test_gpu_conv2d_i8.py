@@ -1,0 +1,65 @@
+"""GPU parity: ac_conv2d_i8 against the direct-definition oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import dev, host
+from paper_2505_18574_amd import inputs, ops
+
+pytestmark = pytest.mark.gpu
+
+
+def check(x, w, bias, stride, pad, shift, act):
+    Nb, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    OH = (H + 2 * pad - KH) // stride + 1
+    OW = (W + 2 * pad - KW) // stride + 1
+    out = torch.full((Nb, OH, OW, Cout), 99, dtype=torch.int8, device="cuda")
+    ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, stride, pad, shift, act)
+    torch.cuda.synchronize()
+    want = oracle.conv2d_i8(x, w, bias, stride, pad, shift, act)
+    np.testing.assert_array_equal(host(out), want)
+
+
+@pytest.mark.parametrize("case", inputs.CONV_I8, ids=lambda c: c.name)
+def test_workload_configs(case):
+    x, w, bias = inputs.conv_i8_case_inputs(case)
+    check(x, w, bias, case.stride, case.pad, case.shift, case.act)
+
+
+@pytest.mark.parametrize("Nb,H,W,Cin,Cout,KH,KW,stride,pad", [
+    (1, 5, 5, 16, 16, 3, 3, 1, 1),      # one tile
+    (2, 9, 7, 16, 32, 3, 3, 2, 1),      # stride 2, odd image
+    (3, 12, 12, 32, 48, 3, 3, 1, 0),    # no padding
+    (1, 8, 8, 3, 8, 3, 3, 1, 1),        # Cin not a multiple of 16: element-wise gather path
+    (2, 10, 6, 5, 7, 3, 2, 2, 1),       # nothing aligned, KH != KW
+    (2, 14, 14, 64, 64, 1, 1, 1, 0),    # 1x1: a plain GEMM over pixels
+    (1, 6, 6, 16, 16, 5, 5, 1, 2),      # 5x5
+    (1, 4, 4, 16, 16, 4, 4, 1, 0),      # kernel as large as the image: one output pixel
+    (1, 3, 3, 16, 16, 5, 5, 1, 1),      # kernel larger than the image, fits only through padding
+    (4, 30, 30, 48, 80, 3, 3, 1, 1),    # many tiles, ragged in M and N
+    (2, 17, 23, 16, 272, 3, 3, 3, 2),   # stride 3, pad 2
+])
+def test_shapes(Nb, H, W, Cin, Cout, KH, KW, stride, pad):
+    x, w, bias = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=H * W + Cin)
+    check(x, w, bias, stride, pad, 8, 1)
+    check(x, w, None, stride, pad, 5, 0)
+
+
+def test_small_magnitudes():
+    x, w, bias = inputs.conv_i8_inputs(2, 9, 9, 16, 32, 3, 3, seed=1, lo=-3, hi=3, bias_bits=4)
+    for shift in (0, 1, 2, 3):
+        check(x, w, bias, 1, 1, shift, 0)
+
+
+def test_empty_and_errors():
+    L = ops.lib()
+    a = torch.zeros(4096, dtype=torch.int8, device="cuda").data_ptr()
+    # batch of zero images: accepted, no launch
+    assert L.ac_conv2d_i8(a, a + 1024, None, a + 2048, 0, 5, 5, 16, 16, 3, 3, 1, 1, 8, 1, None, 0, None) == 0
+    assert L.ac_conv2d_i8(a, a + 1024, None, a + 2048, 1, 5, 5, 16, 16, 9, 3, 1, 1, 8, 1, None, 0, None) == ops.AC_ERR_SHAPE
+    assert L.ac_conv2d_i8(a, a + 1024, None, a + 2048, 1, 5, 5, 16, 16, 3, 3, 0, 1, 8, 1, None, 0, None) == ops.AC_ERR_SHAPE
+    assert L.ac_conv2d_i8(a, a + 1024, None, a, 1, 5, 5, 16, 16, 3, 3, 1, 1, 8, 1, None, 0, None) == ops.AC_ERR_ALIAS
+    assert L.ac_conv2d_i8(None, a + 1024, None, a + 2048, 1, 5, 5, 16, 16, 3, 3, 1, 1, 8, 1, None, 0, None) == ops.AC_ERR_NULL
+    assert L.ac_conv2d_i8(a, a + 1024, None, a + 2048, 1, 5, 5, 16, 16, 3, 3, 1, 1, 40, 1, None, 0, None) == ops.AC_ERR_SHIFT

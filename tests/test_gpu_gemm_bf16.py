@@ -1,0 +1,128 @@
+"""GPU parity: ac_gemm_bf16 against the fp64 oracle.
+
+Tolerances.  The target is a relative Frobenius error <= 1e-3 against the fp64 result on the
+bf16-rounded inputs.  bf16 products are exact in fp32 (8 + 8 significant bits), so the only error is
+fp32 accumulation: each of the K additions contributes at most 2^-24 relative to the running sum,
+giving |err| <= K * 2^-24 * sum_k |a_k b_k| per element; the element-wise check uses 4x that bound so
+a single wrong tile cannot hide inside the norm."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import dev, host, rel_fro
+from paper_2505_18574_amd import inputs, ops
+
+pytestmark = pytest.mark.gpu
+REL_FRO_TOL = 1e-3
+
+
+def run_gpu(A, B, alpha=1.0, beta=0.0, C_in=None):
+    M, K = A.shape
+    N = B.shape[1]
+    if C_in is None:
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")  # beta == 0 must not read C
+    else:
+        C = dev(C_in).clone()
+    ops.ac_gemm_bf16(dev(A), dev(B), C, alpha, beta)
+    torch.cuda.synchronize()
+    return host(C)
+
+
+def check_full(A, B, alpha=1.0, beta=0.0, C_in=None):
+    got = run_gpu(A, B, alpha, beta, C_in)
+    want = oracle.gemm_bf16(A, B, alpha, beta, C_in)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= REL_FRO_TOL
+    K = A.shape[1]
+    Aa = np.abs(inputs.bf16_bits_to_f32(A).astype(np.float64))
+    Ba = np.abs(inputs.bf16_bits_to_f32(B).astype(np.float64))
+    bound = 4.0 * (K + 2) * 2.0 ** -24 * (abs(alpha) * (Aa @ Ba) + (abs(beta) * np.abs(C_in) if C_in is not None else 0.0)) + 1e-30
+    assert (np.abs(got - want) <= bound).all()
+    return got
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (1, 1, 1), (5, 3, 7), (64, 64, 64), (70, 90, 50), (128, 128, 256), (130, 136, 264), (257, 300, 129),
+    (1792, 1792, 96), (1800, 1796, 100), (4096, 3072, 64), (4100, 3080, 40), (513, 48, 1000)])
+def test_shapes_full_oracle(M, N, K):
+    A, B = inputs.gemm_bf16_inputs(M, N, K, seed=M + N + K)
+    check_full(A, B)
+
+
+def test_alpha_beta():
+    A, B = inputs.gemm_bf16_inputs(200, 264, 136, seed=1)
+    Cin = np.random.default_rng(2).standard_normal((200, 264)).astype(np.float32)
+    check_full(A, B, alpha=0.5, beta=-1.25, C_in=Cin)
+    check_full(A, B, alpha=-2.0, beta=0.0)
+    got = run_gpu(A, B, alpha=0.0, beta=2.0, C_in=Cin)
+    np.testing.assert_array_equal(got, 2.0 * Cin)
+    # K == 0: C = beta * C
+    C = dev(Cin).clone()
+    assert ops.lib().ac_gemm_bf16(None, 0, None, 264, C.data_ptr(), 264, 200, 264, 0, 1.0, 0.5, None) == 0
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C), np.float32(0.5) * Cin)
+
+
+def test_bit_exact_cases():
+    rng = np.random.default_rng(3)
+    # small integers: every partial sum is exact in fp32, so any summation order must give the same bits
+    Ai = rng.integers(-8, 9, size=(192, 320)).astype(np.float32)
+    Bi = rng.integers(-8, 9, size=(320, 160)).astype(np.float32)
+    got = run_gpu(inputs.f32_to_bf16_bits(Ai), inputs.f32_to_bf16_bits(Bi))
+    np.testing.assert_array_equal(got, (Ai.astype(np.float64) @ Bi.astype(np.float64)).astype(np.float32))
+    # K == 1: a product of two bf16 values is exact in fp32
+    a, b = inputs.gemm_bf16_inputs(150, 170, 1, seed=4)
+    np.testing.assert_array_equal(run_gpu(a, b), oracle.gemm_bf16(a, b).astype(np.float32))
+    # identity
+    _, Bn = inputs.gemm_bf16_inputs(128, 200, 128, seed=5)
+    eye = inputs.f32_to_bf16_bits(np.eye(128, dtype=np.float32))
+    np.testing.assert_array_equal(run_gpu(eye, Bn), inputs.bf16_bits_to_f32(Bn))
+
+
+def test_strided_views_and_guard_bands():
+    M, N, K = 90, 70, 40
+    A, B = inputs.gemm_bf16_inputs(M, N, K, seed=6)
+    Abig = torch.zeros((M, K + 5), dtype=torch.bfloat16, device="cuda")
+    Bbig = torch.zeros((K, N + 3), dtype=torch.bfloat16, device="cuda")
+    Cbig = torch.full((M + 2, N + 6), 7.0, dtype=torch.float32, device="cuda")
+    Abig[:, 1:1 + K] = dev(A)
+    Bbig[:, 2:2 + N] = dev(B)
+    ops.ac_gemm_bf16(Abig[:, 1:1 + K], Bbig[:, 2:2 + N], Cbig[1:1 + M, 3:3 + N])
+    torch.cuda.synchronize()
+    out = host(Cbig)
+    assert rel_fro(out[1:1 + M, 3:3 + N], oracle.gemm_bf16(A, B)) <= REL_FRO_TOL
+    mask = np.ones_like(out, dtype=bool)
+    mask[1:1 + M, 3:3 + N] = False
+    assert (out[mask] == 7.0).all()
+
+
+@pytest.mark.parametrize("case", inputs.GEMM_BF16, ids=lambda c: c.name)
+def test_workload_configs_sampled(case):
+    """Full-size workloads as the benchmark launches them: sampled elements and whole rows against the
+    oracle, plus a whole-matrix property, C v == A (B v), evaluated in fp64."""
+    A, B = inputs.gemm_bf16_case_inputs(case)
+    got = run_gpu(A, B)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(0)
+    M, N, K = case.M, case.N, case.K
+    r = np.concatenate([rng.integers(0, M, 6000), [0, 0, M - 1, M - 1], np.repeat(rng.integers(0, M, 4), N)])
+    c = np.concatenate([rng.integers(0, N, 6000), [0, N - 1, 0, N - 1], np.tile(np.arange(N), 4)])
+    want, mag = oracle.gemm_bf16_at(A, B, r, c)
+    g = got[r, c].astype(np.float64)
+    assert rel_fro(g, want) <= REL_FRO_TOL
+    assert (np.abs(g - want) <= 4.0 * (K + 2) * 2.0 ** -24 * mag + 1e-30).all()
+    Ad = inputs.bf16_bits_to_f32(A).astype(np.float64)
+    Bd = inputs.bf16_bits_to_f32(B).astype(np.float64)
+    v = rng.standard_normal((N, 3))
+    assert rel_fro(got.astype(np.float64) @ v, Ad @ (Bd @ v)) <= 1e-4
+
+
+def test_argument_errors():
+    L = ops.lib()
+    a = torch.zeros(1024, dtype=torch.float32, device="cuda").data_ptr()
+    assert L.ac_gemm_bf16(a, 4, a + 64, 3, a + 128, 4, 4, 4, 4, 1.0, 0.0, None) == ops.AC_ERR_STRIDE
+    assert L.ac_gemm_bf16(a, 4, a + 64, 4, a, 4, 4, 4, 4, 1.0, 0.0, None) == ops.AC_ERR_ALIAS
+    assert L.ac_gemm_bf16(a, 4, a + 64, 4, None, 4, 4, 4, 4, 1.0, 0.0, None) == ops.AC_ERR_NULL
+    assert L.ac_gemm_bf16(a, 4, a + 64, 4, a + 128, 4, 4, -4, 4, 1.0, 0.0, None) == ops.AC_ERR_SHAPE
+    assert L.ac_gemm_bf16(a, 4, a + 64, 4, a + 128, 4, 0, 4, 4, 1.0, 0.0, None) == 0

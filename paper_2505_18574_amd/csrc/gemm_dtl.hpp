@@ -1,0 +1,405 @@
+// Fast-path tiled MFMA GEMM for gfx950: operands stream global -> LDS directly
+// (global_load_lds_dwordx4, no register staging, no ds_write), LDS tiles are
+// XOR-swizzled instead of padded, and the K loop is software-pipelined over a
+// ring of LDS stages with one workgroup barrier per K tile.
+//
+// Preconditions (checked by the host launcher; anything else takes the generic
+// kernel in gemm_mfma.hpp): all base pointers 16-byte aligned, row pitches of A
+// and B multiples of 16 bytes, K and N multiples of 16 bytes' worth of elements,
+// C suitably aligned for vector stores.  M, N, K need not be multiples of the
+// tile: out-of-range 16-byte chunks are fetched from a 16-byte block of zeros.
+//
+// LDS layouts (16-byte slots; a direct-to-LDS wave instruction fills 64
+// consecutive slots, the source address of each slot is free):
+//   A tile  [BM rows][KTB/16 slots]      slot' = slot ^ ((row / rows-per-256B) & (slots-1))
+//   B tile  [KTB/EB k-rows][BN*EB/16]    32-column segments XOR-ed with the k-row (BSwizzle)
+// chosen so that the ds_read_b128 of an A fragment (32 rows x 16 B) and the
+// transposing ds_read_b64_tr of a B fragment (4 or 8 k-rows x 64 or 32 B) touch
+// every LDS bank once.
+#pragma once
+#include "gemm_mfma.hpp"
+
+namespace ac {
+
+// 16 bytes of zeros in device memory: the source for chunks outside M, N, K and
+// for convolution taps that fall in the padding.
+__device__ __attribute__((aligned(16))) const int g_zero16[4] = {0, 0, 0, 0};
+
+// One direct-to-LDS wave instruction: lane i copies 16 bytes from gptr to
+// lds_base + 16*i.  Issued through inline assembly so that the compiler does not
+// serialise later LDS reads against it; ordering is enforced explicitly with
+// wait_vm<N>() + a barrier.
+static __device__ __forceinline__ void load_to_lds16(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+// Same, with the source given as a wave-uniform base pointer plus a 32-bit byte offset per lane.
+static __device__ __forceinline__ void load_to_lds16_so(const void* sbase, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+}
+template <int N>
+static __device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// B-tile swizzle.  A transposing read phase touches R k-rows (4 for bf16, 8 for int8) times one
+// SEGB-byte segment (64 / 32 bytes: 32 columns).  With RPW rows per 256-byte bank window, XOR-ing the
+// segment index with (row / RPW) & MASK spreads those R segments over all 64 banks.
+template <int EB, int B_ROW>
+struct BSwizzle {
+  static constexpr int R = EB == 2 ? 4 : 8;
+  static constexpr int SEGB = EB == 2 ? 64 : 32;
+  static constexpr int SEG_SHIFT = EB == 2 ? 6 : 5;
+  static constexpr int SEGS = B_ROW / SEGB;
+  static constexpr int RPW = B_ROW >= 256 ? 1 : 256 / B_ROW;
+  static constexpr int SPAN = R / RPW < SEGS ? R / RPW : SEGS;
+  static constexpr int MASK = SPAN - 1;
+  static_assert(SEGS >= 1 && (SEGS & (SEGS - 1)) == 0 && SPAN >= 1, "B tile width must be a power of two of 32-column segments");
+  static __device__ __forceinline__ int seg_xor(int row) { return (row / RPW) & MASK; }
+  // logical 16-byte slot held by physical slot `pslot` of k-row `row` (an involution)
+  static __device__ __forceinline__ int slot(int pslot, int row) { return pslot ^ (seg_xor(row) << (SEG_SHIFT - 4)); }
+};
+
+// Swizzled B-fragment reads (see TypeI8/TypeBF16::read_col for the lane roles).
+// kb: byte offset of this lane's 16 K-bytes inside the 128-byte K tile; seg: index of the 32-column block.
+template <int B_ROW>
+static __device__ __forceinline__ v4i dtl_read_col_bf16(const unsigned char* Bs, int kb, int seg, int lane) {
+  using S = BSwizzle<2, B_ROW>;
+  const int i = lane & 15, g1 = (lane >> 4) & 1;
+  const int r = (kb >> 1) + (i >> 2);  // k-row; rows r and r + 4 share one swizzle term
+  const unsigned char* p = Bs + r * B_ROW + ((seg ^ S::seg_xor(r)) << 6) + g1 * 32 + 8 * (i & 3);
+  v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(AC_LDS(v4s, p));
+  v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(AC_LDS(v4s, p + 4 * B_ROW));
+  v2i l2 = __builtin_bit_cast(v2i, lo), h2 = __builtin_bit_cast(v2i, hi);
+  return (v4i){l2[0], l2[1], h2[0], h2[1]};
+}
+template <int B_ROW>
+static __device__ __forceinline__ v4i dtl_read_col_i8(const unsigned char* Bs, int kb, int seg, int lane) {
+  using S = BSwizzle<1, B_ROW>;
+  const int i = lane & 15, g1 = (lane >> 4) & 1;
+  const int r = kb + (i >> 1);  // k-row; rows r and r + 8 share one swizzle term
+  const unsigned char* p = Bs + r * B_ROW + ((seg ^ S::seg_xor(r)) << 5) + g1 * 16 + 8 * (i & 1);
+  v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(AC_LDS(v2i, p));
+  v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(AC_LDS(v2i, p + 8 * B_ROW));
+  return (v4i){lo[0], lo[1], hi[0], hi[1]};
+}
+template <class T, int B_ROW>
+static __device__ __forceinline__ v4i dtl_read_col(const unsigned char* Bs, int kb, int seg, int lane) {
+  if constexpr (T::EB == 2) return dtl_read_col_bf16<B_ROW>(Bs, kb, seg, lane);
+  else return dtl_read_col_i8<B_ROW>(Bs, kb, seg, lane);
+}
+
+template <class T, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int KTB_>
+struct DtlGeometry {
+  static constexpr int EB = T::EB;
+  static constexpr int KTB = KTB_;                // K bytes per A row per tile (64 or 128)
+  static constexpr int BK = KTB / EB;             // K elements per tile == k-rows of the B tile
+  static constexpr int KSTEPS = KTB / 32;         // MFMA K-steps per tile (32 bytes of K each)
+  static constexpr int WAVES = WAVES_M * WAVES_N;
+  static constexpr int THREADS = 64 * WAVES;
+  static constexpr int A_BYTES = BM * KTB;
+  static constexpr int A_SPR = KTB / 16;          // slots per A row
+  static constexpr int A_RPW = 256 / KTB;         // A rows per 256-byte bank window
+  static constexpr int A_ROWS_PER_INSTR = 64 / A_SPR;
+  static constexpr int B_ROW = BN * EB;           // bytes per k-row of the B tile
+  static constexpr int B_SPR = B_ROW / 16;        // slots per k-row
+  static constexpr int B_BYTES = BK * B_ROW;
+  static constexpr int STAGE = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = STAGES * STAGE;
+  static constexpr int A_INSTR = A_BYTES / 1024 / WAVES;  // direct-to-LDS instructions per wave per tile
+  static constexpr int B_INSTR = B_BYTES / 1024 / WAVES;
+  static constexpr int B_ROWS_PER_INSTR = 64 / B_SPR;
+  static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  static constexpr int TM = WTM / 32, TN = WTN / 32;
+  static_assert(KTB == 64 || KTB == 128, "K tile is 64 or 128 bytes");
+  static_assert(A_BYTES % (1024 * WAVES) == 0 && B_BYTES % (1024 * WAVES) == 0, "tile must split into whole wave loads");
+  static_assert(B_SPR <= 64 && 64 % B_SPR == 0, "B row must divide a wave load");
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+  // swizzle term of an A row: rows that share a 256-byte bank window get the same term
+  static __device__ __forceinline__ int a_xor(int row) { return (row / A_RPW) & (A_SPR - 1); }
+};
+
+template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, int STAGES, int KTB_, bool PINGPONG>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const GemmParams p, const int tiles_m, const int tiles_n) {
+  using G = DtlGeometry<T, BM, BN, WAVES_M, WAVES_N, STAGES, KTB_>;
+  constexpr int EB = G::EB;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const unsigned lds0 = (unsigned)(uintptr_t)AC_LDS(unsigned char, smem);
+
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  int tm, tn;
+  tile_coords(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int kbytes = p.K * EB, nbytes = p.N * EB;
+  const unsigned char* zero = (const unsigned char*)g_zero16;
+
+  // ---- per-lane source addressing of the direct-to-LDS loads -------------------------------------------
+  // A: wave instruction j (j = wave * A_INSTR + i) fills A_ROWS_PER_INSTR tile rows; lane l -> row
+  // j * A_ROWS_PER_INSTR + l / A_SPR, physical slot l % A_SPR, holding logical chunk (l % A_SPR) ^ a_xor(row).
+  // The XOR term takes NVAR distinct values per lane as j varies (2 for 128-byte rows, 1 for 64-byte rows).
+  // B: wave instruction j fills B_ROWS_PER_INSTR k-rows; lane l -> row j * B_ROWS_PER_INSTR + l / B_SPR,
+  // physical slot l % B_SPR.
+  constexpr int NVAR = G::KTB == 128 ? 2 : 1;
+  int a_chunk[NVAR];
+#pragma unroll
+  for (int v = 0; v < NVAR; v++) a_chunk[v] = (lane % G::A_SPR) ^ G::a_xor(v * G::A_ROWS_PER_INSTR + lane / G::A_SPR);
+
+  // GEMM (AMODE 0): a wave-uniform base pointer per operand that advances by one K tile per issue, plus a
+  // constant 32-bit byte offset per lane and instruction.  Rows beyond M and columns beyond N are clamped
+  // to valid ones (their products land in accumulators that are never stored); only a partial last K tile
+  // needs zeros and takes the slower per-lane pointer path.
+  unsigned a_voff[G::A_INSTR], b_voff[G::B_INSTR];
+  int b_krow[G::B_INSTR];
+  ARow<1> a_pix[G::A_INSTR];  // AMODE 1: output pixel of the row
+#pragma unroll
+  for (int i = 0; i < G::A_INSTR; i++) {
+    const int row = (wave * G::A_INSTR + i) * G::A_ROWS_PER_INSTR + lane / G::A_SPR;
+    const int v = (wave * G::A_INSTR + i) & (NVAR - 1);
+    if constexpr (AMODE == 0) {
+      const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
+      a_voff[i] = (unsigned)rclamp * (unsigned)(p.lda * EB) + a_chunk[v] * 16;
+    } else {
+      a_pix[i].init(p, m0 + row, EB);
+      a_voff[i] = 0;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < G::B_INSTR; i++) {
+    const int row = (wave * G::B_INSTR + i) * G::B_ROWS_PER_INSTR + lane / G::B_SPR;
+    const int ls = BSwizzle<EB, G::B_ROW>::slot(lane % G::B_SPR, row);
+    b_krow[i] = row;
+    b_voff[i] = (unsigned)row * (unsigned)(p.ldb * EB) + (n0 * EB + ls * 16 < nbytes ? ls * 16 : 0);
+  }
+  const unsigned char* a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda * EB : 0);  // tile kt: + kt * KTB
+  const unsigned char* b_base = (const unsigned char*)p.B + (int64_t)n0 * EB;                              // tile kt: + kt * BK rows
+  const int64_t b_step = (int64_t)G::BK * p.ldb * EB;
+
+  // convolution: (kh, kw, ci) of this lane's possible chunks, advanced by KTB bytes of K per tile
+  int c_kh[NVAR], c_kw[NVAR], c_ci[NVAR];
+#pragma unroll
+  for (int v = 0; v < NVAR; v++) {
+    c_kh[v] = c_kw[v] = c_ci[v] = 0;
+    if constexpr (AMODE == 1) {
+      int kb = a_chunk[v] * 16;
+      int tap = kb / p.Cin;
+      c_ci[v] = kb - tap * p.Cin;
+      c_kh[v] = tap / p.KW;
+      c_kw[v] = tap - c_kh[v] * p.KW;
+    }
+  }
+
+  // Tiles are issued strictly in order 0, 1, 2, ...: the running bases and tap decode rely on it.
+  auto issue_loads = [&](int kt, int buf) {
+    const unsigned As = lds0 + buf * G::STAGE;
+    const unsigned Bs = As + G::A_BYTES;
+    const int kbase = kt * G::KTB;
+    const bool full = kbase + G::KTB <= kbytes;  // wave-uniform
+    if (AMODE == 0 && full) {
+#pragma unroll
+      for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], As + (wave * G::A_INSTR + i) * 1024);
+#pragma unroll
+      for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], Bs + (wave * G::B_INSTR + i) * 1024);
+    } else {
+#pragma unroll
+      for (int i = 0; i < G::A_INSTR; i++) {
+        const int v = (wave * G::A_INSTR + i) & (NVAR - 1);
+        const int kb = kbase + a_chunk[v] * 16;
+        const unsigned char* src = zero;
+        if constexpr (AMODE == 0) {
+          if (kb < kbytes) src = a_base + a_voff[i];
+        } else {
+          const ARow<1>& r = a_pix[i];
+          const int ih = r.ih0 + c_kh[v], iw = r.iw0 + c_kw[v];
+          if (r.ok && kb < kbytes && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
+            src = (const unsigned char*)p.A + r.base + (c_kh[v] * p.W + c_kw[v]) * p.Cin + c_ci[v];
+        }
+        load_to_lds16(src, As + (wave * G::A_INSTR + i) * 1024);
+      }
+#pragma unroll
+      for (int i = 0; i < G::B_INSTR; i++) {
+        const int k = kt * G::BK + b_krow[i];
+        const unsigned char* src = zero;
+        if (k < p.K && (AMODE == 0 || n0 * EB + (int)(b_voff[i] - (unsigned)b_krow[i] * (unsigned)(p.ldb * EB)) < nbytes)) src = b_base + b_voff[i];
+        load_to_lds16(src, Bs + (wave * G::B_INSTR + i) * 1024);
+      }
+    }
+    a_base += G::KTB;
+    b_base += b_step;
+    if constexpr (AMODE == 1) {  // advance the tap decode by one K tile
+#pragma unroll
+      for (int v = 0; v < NVAR; v++) {
+        c_ci[v] += G::KTB;
+        while (c_ci[v] >= p.Cin) {
+          c_ci[v] -= p.Cin;
+          if (++c_kw[v] == p.KW) {
+            c_kw[v] = 0;
+            ++c_kh[v];
+          }
+        }
+      }
+    }
+  };
+
+  typename T::accv acc[G::TM][G::TN];
+#pragma unroll
+  for (int i = 0; i < G::TM; i++)
+#pragma unroll
+    for (int j = 0; j < G::TN; j++) acc[i][j] = T::zero();
+
+  // ---- fragments ---------------------------------------------------------------------------------------
+  // the lane's A row within a 32-row MFMA tile is lane & 31; tile origins are multiples of 32 rows and do
+  // not change the swizzle term
+  const int a_swz = G::a_xor(lane & 31);
+  const int a_lane_off = (wm * G::WTM + (lane & 31)) * G::KTB;
+  struct Frag {
+    v4i a[G::TM], b[G::TN];
+  };
+  auto read_frags = [&](int buf, int ks, Frag& f) {
+    const unsigned char* As = smem + buf * G::STAGE;
+    const unsigned char* Bs = As + G::A_BYTES;
+    const int chunk = 2 * ks + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < G::TM; i++) f.a[i] = *(const v4i*)(As + a_lane_off + i * 32 * G::KTB + ((chunk ^ a_swz) << 4));
+#pragma unroll
+    for (int j = 0; j < G::TN; j++) f.b[j] = dtl_read_col<T, G::B_ROW>(Bs, chunk * 16, wn * G::TN + j, lane);
+  };
+  auto mfma_rows = [&](const Frag& f, int i0, int i1) {  // MFMA row tiles i0 .. i1-1 of one K-step
+#pragma unroll
+    for (int i = i0; i < i1; i++)
+#pragma unroll
+      for (int j = 0; j < G::TN; j++) acc[i][j] = T::mfma(f.b[j], f.a[i], acc[i][j]);
+  };
+
+  // ---- main loop ---------------------------------------------------------------------------------------
+  const int nkt = (kbytes + G::KTB - 1) / G::KTB;
+  constexpr int PER_TILE = G::A_INSTR + G::B_INSTR;  // outstanding vector-memory ops per tile per wave
+  static_assert((STAGES - 1) * PER_TILE <= 63, "vmcnt is a 6-bit counter");
+  if constexpr (PINGPONG) {
+    // ---- ping-pong main loop ---------------------------------------------------------------------------
+    // Eight waves, two per SIMD, in two groups of four (one wave of each group on every SIMD).  A wave
+    // alternates between a memory phase (issue its share of the direct-to-LDS loads for a later tile, read
+    // all fragments of the current tile into registers) and a compute phase (all MFMAs of that tile), with a
+    // workgroup barrier after each phase.  Group 1 is held back by one phase, so at any time one wave per
+    // SIMD is feeding the matrix pipe while the other fetches:
+    //   phase 2t   : group 0 reads tile t      | group 1 computes tile t-1
+    //   phase 2t+1 : group 0 computes tile t   | group 1 reads tile t
+    // Tile t sits in stage t % STAGES.  In its memory phase of tile t a wave issues the loads of tile
+    // t + STAGES - 1 (into the stage of tile t - 1, whose last reader finished one phase earlier) and waits
+    // until its own loads of tile t + 1 have landed; the barrier that ends phase 2t+1 therefore publishes tile
+    // t + 1 completely before phase 2t+2 reads it.
+    static_assert(!PINGPONG || G::WAVES == 8, "ping-pong needs two waves per SIMD");
+    static_assert(!PINGPONG || STAGES >= 3, "ping-pong needs at least three LDS stages");
+    const int grp = wave >> 2;
+    Frag fr[G::KSTEPS];
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; s++)
+      if (s < nkt) issue_loads(s, s);
+    if (STAGES - 2 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
+    else wait_vm<0>();
+    __syncthreads();                  // tile 0 is visible
+    if (grp == 1) __syncthreads();    // hold group 1 back by one phase
+    int buf = 0;
+    for (int kt = 0; kt < nkt; kt++) {
+      // memory phase
+      const int lbuf = buf == 0 ? STAGES - 1 : buf - 1;  // stage of tile kt - 1 == stage of tile kt + STAGES - 1
+      if (kt + STAGES - 1 < nkt) issue_loads(kt + STAGES - 1, lbuf);
+#pragma unroll
+      for (int ks = 0; ks < G::KSTEPS; ks++) read_frags(buf, ks, fr[ks]);
+      if (kt + STAGES - 1 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
+      else wait_vm<0>();
+      __syncthreads();
+      // compute phase
+      __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+      for (int ks = 0; ks < G::KSTEPS; ks++) mfma_rows(fr[ks], 0, G::TM);
+      __builtin_amdgcn_s_setprio(0);
+      __syncthreads();
+      buf = buf + 1 == STAGES ? 0 : buf + 1;
+    }
+    if (grp == 0) __syncthreads();    // every wave executes the same number of barriers
+  } else {
+  // Tile t lives in LDS stage t % STAGES.  The fragments of the next K-step are read while the MFMAs of the
+  // current one run (two register sets).  The one barrier per tile sits in the last K-step of tile kt, after
+  // this wave has read its last fragments of that tile: past it, tile kt + 1 is visible to everyone, and the
+  // stage of tile kt is free to receive tile kt + STAGES.
+  static_assert(G::KSTEPS % 2 == 0, "fragment double buffering assumes an even number of K-steps per tile");
+  Frag fr[2];
+#pragma unroll
+  for (int s = 0; s < STAGES; s++)
+    if (s < nkt) issue_loads(s, s);
+  if (nkt > 0) {
+    if (STAGES - 1 < nkt) wait_vm<(STAGES - 1) * PER_TILE>();
+    else wait_vm<0>();
+    __syncthreads();
+    read_frags(0, 0, fr[0]);
+  }
+  int buf = 0;
+  for (int kt = 0; kt + 1 < nkt; kt++) {  // every tile but the last: ends by handing over to tile kt + 1
+    const int nbuf = buf + 1 == STAGES ? 0 : buf + 1;
+#pragma unroll
+    for (int ks = 0; ks < G::KSTEPS; ks++) {
+      const Frag& cur = fr[ks & 1];
+      if (ks + 1 < G::KSTEPS) {
+        read_frags(buf, ks + 1, fr[(ks + 1) & 1]);
+        mfma_rows(cur, 0, G::TM);
+      } else {
+        // Half of this K-step's MFMAs are queued before the barrier (they keep the matrix pipe busy while
+        // the waves gather), the other half after the next tile's first fragments have been requested
+        // (they cover the LDS latency).  The scheduling fences keep the compiler from regrouping them.
+        mfma_rows(cur, 0, G::TM / 2);
+        __builtin_amdgcn_sched_barrier(0);
+        // tile kt + 1 must have landed: only the (STAGES - 2) younger tiles may still be in flight
+        if (kt + STAGES - 1 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
+        else wait_vm<0>();
+        __syncthreads();
+        if (kt + STAGES < nkt) issue_loads(kt + STAGES, buf);
+        read_frags(nbuf, 0, fr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_rows(cur, G::TM / 2, G::TM);
+      }
+    }
+    buf = nbuf;
+  }
+  if (nkt > 0) {  // last tile
+#pragma unroll
+    for (int ks = 0; ks < G::KSTEPS; ks++) {
+      if (ks + 1 < G::KSTEPS) read_frags(buf, ks + 1, fr[(ks + 1) & 1]);
+      mfma_rows(fr[ks & 1], 0, G::TM);
+    }
+  }
+  }
+
+  // ---- epilogue (same register layout as the generic kernel) ----------------------------------------------
+#pragma unroll
+  for (int i = 0; i < G::TM; i++) {
+    const int m = m0 + wm * G::WTM + i * 32 + (lane & 31);
+#pragma unroll
+    for (int j = 0; j < G::TN; j++) {
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int n = n0 + wn * G::WTN + j * 32 + 8 * q + 4 * (lane >> 5);
+        decltype(acc[i][j][0] + 0) a4[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        EPI::template store4<true>(p, m, n, a4);
+      }
+    }
+  }
+}
+
+template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, int STAGES, int KTB_ = 128, bool PINGPONG = false>
+static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
+  using G = DtlGeometry<T, BM, BN, WAVES_M, WAVES_N, STAGES, KTB_>;
+  auto kern = gemm_dtl_kernel<T, EPI, BM, BN, WAVES_M, WAVES_N, AMODE, STAGES, KTB_, PINGPONG>;
+  static bool configured = false;
+  if (!configured && G::LDS_BYTES > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(G::THREADS), G::LDS_BYTES, stream, p, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+}  // namespace ac

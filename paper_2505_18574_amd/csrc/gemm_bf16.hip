@@ -28,6 +28,12 @@ hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream) {
         case 8: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 2, 2, 0, 6, 64>(p, stream);
         case 9: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 4, 2, 0, 4, 64>(p, stream);
         case 11: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 4, 2, 0, 4, 64, true>(p, stream);
+        case 13: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 4, 2, 0, 3, 64, true>(p, stream);
+        case 14: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 4, 2, 0, 3, 64, false>(p, stream);
+        case 15: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 2, 4, 0, 3, 64, true>(p, stream);
+        case 16: return launch_dtl<TypeBF16, EpilogueF32, 128, 256, 2, 4, 0, 3, 64, true>(p, stream);
+        case 17: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 2, 2, 0, 3, 64, false>(p, stream);
+        case 18: return launch_dtl<TypeBF16, EpilogueF32, 128, 128, 2, 2, 0, 4, 64, false>(p, stream);
         case 12: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 3, 64, true>(p, stream);
         case 0: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 2, 0, 2, 128>(p, stream);
         default: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);

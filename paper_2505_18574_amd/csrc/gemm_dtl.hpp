@@ -36,6 +36,11 @@ static __device__ __forceinline__ void load_to_lds16(const void* gptr, unsigned 
 static __device__ __forceinline__ void load_to_lds16_so(const void* sbase, unsigned voff, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
 }
+// Workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() would also drain every
+// outstanding global store, which would serialise one tile's epilogue with the next tile's main loop.
+static __device__ __forceinline__ void block_sync() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 template <int N>
 static __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -129,11 +134,17 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  int tm, tn;
-  tile_coords(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN;
   const int kbytes = p.K * EB, nbytes = p.N * EB;
   const unsigned char* zero = (const unsigned char*)g_zero16;
+  const int ntiles = tiles_m * tiles_n;
+
+  // Persistent workgroups: each takes output tiles blockIdx.x, blockIdx.x + gridDim.x, ...  The stores of one
+  // tile drain while the loads and MFMAs of the next are already running.  gridDim.x is a multiple of the
+  // number of XCDs (or equals ntiles), so a workgroup's tiles all map to its own XCD in tile_coords().
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+  int tm, tn;
+  tile_coords(tile, ntiles, tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
 
   // ---- per-lane source addressing of the direct-to-LDS loads -------------------------------------------
   // A: wave instruction j (j = wave * A_INSTR + i) fills A_ROWS_PER_INSTR tile rows; lane l -> row
@@ -298,8 +309,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
       if (s < nkt) issue_loads(s, s);
     if (STAGES - 2 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
     else wait_vm<0>();
-    __syncthreads();                  // tile 0 is visible
-    if (grp == 1) __syncthreads();    // hold group 1 back by one phase
+    block_sync();                  // tile 0 is visible
+    if (grp == 1) block_sync();    // hold group 1 back by one phase
     int buf = 0;
     for (int kt = 0; kt < nkt; kt++) {
       // memory phase
@@ -309,16 +320,16 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
       for (int ks = 0; ks < G::KSTEPS; ks++) read_frags(buf, ks, fr[ks]);
       if (kt + STAGES - 1 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
       else wait_vm<0>();
-      __syncthreads();
+      block_sync();
       // compute phase
       __builtin_amdgcn_s_setprio(1);
 #pragma unroll
       for (int ks = 0; ks < G::KSTEPS; ks++) mfma_rows(fr[ks], 0, G::TM);
       __builtin_amdgcn_s_setprio(0);
-      __syncthreads();
+      block_sync();
       buf = buf + 1 == STAGES ? 0 : buf + 1;
     }
-    if (grp == 0) __syncthreads();    // every wave executes the same number of barriers
+    if (grp == 0) block_sync();    // every wave executes the same number of barriers
   } else {
   // Tile t lives in LDS stage t % STAGES.  The fragments of the next K-step are read while the MFMAs of the
   // current one run (two register sets).  The one barrier per tile sits in the last K-step of tile kt, after
@@ -332,7 +343,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   if (nkt > 0) {
     if (STAGES - 1 < nkt) wait_vm<(STAGES - 1) * PER_TILE>();
     else wait_vm<0>();
-    __syncthreads();
+    block_sync();
     read_frags(0, 0, fr[0]);
   }
   int buf = 0;
@@ -353,7 +364,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
         // tile kt + 1 must have landed: only the (STAGES - 2) younger tiles may still be in flight
         if (kt + STAGES - 1 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
         else wait_vm<0>();
-        __syncthreads();
+        block_sync();
         if (kt + STAGES < nkt) issue_loads(kt + STAGES, buf);
         read_frags(nbuf, 0, fr[0]);
         __builtin_amdgcn_sched_barrier(0);
@@ -385,6 +396,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
       }
     }
   }
+  block_sync();  // all fragment reads of this tile are done before the next tile refills the LDS stages
+  }  // tile loop
 }
 
 template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, int STAGES, int KTB_ = 128, bool PINGPONG = false>
@@ -398,7 +411,19 @@ static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
     configured = true;
   }
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(G::THREADS), G::LDS_BYTES, stream, p, tiles_m, tiles_n);
+  const int ntiles = tiles_m * tiles_n;
+  // one persistent workgroup per LDS-limited slot of every compute unit
+  static int slots = 0;
+  if (slots == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    const int per_cu = (160 * 1024) / (G::LDS_BYTES > 0 ? G::LDS_BYTES : 1);
+    slots = cus * (per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu));
+    slots -= slots % 8;
+  }
+  const int grid = ntiles < slots ? ntiles : slots;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(G::THREADS), G::LDS_BYTES, stream, p, tiles_m, tiles_n);
   return hipGetLastError();
 }
 

@@ -8,6 +8,8 @@
 // stores are coalesced as well.
 #include "common.hpp"
 
+#include <stdlib.h>
+
 namespace ac {
 
 static __device__ __forceinline__ float quad_xor1(float v) {  // lane ^ 1 within a quad
@@ -131,17 +133,145 @@ __global__ void __launch_bounds__(256) batched_f32_kernel(const BatchedParams p)
   }
 }
 
+// ---- 12 x 12 streaming kernel -----------------------------------------------------------------------------
+// Each wavefront works alone (no workgroup barrier anywhere): it walks over groups of 4 consecutive items,
+// brings a group's A, B, x, d into its private LDS window with direct-to-LDS loads (two windows, the next
+// group is in flight while the current one is computed), and stores C and y straight from registers.
+// 16 lanes own one item: lane (bi, bj) holds rows 3bi..3bi+2 and columns 4bj..4bj+3 of C (bj == 3 idles in the
+// product but takes part in the quad reduction), so every store is a whole 16-byte chunk of a C row.
+#define AC_LDS3(T, p) ((__attribute__((address_space(3))) T*)(p))
+constexpr int B12_ITEM = 12 * 12 * 4;            // bytes of one matrix
+constexpr int B12_GROUP = 4;                     // items per wave step
+constexpr int B12_MAT = B12_GROUP * B12_ITEM;    // 2304 bytes of A (or B) per group
+constexpr int B12_VEC = B12_GROUP * 48;          // 192 bytes of x (or d) per group
+constexpr int B12_WIN = 2 * B12_MAT + 2 * B12_VEC + 128;  // one LDS window (5120 bytes)
+constexpr int B12_WAVES = 4;                     // waves per workgroup
+
+static __device__ __forceinline__ void b12_dma(const void* g, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory");
+}
+
+__global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const BatchedParams p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_b[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  unsigned char* win0 = lds_b + wave * 2 * B12_WIN;
+  const unsigned win0_addr = (unsigned)(uintptr_t)AC_LDS3(unsigned char, win0);
+  const int64_t ngroups = (p.batch + B12_GROUP - 1) / B12_GROUP;
+  const int64_t stride = (int64_t)gridDim.x * B12_WAVES;
+  const bool has_x = p.x != nullptr, has_d = p.d != nullptr;
+
+  auto issue = [&](int64_t g, int w) {  // group g -> window w
+    const unsigned base = win0_addr + w * B12_WIN;
+    const int64_t left = p.batch - g * B12_GROUP;
+    const int items = left < B12_GROUP ? (int)left : B12_GROUP;
+    const int mat_bytes = items * B12_ITEM, vec_bytes = items * 48;
+    const unsigned char* Ag = (const unsigned char*)p.A + g * B12_MAT;
+    const unsigned char* Bg = (const unsigned char*)p.B + g * B12_MAT;
+#pragma unroll
+    for (int j = 0; j < 3; j++) {
+      const int off = j * 1024 + lane * 16;
+      if (off < mat_bytes) {
+        b12_dma(Ag + off, base + j * 1024);
+        b12_dma(Bg + off, base + B12_MAT + j * 1024);
+      }
+    }
+    if (has_x && lane * 16 < vec_bytes) b12_dma((const unsigned char*)p.x + g * B12_VEC + lane * 16, base + 2 * B12_MAT);
+    if (has_d && lane * 16 < vec_bytes) b12_dma((const unsigned char*)p.d + g * B12_VEC + lane * 16, base + 2 * B12_MAT + B12_VEC);
+  };
+
+  const int it = lane >> 4, sub = lane & 15, bi = sub >> 2, bj = sub & 3;
+  const int cb = bj < 3 ? bj : 2;  // idle lanes shadow column block 2
+  int64_t g = (int64_t)blockIdx.x * B12_WAVES + wave;
+  int w = 0;
+  if (g < ngroups) issue(g, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  for (; g < ngroups; g += stride) {
+    const int64_t gn = g + stride;
+    if (gn < ngroups) issue(gn, w ^ 1);
+    const int64_t item = g * B12_GROUP + it;
+    if (item < p.batch) {
+      const unsigned char* Wn = win0 + w * B12_WIN;
+      const float* Ai = (const float*)(Wn + it * B12_ITEM) + 3 * bi * 12;
+      const float* Bi = (const float*)(Wn + B12_MAT + it * B12_ITEM) + 4 * cb;
+      v4f a[3][3];
+#pragma unroll
+      for (int i = 0; i < 3; i++)
+#pragma unroll
+        for (int q = 0; q < 3; q++) a[i][q] = *(const v4f*)(Ai + i * 12 + q * 4);
+      v4f c[3] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+      for (int k = 0; k < 12; k++) {
+        const v4f b = *(const v4f*)(Bi + k * 12);
+#pragma unroll
+        for (int i = 0; i < 3; i++) {
+          const float av = a[i][k >> 2][k & 3];
+#pragma unroll
+          for (int e = 0; e < 4; e++) c[i][e] = __builtin_fmaf(av, b[e], c[i][e]);
+        }
+      }
+      if (p.C && bj < 3) {
+        float* Cg = p.C + item * 144 + 3 * bi * 12 + 4 * bj;
+#pragma unroll
+        for (int i = 0; i < 3; i++) *(v4f*)(Cg + i * 12) = c[i];
+      }
+      if (has_x) {
+        const v4f xv = *(const v4f*)((const float*)(Wn + 2 * B12_MAT + it * 48) + 4 * cb);
+        float s[3];
+#pragma unroll
+        for (int i = 0; i < 3; i++) {
+          float t = 0.f;
+#pragma unroll
+          for (int e = 0; e < 4; e++) t = __builtin_fmaf(c[i][e], xv[e], t);
+          t = bj < 3 ? t : 0.f;
+          t += quad_xor1(t);
+          t += quad_xor2(t);
+          s[i] = t;
+        }
+        if (bj == 0) {
+          const float* dv = (const float*)(Wn + 2 * B12_MAT + B12_VEC + it * 48) + 3 * bi;
+          float* yg = p.y + item * 12 + 3 * bi;
+#pragma unroll
+          for (int i = 0; i < 3; i++) yg[i] = s[i] + (has_d ? dv[i] : 0.f);
+        }
+      }
+    }
+    // the next group's loads must have landed; every LDS read of this window has been consumed above
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    w ^= 1;
+  }
+}
+
 hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream) {
   auto al = [](const void* q) { return q == nullptr || ((uintptr_t)q & 15) == 0; };
   const bool vec = al(p.A) && al(p.B) && al(p.C) && al(p.x) && al(p.d);
   const int n = p.n;
   // items per workgroup: 32 for the 12 x 12 case (39 KB of LDS, 4 workgroups per CU), 16 otherwise
-  const int G = n == 12 ? 32 : 16;
+  static const int g12 = getenv("AC_BATCHED_G") ? atoi(getenv("AC_BATCHED_G")) : 32;
+  const int G = n == 12 ? g12 : 16;
   const size_t lds = (size_t)G * (2 * n * n + 2 * n) * sizeof(float);
   const int64_t blocks = (p.batch + G - 1) / G;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   dim3 grid((unsigned)blocks), block(256);
-  if (n == 12) {
+  static const int stream12 = getenv("AC_BATCHED_STREAM") ? atoi(getenv("AC_BATCHED_STREAM")) : 2;
+  if (n == 12 && vec && stream12) {
+    // 3 workgroups of 4 waves per CU (LDS: 40 KB each); persistent over groups of 4 items
+    static int cus = 0;
+    if (cus == 0) {
+      int dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    }
+    const int64_t ngroups = (p.batch + B12_GROUP - 1) / B12_GROUP;
+    int64_t wgs = (ngroups + B12_WAVES - 1) / B12_WAVES;
+    if (wgs > (int64_t)cus * stream12) wgs = (int64_t)cus * stream12;  // stream12 = workgroups per CU
+    hipLaunchKernelGGL(batched12_stream_kernel, dim3((unsigned)wgs), dim3(64 * B12_WAVES), B12_WAVES * 2 * B12_WIN, stream, p);
+  } else if (n == 12 && vec && G == 16) {
+    hipLaunchKernelGGL((batched_f32_kernel<12, 16, true>), grid, block, lds, stream, p);
+  } else if (n == 12 && vec && G == 64) {
+    static bool cfg = false;
+    if (!cfg) { (void)hipFuncSetAttribute((const void*)batched_f32_kernel<12, 64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); cfg = true; }
+    hipLaunchKernelGGL((batched_f32_kernel<12, 64, true>), grid, block, lds, stream, p);
+  } else if (n == 12) {
     if (vec) hipLaunchKernelGGL((batched_f32_kernel<12, 32, true>), grid, block, lds, stream, p);
     else hipLaunchKernelGGL((batched_f32_kernel<12, 32, false>), grid, block, lds, stream, p);
   } else {

@@ -247,6 +247,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch the pass eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-supplementary", action="store_true")
+    ap.add_argument("--copy-reference", type=int, default=0, metavar="MiB",
+                    help="only run a plain device-to-device copy of this many MiB five times (reference for scaling HBM counters)")
     ap.add_argument("--only", default=None, help="restrict the pass to workloads whose name contains this string (profiling aid)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -256,6 +258,15 @@ def main():
     ops.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
 
+    if args.copy_reference:
+        n = args.copy_reference << 20
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_reference_bytes": n, "launches": 5}))
+        return
     wl = make_workloads()
     if args.only:
         wl = [w for w in wl if args.only in w.name]

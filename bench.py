@@ -65,8 +65,10 @@ def make_workloads():
     for case in inputs.CONV_I8:
         x, w, bias = (dev(t) for t in inputs.conv_i8_case_inputs(case))
         out = torch.empty((case.Nb, case.OH, case.OW, case.Cout), dtype=torch.int8, device="cuda")
+        nbytes = ops.ac_gemm_i8_workspace_bytes(*case.gemm_mnk)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
         wl.append(Workload(case.name, "conv2d_i8", "i8", case.ops, case.bytes,
-                           lambda x=x, w=w, bias=bias, out=out, c=case: ops.ac_conv2d_i8(x, w, bias, out, c.stride, c.pad, c.shift, c.act),
+                           lambda x=x, w=w, bias=bias, out=out, c=case, ws=ws: ops.ac_conv2d_i8(x, w, bias, out, c.stride, c.pad, c.shift, c.act, workspace=ws),
                            "gemm_dtl_kernel<TypeI8,...,AMODE=1>"))
     for case in inputs.GEMM_BF16:
         A, B = (dev(t) for t in inputs.gemm_bf16_case_inputs(case))

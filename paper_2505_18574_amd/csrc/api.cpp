@@ -40,9 +40,8 @@ size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K) {
   if (M <= 0 || N <= 0 || K <= 0) return 0;
   const ac::I8Plan plan = ac::plan_gemm_i8(M, N, K, true);
   if (plan.splits <= 1) return 0;
-  const size_t tiles = (size_t)((M + plan.tile - 1) / plan.tile) * (size_t)((N + plan.tile - 1) / plan.tile);
-  // int32 partial sums for every slice, then one arrival counter per output tile
-  return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t) + tiles * sizeof(uint32_t);
+  // int32 partial sums of every K slice
+  return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t);
 }
 
 ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,

@@ -30,9 +30,9 @@ struct GemmParams {
   // convolution geometry (implicit GEMM: m -> (n, oh, ow), k -> (kh, kw, ci))
   int32_t H, W, Cin, KW, OH, OW, stride, pad;
   // split-K (int8): number of K slices and the int32 partial-sum workspace
-  int32_t splits;
-  int32_t* partial;     // [splits][M][N] int32 when splits > 1
-  uint32_t* counters;   // one arrival counter per output tile when splits > 1
+  int32_t splits;        // number of K slices (1 = no split)
+  int32_t kt_per_split;  // K tiles (of the launched kernel's tile depth) per slice
+  int32_t* partial;      // [splits][M][N] int32 partial sums when splits > 1
 };
 
 struct BatchedParams {
@@ -53,8 +53,10 @@ hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream);
 
 // Tile choice made by the int8 launcher for a shape; shared with the workspace query.
 struct I8Plan {
-  int tile;    // 64, 128 or 256 (square block tile)
-  int splits;  // K slices (1 = no split)
+  int bm, bn;        // block tile
+  int ktb;           // K bytes per tile of the kernel chosen for this block tile
+  int splits;        // K slices (1 = no split)
+  int kt_per_split;  // K tiles per slice
 };
 I8Plan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace);
 

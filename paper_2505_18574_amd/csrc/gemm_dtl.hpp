@@ -141,7 +141,12 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   // Persistent workgroups: each takes output tiles blockIdx.x, blockIdx.x + gridDim.x, ...  The stores of one
   // tile drain while the loads and MFMAs of the next are already running.  gridDim.x is a multiple of the
   // number of XCDs (or equals ntiles), so a workgroup's tiles all map to its own XCD in tile_coords().
-  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+  // With split-K (int8 only) a work item is (tile, K slice): slice s covers K tiles s * kt_per_split ...
+  const int nwork = ntiles * p.splits;
+  for (int work = blockIdx.x; work < nwork; work += gridDim.x) {
+  const int split = p.splits > 1 ? work / ntiles : 0;
+  const int tile = work - split * ntiles;
+  const int kt0 = split * p.kt_per_split;  // first K tile of this slice
   int tm, tn;
   tile_coords(tile, ntiles, tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
@@ -183,9 +188,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     b_krow[i] = row;
     b_voff[i] = (unsigned)row * (unsigned)(p.ldb * EB) + (n0 * EB + ls * 16 < nbytes ? ls * 16 : 0);
   }
-  const unsigned char* a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda * EB : 0);  // tile kt: + kt * KTB
-  const unsigned char* b_base = (const unsigned char*)p.B + (int64_t)n0 * EB;                              // tile kt: + kt * BK rows
   const int64_t b_step = (int64_t)G::BK * p.ldb * EB;
+  const unsigned char* a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda * EB : 0) + (int64_t)kt0 * G::KTB;
+  const unsigned char* b_base = (const unsigned char*)p.B + (int64_t)n0 * EB + kt0 * b_step;
 
   // convolution: (kh, kw, ci) of this lane's possible chunks, advanced by KTB bytes of K per tile
   int c_kh[NVAR], c_kw[NVAR], c_ci[NVAR];
@@ -193,7 +198,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   for (int v = 0; v < NVAR; v++) {
     c_kh[v] = c_kw[v] = c_ci[v] = 0;
     if constexpr (AMODE == 1) {
-      int kb = a_chunk[v] * 16;
+      int kb = kt0 * G::KTB + a_chunk[v] * 16;
       int tap = kb / p.Cin;
       c_ci[v] = kb - tap * p.Cin;
       c_kh[v] = tap / p.KW;
@@ -202,9 +207,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   }
 
   // Tiles are issued strictly in order 0, 1, 2, ...: the running bases and tap decode rely on it.
-  auto issue_loads = [&](int kt, int buf) {
+  auto issue_loads = [&](int kt_local, int buf) {
     const unsigned As = lds0 + buf * G::STAGE;
     const unsigned Bs = As + G::A_BYTES;
+    const int kt = kt0 + kt_local;
     const int kbase = kt * G::KTB;
     const bool full = kbase + G::KTB <= kbytes;  // wave-uniform
     if (AMODE == 0 && full) {
@@ -284,7 +290,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   };
 
   // ---- main loop ---------------------------------------------------------------------------------------
-  const int nkt = (kbytes + G::KTB - 1) / G::KTB;
+  const int nkt_total = (kbytes + G::KTB - 1) / G::KTB;
+  const int nkt = p.splits > 1 ? (nkt_total - kt0 < p.kt_per_split ? nkt_total - kt0 : p.kt_per_split) : nkt_total;
   constexpr int PER_TILE = G::A_INSTR + G::B_INSTR;  // outstanding vector-memory ops per tile per wave
   static_assert((STAGES - 1) * PER_TILE <= 63, "vmcnt is a 6-bit counter");
   if constexpr (PINGPONG) {
@@ -392,7 +399,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
       for (int q = 0; q < 4; q++) {
         const int n = n0 + wn * G::WTN + j * 32 + 8 * q + 4 * (lane >> 5);
         decltype(acc[i][j][0] + 0) a4[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        EPI::template store4<true>(p, m, n, a4);
+        EPI::template store4<true>(p, m, n, a4, split);
       }
     }
   }
@@ -422,7 +429,8 @@ static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
     slots = cus * (per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu));
     slots -= slots % 8;
   }
-  const int grid = ntiles < slots ? ntiles : slots;
+  const int nwork = ntiles * (p.splits > 1 ? p.splits : 1);
+  const int grid = nwork < slots ? nwork : slots;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(G::THREADS), G::LDS_BYTES, stream, p, tiles_m, tiles_n);
   return hipGetLastError();
 }

@@ -1,39 +1,84 @@
-// int8 GEMM with the accelerator output stage: tile selection and launch.
+// int8 GEMM / implicit-GEMM convolution with the accelerator output stage: tile selection, split-K and launch.
 #include "gemm_dtl.hpp"
+
+#include <stdlib.h>
 
 namespace ac {
 
-// Pick the square block tile for an M x N x K int8 problem.  The chip has 256
-// compute units; a launch wants at least that many workgroups, and a bigger
-// tile re-reads less of A and B.  Take the largest tile that still yields
-// enough workgroups, else the smallest.
+// Pick block tile and K split for an M x N x K int8 problem.  The chip has 256 compute units: a launch
+// wants at least that many workgroups, and a bigger tile re-reads less of A and B.  Take the largest tile
+// that still yields enough workgroups; when even the smallest tile leaves most CUs idle and K is deep, slice
+// K so that every slice becomes its own workgroup (needs the caller's workspace for the int32 partial sums).
 I8Plan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
-  (void)K;
-  (void)have_workspace;
-  auto tiles = [&](int t) { return (int64_t)((M + t - 1) / t) * ((N + t - 1) / t); };
+  auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
   I8Plan plan;
   plan.splits = 1;
-  if (tiles(256) >= 192) plan.tile = 256;
-  else if (tiles(128) >= 192) plan.tile = 128;
-  else plan.tile = 64;
+  plan.kt_per_split = 0;
+  plan.ktb = 128;
+  if (tiles(256, 256) >= 192) {
+    plan.bm = plan.bn = 256;
+    plan.ktb = 64;
+  } else if (tiles(128, 128) >= 192) {
+    plan.bm = plan.bn = 128;
+  } else if (N <= 64 && tiles(128, 64) >= 160 && !getenv("AC_I8_NO_128x64")) {
+    plan.bm = 128;
+    plan.bn = 64;
+  } else {
+    plan.bm = plan.bn = 64;
+    const int64_t t = tiles(64, 64);
+    const int nkt = (K + plan.ktb - 1) / plan.ktb;
+    if (have_workspace && t <= 64 && nkt >= 16) {  // the second (reduce) launch costs about 3 us: only worth it for deep K
+      int want = (int)((256 + t - 1) / t);             // slices needed to cover the CUs
+      int per = (nkt + want - 1) / want;               // K tiles per slice ...
+      if (per < 2) per = 2;                            // ... but at least two, so a slice amortises its fill
+      plan.kt_per_split = per;
+      plan.splits = (nkt + per - 1) / per;
+      if (plan.splits <= 1) {
+        plan.splits = 1;
+        plan.kt_per_split = 0;
+      }
+    }
+  }
   return plan;
 }
 
+// Output stage of a split-K launch: sum the K slices, then bias / shift / saturate / ReLU, 4 outputs per thread.
+__global__ void __launch_bounds__(256) splitk_reduce_i8_kernel(const GemmParams p) {
+  const int64_t quads_per_row = p.N / 4;  // split-K is only used on the fast path: N is a multiple of 16
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= (int64_t)p.M * quads_per_row) return;
+  const int m = (int)(q / quads_per_row);
+  const int n = (int)(q - (int64_t)m * quads_per_row) * 4;
+  v4i s = {0, 0, 0, 0};
+  for (int k = 0; k < p.splits; k++) s += *(const v4i*)(p.partial + ((int64_t)k * p.M + m) * p.N + n);
+  int a4[4] = {s[0], s[1], s[2], s[3]};
+  EpilogueI8::store4<true>(p, m, n, a4);
+}
+
 template <int AMODE>
-hipError_t dispatch_i8(const GemmParams& p, hipStream_t stream, bool aligned, bool fast) {
-  const I8Plan plan = plan_gemm_i8(p.M, p.N, p.K, p.partial != nullptr);
+hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast) {
+  const I8Plan plan = plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr);
+  p.splits = plan.splits;
+  p.kt_per_split = plan.kt_per_split;
   if (fast) {  // direct-to-LDS kernels
-    switch (plan.tile) {
-      case 256: return launch_dtl<TypeI8, EpilogueI8, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
-      case 128: return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 2, AMODE, 3, 128>(p, stream);
-      default: return launch_dtl<TypeI8, EpilogueI8, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
+    if (plan.splits > 1) {
+      hipError_t e = launch_dtl<TypeI8, EpiloguePartialI32, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
+      if (e != hipSuccess) return e;
+      const int64_t quads = (int64_t)p.M * (p.N / 4);
+      hipLaunchKernelGGL(splitk_reduce_i8_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, p);
+      return hipGetLastError();
     }
+    if (plan.bm == 256) return launch_dtl<TypeI8, EpilogueI8, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
+    if (plan.bm == 128 && plan.bn == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 2, AMODE, 3, 128>(p, stream);
+    if (plan.bm == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 64, 2, 2, AMODE, 4, 128>(p, stream);
+    return launch_dtl<TypeI8, EpilogueI8, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
   }
+  const int tile = plan.bm == 256 ? 256 : (plan.bm == 128 && plan.bn == 128 ? 128 : 64);
 #define AC_I8_CASE(TILE, WM, WN)                                                                         \
   case TILE:                                                                                             \
     return aligned ? launch_tile<TypeI8, EpilogueI8, TILE, TILE, WM, WN, AMODE, true>(p, stream)         \
                    : launch_tile<TypeI8, EpilogueI8, TILE, TILE, WM, WN, AMODE, false>(p, stream);
-  switch (plan.tile) {
+  switch (tile) {
     AC_I8_CASE(256, 2, 2)
     AC_I8_CASE(128, 2, 2)
     AC_I8_CASE(64, 2, 2)
@@ -44,11 +89,16 @@ hipError_t dispatch_i8(const GemmParams& p, hipStream_t stream, bool aligned, bo
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+// Fast (direct-to-LDS) path: 16-byte aligned operands and pitches, K and N in whole 16-byte chunks.
+bool gemm_i8_fast_path(const GemmParams& p) {
+  return aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) && (((uintptr_t)p.C & 3) == 0) &&
+         (p.ldc % 4 == 0) && (p.K % 16 == 0) && (p.N % 16 == 0);
+}
+
 hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream) {
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) &&
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
-  const bool fast = aligned && (p.K % 16 == 0) && (p.N % 16 == 0);
-  return dispatch_i8<0>(p, stream, aligned, fast);
+  return dispatch_i8<0>(p, stream, aligned, gemm_i8_fast_path(p));
 }
 
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream) {

@@ -117,7 +117,7 @@ struct EpilogueI8 {
     return q;
   }
   template <bool VEC>
-  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a) {
+  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
     int8_t* C = (int8_t*)p.C;
     int v[4];
@@ -140,10 +140,27 @@ struct EpilogueI8 {
   }
 };
 
+// Split-K partial sums: raw int32 accumulators of K slice `split` go to partial[split][M][N]; the output stage
+// runs in splitk_reduce_i8_kernel once every slice has been written.
+struct EpiloguePartialI32 {
+  template <bool VEC>
+  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a, int split) {
+    if (m >= p.M || n >= p.N) return;
+    int32_t* dst = p.partial + ((int64_t)split * p.M + m) * p.N + n;
+    if (VEC && n + 3 < p.N) {
+      *(v4i*)dst = (v4i){a[0], a[1], a[2], a[3]};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+        if (n + e < p.N) dst[e] = a[e];
+    }
+  }
+};
+
 // fp32 output: C = alpha * acc + beta * C (C read only when beta != 0).
 struct EpilogueF32 {
   template <bool VEC>
-  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a) {
+  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
     float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
     const bool full = n + 3 < p.N;

@@ -15,11 +15,18 @@ def check(x, w, bias, stride, pad, shift, act):
     KH, KW, _, Cout = w.shape
     OH = (H + 2 * pad - KH) // stride + 1
     OW = (W + 2 * pad - KW) // stride + 1
-    out = torch.full((Nb, OH, OW, Cout), 99, dtype=torch.int8, device="cuda")
-    ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, stride, pad, shift, act)
-    torch.cuda.synchronize()
     want = oracle.conv2d_i8(x, w, bias, stride, pad, shift, act)
-    np.testing.assert_array_equal(host(out), want)
+    for with_ws in (False, True):  # with a workspace the library may split the K range
+        out = torch.full((Nb, OH, OW, Cout), 99, dtype=torch.int8, device="cuda")
+        ws = None
+        if with_ws:
+            nbytes = ops.ac_gemm_i8_workspace_bytes(Nb * OH * OW, Cout, KH * KW * Cin)
+            if not nbytes:
+                continue
+            ws = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device="cuda")  # contents on entry are unspecified
+        ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, stride, pad, shift, act, workspace=ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(out), want)
 
 
 @pytest.mark.parametrize("case", inputs.CONV_I8, ids=lambda c: c.name)
@@ -40,6 +47,8 @@ def test_workload_configs(case):
     (1, 3, 3, 16, 16, 5, 5, 1, 1),      # kernel larger than the image, fits only through padding
     (4, 30, 30, 48, 80, 3, 3, 1, 1),    # many tiles, ragged in M and N
     (2, 17, 23, 16, 272, 3, 3, 3, 2),   # stride 3, pad 2
+    (1, 14, 14, 256, 64, 3, 3, 1, 1),   # few tiles, deep K: split-K when a workspace is given
+    (2, 7, 7, 512, 128, 3, 3, 1, 1),
 ])
 def test_shapes(Nb, H, W, Cin, Cout, KH, KW, stride, pad):
     x, w, bias = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=H * W + Cin)

@@ -18,7 +18,7 @@ def run_gpu(A, B, bias, shift, act, workspace=False):
     if workspace:
         nbytes = ops.ac_gemm_i8_workspace_bytes(M, N, K)
         if nbytes:
-            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            ws = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")  # contents on entry are unspecified
     ops.ac_gemm_i8(dev(A), dev(B), dev(bias), C, shift, act, workspace=ws)
     torch.cuda.synchronize()
     return host(C)
@@ -81,6 +81,17 @@ def test_bias_matrix_and_no_bias():
     A, B, bias = inputs.gemm_i8_inputs(150, 130, 90, seed=5, bias_matrix=True)
     check(A, B, bias, 8, 1)
     check(A, B, None, 8, 1)
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 64, 512), (100, 192, 4096), (49, 2048, 4608), (17, 16, 1040), (130, 80, 656)])
+def test_split_k_shapes(M, N, K):
+    """Few output tiles and a deep K: with a workspace the K range is sliced; results stay bit-exact."""
+    assert ops.ac_gemm_i8_workspace_bytes(M, N, K) > 0
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + K)
+    check(A, B, bias, 11, 1, workspace=True)
+    A, B, biasm = inputs.gemm_i8_inputs(M, N, K, seed=M + K + 1, bias_matrix=True)
+    check(A, B, biasm, 9, 0, workspace=True)
+    check(A, B, None, 9, 0, workspace=True)
 
 
 def test_k_zero_and_empty():

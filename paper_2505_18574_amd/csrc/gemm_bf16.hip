@@ -11,7 +11,9 @@ hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream) {
   // direct-to-LDS fast path: additionally K and N in whole 16-byte chunks
   const bool fast = aligned && (p.K % 8 == 0) && (p.N % 8 == 0);
   auto tiles = [&](int t) { return (int64_t)((p.M + t - 1) / t) * ((p.N + t - 1) / t); };
-  const int tile = tiles(256) >= 192 ? 256 : (tiles(128) >= 192 ? 128 : 64);
+  // a tile much larger than the problem wastes most of its MFMAs: require 3/4 of the tile edge in both dimensions
+  const bool ok256 = p.M >= 192 && p.N >= 192, ok128 = p.M >= 96 && p.N >= 96;
+  const int tile = (ok256 && tiles(256) >= 192) ? 256 : ((ok128 && tiles(128) >= 192) ? 128 : 64);
   if (fast) {
     // AC_BF16_VARIANT selects an alternative schedule of the large-tile kernel (a tuning aid; default 10:
     // eight waves in ping-pong over four 32 KB LDS stages)

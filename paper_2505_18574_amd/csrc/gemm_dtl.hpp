@@ -265,6 +265,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
 #pragma unroll
     for (int j = 0; j < G::TN; j++) acc[i][j] = T::zero();
 
+  // operands of the output stage that do not depend on the product (bias) are requested before the K loop
+  typename EPI::Pre pre[G::TN];
+#pragma unroll
+  for (int j = 0; j < G::TN; j++) EPI::prefetch(p, n0 + wn * G::WTN + j * 32, lane, pre[j]);
+
   // ---- fragments ---------------------------------------------------------------------------------------
   // the lane's A row within a 32-row MFMA tile is lane & 31; tile origins are multiples of 32 rows and do
   // not change the swizzle term
@@ -389,19 +394,12 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   }
   }
 
-  // ---- epilogue (same register layout as the generic kernel) ----------------------------------------------
+  // ---- epilogue: one call per 32x32 MFMA tile -----------------------------------------------------------
 #pragma unroll
   for (int i = 0; i < G::TM; i++) {
     const int m = m0 + wm * G::WTM + i * 32 + (lane & 31);
 #pragma unroll
-    for (int j = 0; j < G::TN; j++) {
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const int n = n0 + wn * G::WTN + j * 32 + 8 * q + 4 * (lane >> 5);
-        decltype(acc[i][j][0] + 0) a4[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        EPI::template store4<true>(p, m, n, a4, split);
-      }
-    }
+    for (int j = 0; j < G::TN; j++) EPI::tile(p, m, n0 + wn * G::WTN + j * 32, acc[i][j], lane, split, pre[j]);
   }
   block_sync();  // all fragment reads of this tile are done before the next tile refills the LDS stages
   }  // tile loop

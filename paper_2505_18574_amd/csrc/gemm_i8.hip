@@ -1,8 +1,6 @@
 // int8 GEMM / implicit-GEMM convolution with the accelerator output stage: tile selection, split-K and launch.
 #include "gemm_dtl.hpp"
 
-#include <stdlib.h>
-
 namespace ac {
 
 // Pick block tile and K split for an M x N x K int8 problem.  The chip has 256 compute units: a launch
@@ -15,14 +13,13 @@ I8Plan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   plan.splits = 1;
   plan.kt_per_split = 0;
   plan.ktb = 128;
-  if (tiles(256, 256) >= 192) {
+  // a tile much wider (taller) than the problem wastes most of its MFMAs: require 3/4 of the tile edge
+  const bool ok256 = M >= 192 && N >= 192, ok128 = M >= 96 && N >= 96;
+  if (ok256 && tiles(256, 256) >= 192) {
     plan.bm = plan.bn = 256;
     plan.ktb = 64;
-  } else if (tiles(128, 128) >= 192) {
+  } else if (ok128 && tiles(128, 128) >= 192) {
     plan.bm = plan.bn = 128;
-  } else if (N <= 64 && tiles(128, 64) >= 160 && !getenv("AC_I8_NO_128x64")) {
-    plan.bm = 128;
-    plan.bn = 64;
   } else {
     plan.bm = plan.bn = 64;
     const int64_t t = tiles(64, 64);
@@ -70,7 +67,6 @@ hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast
     }
     if (plan.bm == 256) return launch_dtl<TypeI8, EpilogueI8, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
     if (plan.bm == 128 && plan.bn == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 2, AMODE, 3, 128>(p, stream);
-    if (plan.bm == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 64, 2, 2, AMODE, 4, 128>(p, stream);
     return launch_dtl<TypeI8, EpilogueI8, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
   }
   const int tile = plan.bm == 256 ? 256 : (plan.bm == 128 && plan.bn == 128 ? 128 : 64);

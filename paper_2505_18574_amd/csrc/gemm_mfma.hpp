@@ -138,6 +138,61 @@ struct EpilogueI8 {
         if (n + e < p.N) dst[e] = (int8_t)v[e];
     }
   }
+
+  // ---- tile-level interface of the direct-to-LDS kernels ----------------------------------------------
+  // One 32x32 MFMA tile: lane l holds row m = row0 + l % 32 and, for q = 0..3, columns
+  // ncol0 + 8q + 4 (l / 32) + 0..3.
+  struct Pre {
+    v4i bias[4];  // bias of this lane's 16 columns (row-vector bias only), fetched before the K loop
+  };
+  static __device__ __forceinline__ void prefetch(const GemmParams& p, int ncol0, int lane, Pre& pre) {
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+      pre.bias[q] = (v4i){0, 0, 0, 0};
+      if (p.bias && p.bias_ld == 0 && n + 3 < p.N) {
+        if ((((uintptr_t)p.bias) & 15) == 0) pre.bias[q] = *(const v4i*)(p.bias + n);
+        else pre.bias[q] = (v4i){p.bias[n], p.bias[n + 1], p.bias[n + 2], p.bias[n + 3]};
+      }
+    }
+  }
+  template <class ACC>
+  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int, const Pre& pre) {
+    if (m >= p.M || ncol0 >= p.N) return;
+    int8_t* C = (int8_t*)p.C;
+    const bool wide = ncol0 + 32 <= p.N && (p.ldc & 15) == 0 && (((uintptr_t)C) & 15) == 0;
+    const bool row_bias = p.bias && p.bias_ld == 0;
+    if (wide) {
+      unsigned d[4];
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+        int v[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          int b = row_bias ? pre.bias[q][e] : 0;
+          if (p.bias && !row_bias) b = p.bias[(int64_t)m * p.bias_ld + n + e];
+          v[e] = requant(acc[4 * q + e] + b, p.shift, p.act);
+        }
+        d[q] = (unsigned)(v[0] & 0xff) | ((unsigned)(v[1] & 0xff) << 8) | ((unsigned)(v[2] & 0xff) << 16) | ((unsigned)(v[3] & 0xff) << 24);
+      }
+      // Lanes l and l + 32 hold interleaved 4-byte pieces of the same row.  Swapping the upper half of d[0]
+      // (d[1]) with the lower half of d[2] (d[3]) leaves 16 consecutive bytes in every lane: columns 0..15 in
+      // lanes 0..31, columns 16..31 in lanes 32..63, so a row leaves as two whole 16-byte stores.
+      typedef unsigned v2u __attribute__((ext_vector_type(2)));
+      const v2u s02 = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
+      const v2u s13 = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
+      const v4i o = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+      *(v4i*)(C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5)) = o;
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+        int a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        store4<true>(p, m, n, a4);
+      }
+    }
+  }
 };
 
 // Split-K partial sums: raw int32 accumulators of K slice `split` go to partial[split][M][N]; the output stage
@@ -153,6 +208,17 @@ struct EpiloguePartialI32 {
 #pragma unroll
       for (int e = 0; e < 4; e++)
         if (n + e < p.N) dst[e] = a[e];
+    }
+  }
+  struct Pre {};
+  static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
+  template <class ACC>
+  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+      decltype(acc[0] + 0) a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      store4<true>(p, m, n, a4, split);
     }
   }
 };
@@ -179,6 +245,17 @@ struct EpilogueF32 {
           if (p.beta != 0.f) o += p.beta * dst[e];
           dst[e] = o;
         }
+    }
+  }
+  struct Pre {};
+  static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
+  template <class ACC>
+  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+      decltype(acc[0] + 0) a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      store4<true>(p, m, n, a4, split);
     }
   }
 };

@@ -92,6 +92,16 @@ ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
 size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
 /*
+ * int8 GEMM with the raw accumulator as output: C32[i][j] = sum_k A[i][k] * B[k][j] + bias(i, j) in int32,
+ * with no scaling and no activation.  This is the accumulator-type read of the paper's accelerator
+ * (Appendix B, Fig. 14: bit 29 of an accumulator read address selects the full accumulator value and skips
+ * activation and scaling).  Operands and bias as for ac_gemm_i8; C is int32, M x N, row stride ldc >= N.
+ */
+ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                           const int32_t* bias, int64_t bias_ld, int32_t* C, int64_t ldc,
+                           int32_t M, int32_t N, int32_t K, void* stream);
+
+/*
  * int8 2-D convolution (the convolution workload of Section 5.1.2) computed
  * as an implicit GEMM with M = Nb*OH*OW, N = Cout, K = KH*KW*Cin, followed by
  * the same output stage as ac_gemm_i8:
@@ -152,6 +162,26 @@ ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_
 ac_status ac_batched_gemm_f32(const float* A, const float* B, float* C,
                               const float* x, const float* d, float* y,
                               int32_t n, int64_t batch, void* stream);
+
+/*
+ * Forward pass of the TinyMPC primal update (Appendix D.2), batched over independent problems that
+ * share the three model matrices:
+ *
+ *   u[i]   = -Kinf . x[i] - d[i]
+ *   x[i+1] =  Adyn . x[i] + Bdyn . u[i]          i = 0 .. horizon-1,  x[0] = x0
+ *
+ *   Adyn   device, fp32, [nx][nx]     Bdyn  device, fp32, [nx][nu]     Kinf  device, fp32, [nu][nx]
+ *   x0     device, fp32, [batch][nx]
+ *   d      device, fp32, [batch][horizon][nu]
+ *   u      device, fp32, [batch][horizon][nu]   (written)
+ *   x_out  device, fp32, [batch][horizon + 1][nx], or NULL: the state trajectory x[0..horizon]; when NULL the
+ *          state after the last control, which the paper notes is never used, is not computed
+ *   1 <= nx, nu <= 16 (the paper's problem has nx = 12, nu = 4, horizon = 5); horizon == 0 or batch == 0
+ *   return AC_OK without a launch.  Every sum is an fp32 fused multiply-add chain in ascending index order.
+ */
+ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const float* Kinf,
+                                 const float* x0, const float* d, float* u, float* x_out,
+                                 int32_t nx, int32_t nu, int32_t horizon, int64_t batch, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* ac_status_string(ac_status status);

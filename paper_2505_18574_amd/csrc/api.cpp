@@ -70,6 +70,23 @@ ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
   return ac::launch_gemm_i8(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }
 
+ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                           const int32_t* bias, int64_t bias_ld, int32_t* C, int64_t ldc,
+                           int32_t M, int32_t N, int32_t K, void* stream) {
+  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
+  if (bias_ld < 0 || (bias && bias_ld != 0 && bias_ld < N)) return AC_ERR_STRIDE;
+  if (M == 0 || N == 0) return AC_OK;
+  if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
+  if ((const void*)C == (const void*)A || (const void*)C == (const void*)B || (const void*)C == (const void*)bias) return AC_ERR_ALIAS;
+  ac::GemmParams p = {};
+  p.A = A; p.B = B; p.C = C; p.bias = bias;
+  p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.bias_ld = bias_ld;
+  p.M = M; p.N = N; p.K = K;
+  p.splits = 1;
+  return ac::launch_gemm_i8_acc32(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
 ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, int8_t* out,
                        int32_t Nb, int32_t H, int32_t W, int32_t Cin, int32_t Cout,
                        int32_t KH, int32_t KW, int32_t stride, int32_t pad,
@@ -136,6 +153,20 @@ ac_status ac_batched_gemm_f32(const float* A, const float* B, float* C,
 
   ac::BatchedParams p = {A, B, C, x, d, y, n, batch};
   return ac::launch_batched_f32(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
+ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const float* Kinf,
+                                 const float* x0, const float* d, float* u, float* x_out,
+                                 int32_t nx, int32_t nu, int32_t horizon, int64_t batch, void* stream) {
+  if (nx < 1 || nx > 16 || nu < 1 || nu > 16 || horizon < 0 || batch < 0) return AC_ERR_SHAPE;
+  if (batch == 0 || horizon == 0) return AC_OK;  // no control to compute
+  if (!Adyn || !Bdyn || !Kinf || !x0 || !d || !u) return AC_ERR_NULL;
+  const void* ins[5] = {Adyn, Bdyn, Kinf, x0, d};
+  for (const void* q : ins)
+    if ((const void*)u == q || (x_out && (const void*)x_out == q)) return AC_ERR_ALIAS;
+  if (x_out && (const void*)x_out == (const void*)u) return AC_ERR_ALIAS;
+  ac::TinyMpcParams p = {Adyn, Bdyn, Kinf, x0, d, u, x_out, nx, nu, horizon, batch};
+  return ac::launch_tinympc_forward(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }
 
 }  // extern "C"

@@ -46,7 +46,21 @@ struct BatchedParams {
   int64_t batch;
 };
 
+struct TinyMpcParams {
+  const float* Adyn;  // [nx][nx]
+  const float* Bdyn;  // [nx][nu]
+  const float* Kinf;  // [nu][nx]
+  const float* x0;    // [batch][nx]
+  const float* d;     // [batch][horizon][nu]
+  float* u;           // [batch][horizon][nu]
+  float* x_out;       // [batch][horizon + 1][nx] or null
+  int32_t nx, nu, horizon;
+  int64_t batch;
+};
+
+hipError_t launch_tinympc_forward(const TinyMpcParams& p, hipStream_t stream);
 hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream);
+hipError_t launch_gemm_i8_acc32(const GemmParams& p, hipStream_t stream);
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream);
 hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream);
 hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream);

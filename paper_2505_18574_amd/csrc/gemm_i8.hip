@@ -91,6 +91,23 @@ bool gemm_i8_fast_path(const GemmParams& p) {
          (p.ldc % 4 == 0) && (p.K % 16 == 0) && (p.N % 16 == 0);
 }
 
+// Raw int32 accumulator output: same kernels, epilogue without the output stage (no split-K).
+hipError_t launch_gemm_i8_acc32(const GemmParams& p0, hipStream_t stream) {
+  GemmParams p = p0;
+  p.splits = 1;
+  p.kt_per_split = 0;
+  const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) && aligned16(p.C) && (p.ldc % 4 == 0);
+  const bool fast = aligned && (p.K % 16 == 0) && (p.N % 16 == 0);
+  const I8Plan plan = plan_gemm_i8(p.M, p.N, p.K, false);
+  if (fast) {
+    if (plan.bm == 256) return launch_dtl<TypeI8, EpilogueRawI32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
+    if (plan.bm == 128) return launch_dtl<TypeI8, EpilogueRawI32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+    return launch_dtl<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
+  }
+  return aligned ? launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, true>(p, stream)
+                 : launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, false>(p, stream);
+}
+
 hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream) {
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) &&
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);

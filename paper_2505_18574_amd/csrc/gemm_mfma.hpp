@@ -223,6 +223,41 @@ struct EpiloguePartialI32 {
   }
 };
 
+// Raw accumulator output (the accumulator-type read of the paper's accelerator: no scaling, no activation):
+// C32[m][n] = acc + bias, int32, row stride ldc.
+struct EpilogueRawI32 {
+  template <bool VEC>
+  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a, int = 0) {
+    if (m >= p.M || n >= p.N) return;
+    int32_t* dst = (int32_t*)p.C + (int64_t)m * p.ldc + n;
+    int v[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      int b = 0;
+      if (p.bias && n + e < p.N) b = p.bias_ld == 0 ? p.bias[n + e] : p.bias[(int64_t)m * p.bias_ld + n + e];
+      v[e] = a[e] + b;
+    }
+    if (VEC && n + 3 < p.N) {
+      *(v4i*)dst = (v4i){v[0], v[1], v[2], v[3]};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+        if (n + e < p.N) dst[e] = v[e];
+    }
+  }
+  struct Pre {};
+  static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
+  template <class ACC>
+  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+      int a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      store4<true>(p, m, n, a4, split);
+    }
+  }
+};
+
 // fp32 output: C = alpha * acc + beta * C (C read only when beta != 0).
 struct EpilogueF32 {
   template <bool VEC>

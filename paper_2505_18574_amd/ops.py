@@ -23,6 +23,7 @@ AC_ACT_NONE, AC_ACT_RELU = 0, 1
 
 # every symbol include/ac.h declares
 EXPORTS = ("ac_gemm_i8", "ac_gemm_i8_workspace_bytes", "ac_conv2d_i8", "ac_gemm_bf16", "ac_batched_gemm_f32",
+           "ac_tinympc_forward_f32", "ac_gemm_i8_acc32",
            "ac_status_string", "ac_version")
 
 _lib = None
@@ -54,6 +55,10 @@ def lib() -> ctypes.CDLL:
         L.ac_gemm_bf16.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, f32, f32, vp]
         L.ac_batched_gemm_f32.restype = i32
         L.ac_batched_gemm_f32.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, vp]
+        L.ac_gemm_i8_acc32.restype = i32
+        L.ac_gemm_i8_acc32.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp]
+        L.ac_tinympc_forward_f32.restype = i32
+        L.ac_tinympc_forward_f32.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, vp]
         L.ac_status_string.restype = ctypes.c_char_p
         L.ac_status_string.argtypes = [i32]
         L.ac_version.restype = i32
@@ -183,3 +188,45 @@ def ac_batched_gemm_f32(A, B, C=None, x=None, d=None, y=None, stream=None):
     if st != AC_OK:
         raise AcError(st, "ac_batched_gemm_f32")
     return C, y
+
+
+def ac_tinympc_forward_f32(Adyn, Bdyn, Kinf, x0, d, u, x_out=None, stream=None):
+    """Batched TinyMPC forward pass: u[b,i] = -Kinf x[b,i] - d[b,i]; x[b,i+1] = Adyn x[b,i] + Bdyn u[b,i].
+
+    Adyn [nx,nx], Bdyn [nx,nu], Kinf [nu,nx], x0 [batch,nx], d and u [batch,horizon,nu], x_out [batch,horizon+1,nx] or None."""
+    for t, name in ((Adyn, "Adyn"), (Bdyn, "Bdyn"), (Kinf, "Kinf"), (x0, "x0"), (d, "d"), (u, "u"), (x_out, "x_out")):
+        if t is not None and (t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda):
+            raise ValueError(f"{name}: expected a dense fp32 device tensor")
+    nx, nu = Bdyn.shape
+    batch, horizon, nu2 = d.shape
+    if tuple(Adyn.shape) != (nx, nx) or tuple(Kinf.shape) != (nu, nx) or nu2 != nu or tuple(x0.shape) != (batch, nx):
+        raise ValueError("shape mismatch")
+    if tuple(u.shape) != (batch, horizon, nu) or (x_out is not None and tuple(x_out.shape) != (batch, horizon + 1, nx)):
+        raise ValueError("output shape mismatch")
+    st = lib().ac_tinympc_forward_f32(_ptr(Adyn), _ptr(Bdyn), _ptr(Kinf), _ptr(x0), _ptr(d), _ptr(u), _ptr(x_out),
+                                      nx, nu, horizon, batch, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_tinympc_forward_f32")
+    return u, x_out
+
+
+def ac_gemm_i8_acc32(A, B, bias, C, stream=None):
+    """C[M,N] int32 = A[M,K] . B[K,N] + bias (raw accumulator: no scaling, no activation).  Returns C."""
+    _check2d(A, torch.int8, "A")
+    _check2d(B, torch.int8, "B")
+    _check2d(C, torch.int32, "C")
+    M, K = A.shape
+    N = B.shape[1]
+    if B.shape[0] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    bias_ld = 0
+    if bias is not None:
+        if bias.dtype != torch.int32 or not bias.is_cuda:
+            raise ValueError("bias: expected int32 device tensor")
+        if bias.dim() == 2:
+            bias_ld = bias.stride(0)
+    st = lib().ac_gemm_i8_acc32(_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(bias), bias_ld, _ptr(C), C.stride(0),
+                                M, N, K, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_gemm_i8_acc32")
+    return C

@@ -150,3 +150,20 @@ def test_argument_errors():
     assert L.ac_gemm_i8(a, 4, a + 16, 4, None, 0, a, 4, 4, 4, 4, 3, 0, None, 0, None) == ops.AC_ERR_ALIAS
     assert L.ac_gemm_i8(a, 4, None, 4, None, 0, a + 32, 4, 4, 4, 4, 3, 0, None, 0, None) == ops.AC_ERR_NULL
     assert L.ac_gemm_i8(a, 4, a + 16, 4, None, 0, a + 32, 4, -1, 4, 4, 3, 0, None, 0, None) == ops.AC_ERR_SHAPE
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (300, 200, 130), (320, 208, 144), (1792, 1792, 208), (4096, 3072, 64), (12544, 64, 256)])
+def test_raw_accumulator_output(M, N, K):
+    """ac_gemm_i8_acc32: the int32 accumulator itself (no scaling, no activation), against the oracle's exact sums."""
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + 3 * N + K)
+    _, want = oracle.gemm_i8(A, B, bias, 0, 0, return_acc=True)
+    C = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+    ops.ac_gemm_i8_acc32(dev(A), dev(B), dev(bias), C)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C).astype(np.int64), want)
+    # the paper's own GEMM kernel (Appendix D.1): no bias, no activation, scale 1: the int8 result is sat8 of these sums
+    C8 = torch.empty((M, N), dtype=torch.int8, device="cuda")
+    ops.ac_gemm_i8(dev(A), dev(B), None, C8, 0, ops.AC_ACT_NONE)
+    ops.ac_gemm_i8_acc32(dev(A), dev(B), None, C)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C8), np.clip(host(C), -128, 127).astype(np.int8))

@@ -82,7 +82,7 @@ def make_workloads():
     y = torch.empty((case.batch, case.n), dtype=torch.float32, device="cuda")
     wl.append(Workload(case.name, "batched_f32", "f32", case.ops, case.bytes,
                        lambda A=A, B=B, C=C, x=x, d=d, y=y: ops.ac_batched_gemm_f32(A, B, C, x, d, y),
-                       "batched_f32_kernel<12,32,true>"))
+                       "batched12_stream_kernel"))
     return wl
 
 

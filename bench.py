@@ -238,6 +238,30 @@ def supplementary(stream):
                           lambda x=x, wt=wt, bs=bs, o=o, c=case: ops.ac_conv2d_i8(x, wt, bs, o, c.stride, c.pad, c.shift, c.act), "")
             ms = isolated_time(ww, stream, reps=5, rounds=3)
             out.append({"name": ww.name, "ms": ms, "tops": opsn / ms / 1e9, "frac_mfma_peak": opsn / ms / 1e9 / PEAK["i8"]})
+            del x, wt, bs, o
+        del A, B, C
+        # GEMM shapes the paper names outside the workload configurations (reuse-study families, the GPU and
+        # accelerator studies' large GEMMs), on device-generated data of the same distributions
+        for case in inputs.GEMM_I8_PAPER:
+            A = torch.randint(-128, 128, (case.M, case.K), dtype=torch.int8, device="cuda", generator=g)
+            B = torch.randint(-128, 128, (case.K, case.N), dtype=torch.int8, device="cuda", generator=g)
+            bias = torch.randint(-(1 << 15), 1 << 15, (case.N,), dtype=torch.int32, device="cuda", generator=g)
+            C = torch.empty((case.M, case.N), dtype=torch.int8, device="cuda")
+            w = Workload("paper_shape_" + case.name, "gemm_i8", "i8", case.ops, case.bytes,
+                         lambda A=A, B=B, bias=bias, C=C, c=case: ops.ac_gemm_i8(A, B, bias, C, c.shift, c.act), "")
+            ms = isolated_time(w, stream, reps=20, rounds=3)
+            out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"],
+                        "plan": list(ops.ac_gemm_i8_auto_plan(case.M, case.N, case.K, False))})
+        for case in inputs.GEMM_BF16_PAPER:
+            A = torch.randn((case.M, case.K), device="cuda", generator=g).to(torch.bfloat16)
+            B = torch.randn((case.K, case.N), device="cuda", generator=g).to(torch.bfloat16)
+            C = torch.empty((case.M, case.N), dtype=torch.float32, device="cuda")
+            w = Workload("paper_shape_" + case.name, "gemm_bf16", "bf16", case.ops, case.bytes,
+                         lambda A=A, B=B, C=C: ops.ac_gemm_bf16(A, B, C), "")
+            ms = isolated_time(w, stream, reps=5, rounds=3)
+            out.append({"name": w.name, "ms": ms, "tflops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["bf16"],
+                        "gbs": w.bytes / ms / 1e6, "plan": list(ops.ac_gemm_bf16_auto_plan(case.M, case.N, case.K))})
+            del A, B, C
     return out
 
 

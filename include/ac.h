@@ -3,10 +3,10 @@
  *
  * The operations are the ones arxiv 2505.18574 (Autocomp) optimises on its
  * accelerators: int8 GEMM and convolution with the int8 accelerator's bias /
- * scale-down / saturate / ReLU output stage (Section 5.1, Appendix B), the
+ * scale-down / saturate / ReLU output stage (Section 4.4, Appendix C), the
  * large GEMM of the GPU study (Appendix A, Table 5) in bf16 with fp32
  * accumulation, and the batched fine-grained fp32 linear algebra of the
- * TinyMPC study (Section 5.1.3, Appendix D.2).
+ * TinyMPC study (Section 4.4.3, Appendix D.2).
  *
  * Conventions shared by every entry point
  *  - Every data pointer is a DEVICE pointer into memory owned by the caller.
@@ -44,10 +44,11 @@ enum {
   AC_ERR_ACT = -5,       /* unknown activation                                      */
   AC_ERR_ALIAS = -6,     /* an output has the same base address as an input         */
   AC_ERR_WORKSPACE = -7, /* workspace pointer/size inconsistent                     */
-  AC_ERR_LAUNCH = -8     /* the HIP runtime refused the launch                      */
+  AC_ERR_LAUNCH = -8,    /* the HIP runtime refused the launch                      */
+  AC_ERR_PLAN = -9       /* unknown tile, or a K split the shape/operands cannot take */
 };
 
-/* Activations of the output stage (Appendix B, Fig. 13: the `act` field of
+/* Activations of the output stage (Appendix C, Fig. 14: the `act` field of
  * config_ex).  The normalisation-type activations listed there are not part
  * of this library. */
 enum { AC_ACT_NONE = 0, AC_ACT_RELU = 1 };
@@ -61,8 +62,8 @@ enum { AC_ACT_NONE = 0, AC_ACT_RELU = 1 };
  * The contraction is the matrix product of Section 2 (Fig. 2) on the
  * A[M][K], B[K][N], C[M][N] operands of the paper's GEMM kernels
  * (Appendix D.1).  The bias enters through the accumulator ("C = A * B +
- * bias", Appendix B Fig. 13); the int8 result is the scaled-down read of the
- * accumulator with the configured activation (Appendix B Fig. 14, bit 29).
+ * bias", Appendix C Fig. 14); the int8 result is the scaled-down read of the
+ * accumulator with the configured activation (Appendix C Fig. 15, bit 29).
  * rne_rshift(v, s) is v / 2^s rounded to the nearest integer with halves to
  * the even neighbour; sat8 clamps to [-128, 127]; act is AC_ACT_NONE or
  * AC_ACT_RELU.  The result is defined when every exact sum fits in int32.
@@ -94,7 +95,7 @@ size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K);
 /*
  * int8 GEMM with the raw accumulator as output: C32[i][j] = sum_k A[i][k] * B[k][j] + bias(i, j) in int32,
  * with no scaling and no activation.  This is the accumulator-type read of the paper's accelerator
- * (Appendix B, Fig. 14: bit 29 of an accumulator read address selects the full accumulator value and skips
+ * (Appendix C, Fig. 15: bit 29 of an accumulator read address selects the full accumulator value and skips
  * activation and scaling).  Operands and bias as for ac_gemm_i8; C is int32, M x N, row stride ldc >= N.
  */
 ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
@@ -102,7 +103,7 @@ ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_
                            int32_t M, int32_t N, int32_t K, void* stream);
 
 /*
- * int8 2-D convolution (the convolution workload of Section 5.1.2) computed
+ * int8 2-D convolution (the convolution workload of Section 4.4.2) computed
  * as an implicit GEMM with M = Nb*OH*OW, N = Cout, K = KH*KW*Cin, followed by
  * the same output stage as ac_gemm_i8:
  *
@@ -127,7 +128,7 @@ ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, i
 
 /*
  * bf16 GEMM with fp32 accumulation and fp32 output (the square GEMM of
- * Appendix A Table 5, at the reduced input precision Section 5.3 reports as
+ * Appendix A Table 5, at the reduced input precision Section 4.6 reports as
  * the route to the matrix units):
  *
  *   C = alpha * (A . B) + beta * C
@@ -138,7 +139,9 @@ ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, i
  *      (with beta == 0 it may hold anything, NaN included)
  *   K == 0 gives C = beta * C.
  * Products are exact in fp32; sums are accumulated in fp32 in an unspecified
- * order.
+ * order.  Shapes with few output tiles and a deep K are cut along K (see the
+ * planned launches below): their sums may differ in the last bits from run to
+ * run.
  */
 ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
                        float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
@@ -182,6 +185,39 @@ ac_status ac_batched_gemm_f32(const float* A, const float* B, float* C,
 ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const float* Kinf,
                                  const float* x0, const float* d, float* u, float* x_out,
                                  int32_t nx, int32_t nu, int32_t horizon, int64_t batch, void* stream);
+
+/*
+ * Planned launches: the caller, not the library, names the block tile and the K split.
+ *
+ * The paper's search keeps a candidate only if it is still correct and ranks the survivors by
+ * measured latency (Section 3.3); on this chip the candidates of a GEMM are its block tile and K split.  These
+ * entry points run one named candidate so that a tuner can time each of them on the caller's own shape; the
+ * results are those of ac_gemm_i8 / ac_gemm_bf16 (bit for bit for int8; for bf16 up to the summation order).
+ *
+ *   tile    edge of the square block tile: 64, 128 or 256
+ *   splits  1 = no split; n > 1 cuts the K range into at most n slices of equal whole K tiles (64 bytes of K
+ *           per tile for tile 256, 128 bytes otherwise), each slice a workgroup of its own.  Needs operands
+ *           that qualify for the direct-to-LDS kernels: base pointers and row pitches of A and B multiples of
+ *           16 bytes, K and N multiples of 16 (int8) or 8 (bf16) elements, C 4-byte (int8) or 16-byte (bf16)
+ *           aligned with ldc a multiple of 4.
+ *           int8: slices leave int32 partial sums in `workspace`, which must hold
+ *           ac_gemm_i8_planned_workspace_bytes() bytes; a second kernel sums them and applies the output stage.
+ *           bf16: a first kernel sets C = beta * C, then every slice adds alpha * (its product) with fp32
+ *           atomic adds, in no fixed order.
+ *   AC_ERR_PLAN: tile not one of the three, splits < 1 or larger than the number of K tiles, or splits > 1
+ *           with operands that do not qualify.  Everything else as for the unplanned call.
+ * ac_gemm_*_auto_plan report what the unplanned call would choose for a shape (pure host arithmetic).
+ */
+ac_status ac_gemm_i8_planned(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                             const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                             int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
+                             void* workspace, size_t workspace_bytes, int32_t tile, int32_t splits, void* stream);
+size_t ac_gemm_i8_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits);
+ac_status ac_gemm_bf16_planned(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
+                               float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                               float alpha, float beta, int32_t tile, int32_t splits, void* stream);
+void ac_gemm_i8_auto_plan(int32_t M, int32_t N, int32_t K, int32_t have_workspace, int32_t* tile, int32_t* splits);
+void ac_gemm_bf16_auto_plan(int32_t M, int32_t N, int32_t K, int32_t* tile, int32_t* splits);
 
 /* Static, NUL-terminated description of a status code. */
 const char* ac_status_string(ac_status status);

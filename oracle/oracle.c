@@ -13,7 +13,7 @@
  *
  * Precision: integer paths accumulate in int64 (and report any sum that does
  * not fit int32, the accumulator type of the paper's int8 accelerator,
- * Section 5.1); floating-point paths compute in fp64 from the exact values
+ * Section 4.4); floating-point paths compute in fp64 from the exact values
  * of their bf16 / fp32 inputs.
  *
  * Pins (tests/test_oracle_*.py): exact-rational rounding, brute force on tiny
@@ -44,7 +44,7 @@ int oracle_num_threads(void) {
 /*
  * v / 2^s rounded to the nearest integer, ties to the even integer.
  * The paper only says the accumulator is read back as "scaled-down" input-type
- * data (Appendix B, Fig. 14, bit 29); the power-of-two, round-half-even reading
+ * data (Appendix C, Fig. 15, bit 29); the power-of-two, round-half-even reading
  * is the one the int8 workloads here are specified with.
  */
 int64_t oracle_rne_rshift(int64_t v, int32_t s) {
@@ -58,8 +58,8 @@ int64_t oracle_rne_rshift(int64_t v, int32_t s) {
   return fl;
 }
 
-/* Output stage of the int8 accelerator (Fig. 13: activation set by config_ex;
- * Fig. 14: scaled-down read of the accumulator): shift, saturate, ReLU. */
+/* Output stage of the int8 accelerator (Fig. 14: activation set by config_ex;
+ * Fig. 15: scaled-down read of the accumulator): shift, saturate, ReLU. */
 static int8_t requantise(int64_t acc, int32_t shift, int32_t act) {
   int64_t q = oracle_rne_rshift(acc, shift);
   if (q > 127) q = 127;
@@ -81,7 +81,7 @@ void oracle_requantise_vec(const int64_t* acc, int32_t shift, int32_t act, int8_
 
 /*
  * int8 GEMM, Section 2 Fig. 2 (C[i][j] += A[i][k]*B[k][j]) with the bias of
- * Fig. 13 ("C = A * B + bias") and the output stage above.
+ * Fig. 14 ("C = A * B + bias") and the output stage above.
  * A: M x K row-major (lda), B: K x N row-major (ldb), C: M x N row-major (ldc).
  * bias == NULL: none; bias_ld == 0: one row of N values broadcast to every row;
  * otherwise an M x N matrix with row stride bias_ld.
@@ -114,7 +114,7 @@ int64_t oracle_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ld
 }
 
 /*
- * int8 convolution, direct definition (Section 5.1.2 names the workload; the
+ * int8 convolution, direct definition (Section 4.4.2 names the workload; the
  * layouts are NHWC activations, [KH][KW][Cin][Cout] weights, NHWC output):
  *   out[n,oh,ow,co] = stage( bias[co] + sum_{kh,kw,ci} in[n, oh*stride-pad+kh,
  *                            ow*stride-pad+kw, ci] * w[kh,kw,ci,co] )
@@ -257,7 +257,7 @@ void oracle_gemm_i8_at(const int8_t* A, int64_t lda, const int8_t* B, int64_t ld
 }
 
 /*
- * Batched small dense algebra (the fine-grained workload of Section 5.1.3 /
+ * Batched small dense algebra (the fine-grained workload of Section 4.4.3 /
  * Appendix D.2: n x n products followed by a matrix-vector product and an
  * element-wise add), per item b, in fp64 from the fp32 inputs:
  *   C_b = A_b . B_b            (n x n)

@@ -30,6 +30,7 @@ const char* ac_status_string(ac_status status) {
     case AC_ERR_ALIAS: return "an output has the same base address as an input";
     case AC_ERR_WORKSPACE: return "workspace too small or misaligned";
     case AC_ERR_LAUNCH: return "the HIP runtime refused the launch";
+    case AC_ERR_PLAN: return "unknown tile, or a K split that this shape or these operands cannot take";
     default: return "unknown status";
   }
 }
@@ -38,24 +39,50 @@ int32_t ac_version(void) { return 100; }
 
 size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K) {
   if (M <= 0 || N <= 0 || K <= 0) return 0;
-  const ac::I8Plan plan = ac::plan_gemm_i8(M, N, K, true);
+  const ac::GemmPlan plan = ac::plan_gemm_i8(M, N, K, true);
   if (plan.splits <= 1) return 0;
   // int32 partial sums of every K slice
   return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t);
 }
 
-ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
-                     const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
-                     int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
-                     void* workspace, size_t workspace_bytes, void* stream) {
+size_t ac_gemm_i8_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits) {
+  ac::GemmPlan plan;
+  if (M <= 0 || N <= 0 || K <= 0 || !ac::make_plan_i8(K, tile, splits, &plan) || plan.splits <= 1) return 0;
+  return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t);
+}
+
+void ac_gemm_i8_auto_plan(int32_t M, int32_t N, int32_t K, int32_t have_workspace, int32_t* tile, int32_t* splits) {
+  const ac::GemmPlan plan = ac::plan_gemm_i8(M < 0 ? 0 : M, N < 0 ? 0 : N, K < 0 ? 0 : K, have_workspace != 0);
+  if (tile) *tile = plan.tile;
+  if (splits) *splits = plan.splits;
+}
+
+void ac_gemm_bf16_auto_plan(int32_t M, int32_t N, int32_t K, int32_t* tile, int32_t* splits) {
+  const ac::GemmPlan plan = ac::plan_gemm_bf16(M < 0 ? 0 : M, N < 0 ? 0 : N, K < 0 ? 0 : K);
+  if (tile) *tile = plan.tile;
+  if (splits) *splits = plan.splits;
+}
+
+}  // extern "C"
+
+namespace {
+
+// ac_gemm_i8 and ac_gemm_i8_planned: `planned` selects the caller's (tile, splits) over the library's choice.
+ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                        const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                        int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
+                        void* workspace, size_t workspace_bytes, bool planned, int32_t tile, int32_t splits, void* stream) {
   if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
   if (ac_status s = check_stage(shift, act)) return s;
   if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
   if (bias && bias_ld != 0 && bias_ld < N) return AC_ERR_STRIDE;
   if (bias_ld < 0) return AC_ERR_STRIDE;
+  ac::GemmPlan plan;
+  if (planned && !ac::make_plan_i8(K, tile, splits, &plan)) return AC_ERR_PLAN;
   if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;
-  if (workspace && (((uintptr_t)workspace & 15) != 0 || workspace_bytes < ac_gemm_i8_workspace_bytes(M, N, K)))
-    return AC_ERR_WORKSPACE;
+  const size_t need = planned ? ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits) : ac_gemm_i8_workspace_bytes(M, N, K);
+  if (workspace && (((uintptr_t)workspace & 15) != 0 || workspace_bytes < need)) return AC_ERR_WORKSPACE;
+  if (planned && need > 0 && !workspace) return AC_ERR_WORKSPACE;
   if (M == 0 || N == 0) return AC_OK;
   if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
   if ((const void*)C == (const void*)A || (const void*)C == (const void*)B || (const void*)C == (const void*)bias)
@@ -67,7 +94,46 @@ ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
   p.M = M; p.N = N; p.K = K; p.shift = shift; p.act = act;
   p.splits = 1;
   p.partial = (int32_t*)workspace;
-  return ac::launch_gemm_i8(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+  if (planned && plan.splits > 1 && !ac::gemm_i8_fast_path(p)) return AC_ERR_PLAN;
+  return ac::launch_gemm_i8(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
+ac_status gemm_bf16_entry(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
+                          float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                          float alpha, float beta, bool planned, int32_t tile, int32_t splits, void* stream) {
+  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
+  ac::GemmPlan plan;
+  if (planned && !ac::make_plan_bf16(K, tile, splits, &plan)) return AC_ERR_PLAN;
+  if (M == 0 || N == 0) return AC_OK;
+  if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
+  if ((const void*)C == (const void*)A || (const void*)C == (const void*)B) return AC_ERR_ALIAS;
+
+  ac::GemmParams p = {};
+  p.A = A; p.B = B; p.C = C;
+  p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  p.M = M; p.N = N; p.K = K; p.alpha = alpha; p.beta = beta;
+  p.splits = 1;
+  if (planned && plan.splits > 1 && !ac::gemm_bf16_fast_path(p)) return AC_ERR_PLAN;
+  return ac::launch_gemm_bf16(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                     const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                     int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  return gemm_i8_entry(A, lda, B, ldb, bias, bias_ld, C, ldc, M, N, K, shift, act, workspace, workspace_bytes, false, 0, 0, stream);
+}
+
+ac_status ac_gemm_i8_planned(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                             const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                             int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
+                             void* workspace, size_t workspace_bytes, int32_t tile, int32_t splits, void* stream) {
+  return gemm_i8_entry(A, lda, B, ldb, bias, bias_ld, C, ldc, M, N, K, shift, act, workspace, workspace_bytes, true, tile, splits, stream);
 }
 
 ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
@@ -123,18 +189,13 @@ ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, i
 ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
                        float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
                        float alpha, float beta, void* stream) {
-  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
-  if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
-  if (M == 0 || N == 0) return AC_OK;
-  if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
-  if ((const void*)C == (const void*)A || (const void*)C == (const void*)B) return AC_ERR_ALIAS;
+  return gemm_bf16_entry(A, lda, B, ldb, C, ldc, M, N, K, alpha, beta, false, 0, 0, stream);
+}
 
-  ac::GemmParams p = {};
-  p.A = A; p.B = B; p.C = C;
-  p.lda = lda; p.ldb = ldb; p.ldc = ldc;
-  p.M = M; p.N = N; p.K = K; p.alpha = alpha; p.beta = beta;
-  p.splits = 1;
-  return ac::launch_gemm_bf16(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+ac_status ac_gemm_bf16_planned(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
+                               float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                               float alpha, float beta, int32_t tile, int32_t splits, void* stream) {
+  return gemm_bf16_entry(A, lda, B, ldb, C, ldc, M, N, K, alpha, beta, true, tile, splits, stream);
 }
 
 ac_status ac_batched_gemm_f32(const float* A, const float* B, float* C,

@@ -29,10 +29,10 @@ struct GemmParams {
   float alpha, beta;    // bf16 epilogue
   // convolution geometry (implicit GEMM: m -> (n, oh, ow), k -> (kh, kw, ci))
   int32_t H, W, Cin, KW, OH, OW, stride, pad;
-  // split-K (int8): number of K slices and the int32 partial-sum workspace
+  // split-K: number of K slices; int8 slices leave int32 partial sums in a workspace, bf16 slices add into C
   int32_t splits;        // number of K slices (1 = no split)
   int32_t kt_per_split;  // K tiles (of the launched kernel's tile depth) per slice
-  int32_t* partial;      // [splits][M][N] int32 partial sums when splits > 1
+  int32_t* partial;      // int8: [splits][M][N] int32 partial sums when splits > 1
 };
 
 struct BatchedParams {
@@ -58,20 +58,29 @@ struct TinyMpcParams {
   int64_t batch;
 };
 
+// Block tile and K split of one GEMM launch.  Chosen by the library from the shape (plan_gemm_*), or named
+// by the caller through the planned entry points (make_plan_*), which is what a tuner drives.
+struct GemmPlan {
+  int tile;          // square block tile edge: 64, 128 or 256
+  int ktb;           // K bytes per tile of the kernel that serves this block tile
+  int splits;        // K slices (1 = no split)
+  int kt_per_split;  // K tiles per slice (0 when splits == 1)
+};
+GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace);
+GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K);
+// Explicit plans: false when the tile is not one of the three, or splits is outside 1 .. number of K tiles.
+bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan);
+bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan);
+
+// Launchers.  `forced` null: the library plans.  A forced plan with splits > 1 needs the fast (direct-to-LDS)
+// path; the launcher returns hipErrorInvalidValue when the operands do not qualify for it.
 hipError_t launch_tinympc_forward(const TinyMpcParams& p, hipStream_t stream);
-hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream);
+hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
 hipError_t launch_gemm_i8_acc32(const GemmParams& p, hipStream_t stream);
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream);
-hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream);
+hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
 hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream);
-
-// Tile choice made by the int8 launcher for a shape; shared with the workspace query.
-struct I8Plan {
-  int bm, bn;        // block tile
-  int ktb;           // K bytes per tile of the kernel chosen for this block tile
-  int splits;        // K slices (1 = no split)
-  int kt_per_split;  // K tiles per slice
-};
-I8Plan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace);
+bool gemm_i8_fast_path(const GemmParams& p);
+bool gemm_bf16_fast_path(const GemmParams& p);
 
 }  // namespace ac

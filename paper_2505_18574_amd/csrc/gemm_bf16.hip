@@ -1,53 +1,84 @@
-// bf16 GEMM, fp32 accumulate and output: tile selection and launch.
+// bf16 GEMM, fp32 accumulate and output: tile selection, split-K and launch.
 #include "gemm_dtl.hpp"
-
-#include <stdlib.h>
 
 namespace ac {
 
-hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream) {
+// Block tile and K split for an M x N x K bf16 problem: the largest tile that still gives most compute units
+// work (the 256 tile with its eight-wave schedule already wins at one tile on every second unit).  When even
+// 64 x 64 tiles leave most of the chip idle and K is deep, K is cut into slices that add into C (see
+// EpilogueAtomicF32).  The slice count minimises a two-term estimate measured on this chip: a 64 x 64
+// workgroup alone on its compute unit advances one K tile in about 0.28 us, and the fp32 atomic adds of one
+// slice retire at about 43 elements per nanosecond, so every extra slice costs M * N / 43000 us.
+GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K) {
+  auto tiles = [&](int t) { return (int64_t)((M + t - 1) / t) * ((N + t - 1) / t); };
+  // a tile much larger than the problem wastes most of its MFMAs: require 3/4 of the tile edge in both dimensions
+  const bool ok256 = M >= 192 && N >= 192, ok128 = M >= 96 && N >= 96;
+  const int tile = (ok256 && tiles(256) >= 128) ? 256 : ((ok128 && tiles(128) >= 192) ? 128 : 64);
+  GemmPlan plan;
+  make_plan_bf16(K, tile, 1, &plan);
+  if (tile == 64) {
+    const int64_t t = tiles(64);
+    const int64_t nkt = ((int64_t)K * 2 + plan.ktb - 1) / plan.ktb;
+    const double slice_us = (double)M * N / 43000.0;
+    double best = 0.28 * (double)nkt * (double)((t + 255) / 256);
+    int best_s = 1;
+    for (int s = 2; s * t <= 256 && s <= nkt; s *= 2) {  // at most one workgroup per compute unit
+      const double est = 0.28 * (double)((nkt + s - 1) / s) + 2.0 + slice_us * s;
+      if (est < best) {
+        best = est;
+        best_s = s;
+      }
+    }
+    if (best_s > 1) make_plan_bf16(K, tile, best_s, &plan);
+  }
+  return plan;
+}
+
+// C = beta * C ahead of a split-K launch (beta == 0 stores zeros without reading C).
+__global__ void __launch_bounds__(256) scale_c_f32_kernel(float* C, int64_t ldc, int M, int N, float beta) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)M * N) return;
+  float* c = C + (i / N) * ldc + (i % N);
+  *c = beta == 0.f ? 0.f : beta * *c;
+}
+
+bool gemm_bf16_fast_path(const GemmParams& p) {
+  return (((uintptr_t)p.A & 15) == 0) && (((uintptr_t)p.B & 15) == 0) && (p.lda % 8 == 0) && (p.ldb % 8 == 0) &&
+         (((uintptr_t)p.C & 15) == 0) && (p.ldc % 4 == 0) && (p.K % 8 == 0) && (p.N % 8 == 0);
+}
+
+hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const GemmPlan* forced) {
+  GemmParams p = p0;
   const bool aligned = (((uintptr_t)p.A & 15) == 0) && (((uintptr_t)p.B & 15) == 0) && (p.lda % 8 == 0) && (p.ldb % 8 == 0) &&
                        (((uintptr_t)p.C & 15) == 0) && (p.ldc % 4 == 0);
   // direct-to-LDS fast path: additionally K and N in whole 16-byte chunks
-  const bool fast = aligned && (p.K % 8 == 0) && (p.N % 8 == 0);
-  auto tiles = [&](int t) { return (int64_t)((p.M + t - 1) / t) * ((p.N + t - 1) / t); };
-  // a tile much larger than the problem wastes most of its MFMAs: require 3/4 of the tile edge in both dimensions
-  const bool ok256 = p.M >= 192 && p.N >= 192, ok128 = p.M >= 96 && p.N >= 96;
-  const int tile = (ok256 && tiles(256) >= 192) ? 256 : ((ok128 && tiles(128) >= 192) ? 128 : 64);
+  const bool fast = gemm_bf16_fast_path(p);
+  GemmPlan plan = forced ? *forced : plan_gemm_bf16(p.M, p.N, p.K);
+  if (plan.splits > 1 && !fast) {
+    if (forced) return hipErrorInvalidValue;
+    make_plan_bf16(p.K, plan.tile, 1, &plan);
+  }
+  p.splits = plan.splits;
+  p.kt_per_split = plan.kt_per_split;
   if (fast) {
-    // AC_BF16_VARIANT selects an alternative schedule of the large-tile kernel (a tuning aid; default 10:
-    // eight waves in ping-pong over four 32 KB LDS stages)
-    static const int variant = getenv("AC_BF16_VARIANT") ? atoi(getenv("AC_BF16_VARIANT")) : 10;
-    if (tile == 256) {
-      switch (variant) {
-        case 1: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 2, 128>(p, stream);
-        case 2: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 4, 2, 0, 2, 128>(p, stream);
-        case 3: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 2, 0, 4, 64>(p, stream);
-        case 4: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 4, 64>(p, stream);
-        case 5: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 2, 2, 0, 3, 128>(p, stream);
-        case 6: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 4, 2, 0, 3, 128>(p, stream);
-        case 7: return launch_dtl<TypeBF16, EpilogueF32, 128, 256, 2, 2, 0, 3, 128>(p, stream);
-        case 8: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 2, 2, 0, 6, 64>(p, stream);
-        case 9: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 4, 2, 0, 4, 64>(p, stream);
-        case 11: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 4, 2, 0, 4, 64, true>(p, stream);
-        case 13: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 4, 2, 0, 3, 64, true>(p, stream);
-        case 14: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 4, 2, 0, 3, 64, false>(p, stream);
-        case 15: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 2, 4, 0, 3, 64, true>(p, stream);
-        case 16: return launch_dtl<TypeBF16, EpilogueF32, 128, 256, 2, 4, 0, 3, 64, true>(p, stream);
-        case 17: return launch_dtl<TypeBF16, EpilogueF32, 256, 128, 2, 2, 0, 3, 64, false>(p, stream);
-        case 18: return launch_dtl<TypeBF16, EpilogueF32, 128, 128, 2, 2, 0, 4, 64, false>(p, stream);
-        case 12: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 3, 64, true>(p, stream);
-        case 0: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 2, 0, 2, 128>(p, stream);
-        default: return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-      }
+    if (plan.splits > 1) {
+      const int64_t n = (int64_t)p.M * p.N;
+      hipLaunchKernelGGL(scale_c_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (float*)p.C, p.ldc, p.M, p.N, p.beta);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      if (plan.tile == 256) return launch_dtl<TypeBF16, EpilogueAtomicF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
+      if (plan.tile == 128) return launch_dtl<TypeBF16, EpilogueAtomicF32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+      return launch_dtl<TypeBF16, EpilogueAtomicF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
     }
-    if (tile == 128) return launch_dtl<TypeBF16, EpilogueF32, 128, 128, 2, 2, 0, 3>(p, stream);
-    return launch_dtl<TypeBF16, EpilogueF32, 64, 64, 2, 2, 0, 4>(p, stream);
+    // large tile: eight waves in ping-pong over four 32 KB LDS stages
+    if (plan.tile == 256) return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
+    if (plan.tile == 128) return launch_dtl<TypeBF16, EpilogueF32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+    return launch_dtl<TypeBF16, EpilogueF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
   }
 #define AC_BF16_LAUNCH(TILE)                                                                        \
   (aligned ? launch_tile<TypeBF16, EpilogueF32, TILE, TILE, 2, 2, 0, true>(p, stream)               \
            : launch_tile<TypeBF16, EpilogueF32, TILE, TILE, 2, 2, 0, false>(p, stream))
-  switch (tile) {
+  switch (plan.tile) {
     case 256: return AC_BF16_LAUNCH(256);
     case 128: return AC_BF16_LAUNCH(128);
     default: return AC_BF16_LAUNCH(64);

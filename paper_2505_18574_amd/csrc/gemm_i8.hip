@@ -3,26 +3,23 @@
 
 namespace ac {
 
+static int ktb_of_tile_i8(int tile) { return tile == 256 ? 64 : 128; }  // K bytes per tile of each kernel below
+
 // Pick block tile and K split for an M x N x K int8 problem.  The chip has 256 compute units: a launch
 // wants at least that many workgroups, and a bigger tile re-reads less of A and B.  Take the largest tile
 // that still yields enough workgroups; when even the smallest tile leaves most CUs idle and K is deep, slice
 // K so that every slice becomes its own workgroup (needs the caller's workspace for the int32 partial sums).
-I8Plan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
-  auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-  I8Plan plan;
+GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
+  auto tiles = [&](int t) { return (int64_t)((M + t - 1) / t) * ((N + t - 1) / t); };
+  GemmPlan plan;
   plan.splits = 1;
   plan.kt_per_split = 0;
-  plan.ktb = 128;
   // a tile much wider (taller) than the problem wastes most of its MFMAs: require 3/4 of the tile edge
   const bool ok256 = M >= 192 && N >= 192, ok128 = M >= 96 && N >= 96;
-  if (ok256 && tiles(256, 256) >= 192) {
-    plan.bm = plan.bn = 256;
-    plan.ktb = 64;
-  } else if (ok128 && tiles(128, 128) >= 192) {
-    plan.bm = plan.bn = 128;
-  } else {
-    plan.bm = plan.bn = 64;
-    const int64_t t = tiles(64, 64);
+  plan.tile = (ok256 && tiles(256) >= 192) ? 256 : ((ok128 && tiles(128) >= 192) ? 128 : 64);
+  plan.ktb = ktb_of_tile_i8(plan.tile);
+  if (plan.tile == 64) {
+    const int64_t t = tiles(64);
     const int nkt = (K + plan.ktb - 1) / plan.ktb;
     if (have_workspace && t <= 64 && nkt >= 16) {  // the second (reduce) launch costs about 3 us: only worth it for deep K
       int want = (int)((256 + t - 1) / t);             // slices needed to cover the CUs
@@ -39,6 +36,36 @@ I8Plan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   return plan;
 }
 
+// Shared by the int8 and bf16 explicit plans: `splits` slices of ceil(nkt / splits) K tiles each.
+static bool make_plan(int64_t kbytes, int tile, int ktb, int splits, GemmPlan* plan) {
+  const int64_t nkt = (kbytes + ktb - 1) / ktb;
+  if (splits < 1 || (splits > 1 && splits > nkt)) return false;
+  plan->tile = tile;
+  plan->ktb = ktb;
+  plan->splits = 1;
+  plan->kt_per_split = 0;
+  if (splits > 1) {
+    const int per = (int)((nkt + splits - 1) / splits);
+    plan->kt_per_split = per;
+    plan->splits = (int)((nkt + per - 1) / per);  // slices that actually hold K tiles
+    if (plan->splits <= 1) {
+      plan->splits = 1;
+      plan->kt_per_split = 0;
+    }
+  }
+  return true;
+}
+
+bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
+  if (tile != 64 && tile != 128 && tile != 256) return false;
+  return make_plan(K, tile, ktb_of_tile_i8(tile), splits, plan);
+}
+
+bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
+  if (tile != 64 && tile != 128 && tile != 256) return false;
+  return make_plan((int64_t)K * 2, tile, tile == 256 ? 64 : 128, splits, plan);
+}
+
 // Output stage of a split-K launch: sum the K slices, then bias / shift / saturate / ReLU, 4 outputs per thread.
 __global__ void __launch_bounds__(256) splitk_reduce_i8_kernel(const GemmParams p) {
   const int64_t quads_per_row = p.N / 4;  // split-K is only used on the fast path: N is a multiple of 16
@@ -53,28 +80,31 @@ __global__ void __launch_bounds__(256) splitk_reduce_i8_kernel(const GemmParams 
 }
 
 template <int AMODE>
-hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast) {
-  const I8Plan plan = plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr);
+hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast, const GemmPlan* forced) {
+  const GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr);
   p.splits = plan.splits;
   p.kt_per_split = plan.kt_per_split;
+  if (plan.splits > 1 && (!fast || p.partial == nullptr)) return hipErrorInvalidValue;
   if (fast) {  // direct-to-LDS kernels
     if (plan.splits > 1) {
-      hipError_t e = launch_dtl<TypeI8, EpiloguePartialI32, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
+      hipError_t e;
+      if (plan.tile == 256) e = launch_dtl<TypeI8, EpiloguePartialI32, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
+      else if (plan.tile == 128) e = launch_dtl<TypeI8, EpiloguePartialI32, 128, 128, 2, 2, AMODE, 3, 128>(p, stream);
+      else e = launch_dtl<TypeI8, EpiloguePartialI32, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
       if (e != hipSuccess) return e;
       const int64_t quads = (int64_t)p.M * (p.N / 4);
       hipLaunchKernelGGL(splitk_reduce_i8_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, p);
       return hipGetLastError();
     }
-    if (plan.bm == 256) return launch_dtl<TypeI8, EpilogueI8, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
-    if (plan.bm == 128 && plan.bn == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 2, AMODE, 3, 128>(p, stream);
+    if (plan.tile == 256) return launch_dtl<TypeI8, EpilogueI8, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
+    if (plan.tile == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 2, AMODE, 3, 128>(p, stream);
     return launch_dtl<TypeI8, EpilogueI8, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
   }
-  const int tile = plan.bm == 256 ? 256 : (plan.bm == 128 && plan.bn == 128 ? 128 : 64);
 #define AC_I8_CASE(TILE, WM, WN)                                                                         \
   case TILE:                                                                                             \
     return aligned ? launch_tile<TypeI8, EpilogueI8, TILE, TILE, WM, WN, AMODE, true>(p, stream)         \
                    : launch_tile<TypeI8, EpilogueI8, TILE, TILE, WM, WN, AMODE, false>(p, stream);
-  switch (tile) {
+  switch (plan.tile) {
     AC_I8_CASE(256, 2, 2)
     AC_I8_CASE(128, 2, 2)
     AC_I8_CASE(64, 2, 2)
@@ -98,27 +128,27 @@ hipError_t launch_gemm_i8_acc32(const GemmParams& p0, hipStream_t stream) {
   p.kt_per_split = 0;
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) && aligned16(p.C) && (p.ldc % 4 == 0);
   const bool fast = aligned && (p.K % 16 == 0) && (p.N % 16 == 0);
-  const I8Plan plan = plan_gemm_i8(p.M, p.N, p.K, false);
+  const GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, false);
   if (fast) {
-    if (plan.bm == 256) return launch_dtl<TypeI8, EpilogueRawI32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-    if (plan.bm == 128) return launch_dtl<TypeI8, EpilogueRawI32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+    if (plan.tile == 256) return launch_dtl<TypeI8, EpilogueRawI32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
+    if (plan.tile == 128) return launch_dtl<TypeI8, EpilogueRawI32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
     return launch_dtl<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
   }
   return aligned ? launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, true>(p, stream)
                  : launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, false>(p, stream);
 }
 
-hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream) {
+hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced) {
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) &&
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
-  return dispatch_i8<0>(p, stream, aligned, gemm_i8_fast_path(p));
+  return dispatch_i8<0>(p, stream, aligned, gemm_i8_fast_path(p), forced);
 }
 
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream) {
   // Fast path: channel counts in multiples of 16 so that a 16-byte K chunk stays inside one kernel tap.
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.Cin % 16 == 0) && (p.ldb % 16 == 0) &&
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
-  return dispatch_i8<1>(p, stream, aligned, aligned);
+  return dispatch_i8<1>(p, stream, aligned, aligned, nullptr);
 }
 
 }  // namespace ac

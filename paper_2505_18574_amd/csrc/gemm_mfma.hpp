@@ -295,6 +295,31 @@ struct EpilogueF32 {
   }
 };
 
+// Split-K output of the fp32 epilogue: every K slice adds alpha * (its partial product) into C with the
+// hardware fp32 atomic add; C was set to beta * C by scale_c_f32_kernel before the slices run.  The order in
+// which slices arrive is not fixed, so the last bits of a sum may differ between runs.
+struct EpilogueAtomicF32 {
+  struct Pre {};
+  static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
+  template <bool VEC>
+  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a, int = 0) {
+    if (m >= p.M || n >= p.N) return;
+    float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
+#pragma unroll
+    for (int e = 0; e < 4; e++)
+      if (n + e < p.N) unsafeAtomicAdd(dst + e, p.alpha * a[e]);
+  }
+  template <class ACC>
+  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+      float a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      store4<true>(p, m, n, a4, split);
+    }
+  }
+};
+
 // A-operand addressing ----------------------------------------------------------
 // AMODE 0: A is an M x K matrix.  AMODE 1: A(m, k) is gathered from an NHWC image
 // (m -> (image, oh, ow), k -> (kh, kw, ci)), zero outside the image.

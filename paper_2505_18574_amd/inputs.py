@@ -5,9 +5,9 @@ oracle.  It holds no arithmetic of the operations themselves: only shapes,
 random draws and the float32 -> bfloat16 rounding of input data.
 
 The shapes stand in for the paper's workloads, none of which ships with it:
-ResNet-50 GEMM and convolution layers on the int8 accelerator (Section 5.1.1,
+ResNet-50 GEMM and convolution layers on the int8 accelerator (Section 4.4.1,
 5.1.2), the 4096^3 GEMM of the GPU study (Appendix A, Table 5) and the
-12x12 fine-grained linear algebra of the TinyMPC study (Section 5.1.3,
+12x12 fine-grained linear algebra of the TinyMPC study (Section 4.4.3,
 Appendix D.2).  Values are uniform int8 / int32 / [-1,1) fp32 or N(0,1).
 
 Seeds: the 256^3 GEMM uses seed 0; every other case uses
@@ -138,6 +138,30 @@ GEMM_BF16 = (
 )
 
 BATCHED_F32 = BatchedF32Case("batched_f32_262144x12", 262144, 12, seed=5000)
+
+# Shapes the paper names outside its main sweep, read as M x N x K (the order its 12544x64x256 kernel fixes:
+# A[12544][256], B[256][64], Appendix D.1): the GEMM of the code example, and the square / column-dominant /
+# row-dominant families of the schedule-reuse study (Section 5, Table 2: a base shape followed by its two
+# reuse targets).
+GEMM_I8_PAPER = tuple(
+    GemmI8Case(f"gemm_i8_{m}x{n}x{k}", m, n, k, shift=10, act=ACT_RELU, seed=1000 * 6 + i)
+    for i, (m, n, k) in enumerate(
+        [(12544, 64, 256),
+         (1024, 1024, 1024), (512, 512, 512), (256, 256, 256),
+         (12544, 256, 64), (6272, 256, 64), (12544, 128, 64),
+         (128, 1024, 1024), (64, 1024, 1024), (32, 1024, 1024)]
+    )
+)
+GEMM_I8_REUSE_FAMILIES = ((1, 2, 3), (4, 5, 6), (7, 8, 9))  # indices into GEMM_I8_PAPER: base, target, target
+
+# GEMM shapes of the accelerator and GPU studies (Appendix A, Tables 3 and 5), written there as
+# (M x K) * (K x N): a tall-K product, the 4096 x 8192 x 8192 GEMM, a very deep K and a very shallow K.
+GEMM_BF16_PAPER = tuple(
+    GemmBf16Case(f"gemm_bf16_{m}x{n}x{k}", m, n, k, seed=1000 * 7 + i)
+    for i, (m, n, k) in enumerate(
+        [(2048, 4096, 8192), (4096, 8192, 8192), (256, 256, 524288), (32768, 32768, 32)]
+    )
+)
 
 
 # ----------------------------------------------------------------------------

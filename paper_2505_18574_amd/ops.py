@@ -19,11 +19,14 @@ LIB_PATH = os.path.join(_HERE, "libac_mi355x.so")
 AC_OK = 0
 AC_ERR_NULL, AC_ERR_SHAPE, AC_ERR_STRIDE, AC_ERR_SHIFT = -1, -2, -3, -4
 AC_ERR_ACT, AC_ERR_ALIAS, AC_ERR_WORKSPACE, AC_ERR_LAUNCH = -5, -6, -7, -8
+AC_ERR_PLAN = -9
 AC_ACT_NONE, AC_ACT_RELU = 0, 1
 
 # every symbol include/ac.h declares
 EXPORTS = ("ac_gemm_i8", "ac_gemm_i8_workspace_bytes", "ac_conv2d_i8", "ac_gemm_bf16", "ac_batched_gemm_f32",
            "ac_tinympc_forward_f32", "ac_gemm_i8_acc32",
+           "ac_gemm_i8_planned", "ac_gemm_i8_planned_workspace_bytes", "ac_gemm_bf16_planned",
+           "ac_gemm_i8_auto_plan", "ac_gemm_bf16_auto_plan",
            "ac_status_string", "ac_version")
 
 _lib = None
@@ -59,6 +62,17 @@ def lib() -> ctypes.CDLL:
         L.ac_gemm_i8_acc32.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp]
         L.ac_tinympc_forward_f32.restype = i32
         L.ac_tinympc_forward_f32.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, vp]
+        L.ac_gemm_i8_planned.restype = i32
+        L.ac_gemm_i8_planned.argtypes = L.ac_gemm_i8.argtypes[:-1] + [i32, i32, vp]
+        L.ac_gemm_i8_planned_workspace_bytes.restype = sz
+        L.ac_gemm_i8_planned_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.ac_gemm_bf16_planned.restype = i32
+        L.ac_gemm_bf16_planned.argtypes = L.ac_gemm_bf16.argtypes[:-1] + [i32, i32, vp]
+        pi32 = ctypes.POINTER(i32)
+        L.ac_gemm_i8_auto_plan.restype = None
+        L.ac_gemm_i8_auto_plan.argtypes = [i32, i32, i32, i32, pi32, pi32]
+        L.ac_gemm_bf16_auto_plan.restype = None
+        L.ac_gemm_bf16_auto_plan.argtypes = [i32, i32, i32, pi32, pi32]
         L.ac_status_string.restype = ctypes.c_char_p
         L.ac_status_string.argtypes = [i32]
         L.ac_version.restype = i32
@@ -82,6 +96,24 @@ def ac_gemm_i8_workspace_bytes(M: int, N: int, K: int) -> int:
     return int(lib().ac_gemm_i8_workspace_bytes(M, N, K))
 
 
+def ac_gemm_i8_planned_workspace_bytes(M: int, N: int, K: int, tile: int, splits: int) -> int:
+    return int(lib().ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits))
+
+
+def ac_gemm_i8_auto_plan(M: int, N: int, K: int, have_workspace: bool = True):
+    """(tile, splits) that ac_gemm_i8 chooses for this shape."""
+    tile, splits = ctypes.c_int32(0), ctypes.c_int32(0)
+    lib().ac_gemm_i8_auto_plan(M, N, K, int(bool(have_workspace)), ctypes.byref(tile), ctypes.byref(splits))
+    return tile.value, splits.value
+
+
+def ac_gemm_bf16_auto_plan(M: int, N: int, K: int):
+    """(tile, splits) that ac_gemm_bf16 chooses for this shape."""
+    tile, splits = ctypes.c_int32(0), ctypes.c_int32(0)
+    lib().ac_gemm_bf16_auto_plan(M, N, K, ctypes.byref(tile), ctypes.byref(splits))
+    return tile.value, splits.value
+
+
 def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
@@ -103,8 +135,7 @@ def _ws(workspace):
     return _ptr(workspace), workspace.numel() * workspace.element_size()
 
 
-def ac_gemm_i8(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, workspace=None, stream=None):
-    """C[M,N] int8 = stage(A[M,K] . B[K,N] + bias); bias is None, (N,) or (M,N) int32.  Returns C."""
+def _gemm_i8_args(A, B, bias, C):
     _check2d(A, torch.int8, "A")
     _check2d(B, torch.int8, "B")
     _check2d(C, torch.int8, "C")
@@ -122,11 +153,24 @@ def ac_gemm_i8(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, workspace=None
             bias_ld = bias.stride(0)
         elif tuple(bias.shape) != (N,) or (N > 1 and bias.stride(0) != 1):
             raise ValueError("bias vector must have N contiguous entries")
+    return [_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(bias), bias_ld, _ptr(C), C.stride(0), M, N, K]
+
+
+def ac_gemm_i8(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, workspace=None, stream=None):
+    """C[M,N] int8 = stage(A[M,K] . B[K,N] + bias); bias is None, (N,) or (M,N) int32.  Returns C."""
     wp, wb = _ws(workspace)
-    st = lib().ac_gemm_i8(_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(bias), bias_ld, _ptr(C), C.stride(0),
-                          M, N, K, shift, act, wp, wb, _stream(stream))
+    st = lib().ac_gemm_i8(*_gemm_i8_args(A, B, bias, C), shift, act, wp, wb, _stream(stream))
     if st != AC_OK:
         raise AcError(st, "ac_gemm_i8")
+    return C
+
+
+def ac_gemm_i8_planned(A, B, bias, C, shift: int, act: int, tile: int, splits: int, workspace=None, stream=None):
+    """ac_gemm_i8 with the block tile (64, 128, 256) and the K split named by the caller.  Returns C."""
+    wp, wb = _ws(workspace)
+    st = lib().ac_gemm_i8_planned(*_gemm_i8_args(A, B, bias, C), shift, act, wp, wb, tile, splits, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_gemm_i8_planned")
     return C
 
 
@@ -153,8 +197,7 @@ def ac_conv2d_i8(x, w, bias, out, stride: int, pad: int, shift: int, act: int = 
     return out
 
 
-def ac_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, stream=None):
-    """C[M,N] fp32 = alpha * A[M,K] . B[K,N] + beta * C; A, B are bf16 (torch.bfloat16, or int16/uint16 bit patterns)."""
+def _gemm_bf16_args(A, B, C):
     ok = (torch.bfloat16, torch.int16, torch.uint16)
     for t, name in ((A, "A"), (B, "B")):
         if t.dtype not in ok or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or not t.is_cuda:
@@ -164,10 +207,22 @@ def ac_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, stream=None):
     N = B.shape[1]
     if B.shape[0] != K or tuple(C.shape) != (M, N):
         raise ValueError("shape mismatch")
-    st = lib().ac_gemm_bf16(_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(C), C.stride(0), M, N, K,
-                            float(alpha), float(beta), _stream(stream))
+    return [_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(C), C.stride(0), M, N, K]
+
+
+def ac_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, stream=None):
+    """C[M,N] fp32 = alpha * A[M,K] . B[K,N] + beta * C; A, B are bf16 (torch.bfloat16, or int16/uint16 bit patterns)."""
+    st = lib().ac_gemm_bf16(*_gemm_bf16_args(A, B, C), float(alpha), float(beta), _stream(stream))
     if st != AC_OK:
         raise AcError(st, "ac_gemm_bf16")
+    return C
+
+
+def ac_gemm_bf16_planned(A, B, C, alpha: float, beta: float, tile: int, splits: int, stream=None):
+    """ac_gemm_bf16 with the block tile (64, 128, 256) and the K split named by the caller.  Returns C."""
+    st = lib().ac_gemm_bf16_planned(*_gemm_bf16_args(A, B, C), float(alpha), float(beta), tile, splits, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_gemm_bf16_planned")
     return C
 
 

@@ -56,6 +56,47 @@ def test_validation_without_gpu():
     assert ops.ac_gemm_i8_workspace_bytes(0, 8, 8) == 0
 
 
+def test_planned_entry_validation_without_gpu():
+    """Tile / split arguments of the planned launches are checked on the host before anything else runs."""
+    L = ops.lib()
+    p = 0x1000  # never dereferenced
+    i8 = lambda tile, splits, K=4096, ws=None, wsb=0: L.ac_gemm_i8_planned(
+        p, K, p + 256, 64, None, 0, p + 512, 64, 64, 64, K, 0, 0, ws, wsb, tile, splits, None)
+    assert i8(100, 1) == ops.AC_ERR_PLAN          # unknown tile
+    assert i8(64, 0) == ops.AC_ERR_PLAN           # no slices
+    assert i8(64, 33) == ops.AC_ERR_PLAN          # 4096 bytes of K are 32 tiles of 128 bytes
+    assert i8(256, 65) == ops.AC_ERR_PLAN         # ... and 64 tiles of 64 bytes
+    assert i8(64, 4) == ops.AC_ERR_WORKSPACE      # a split needs the workspace
+    need = ops.ac_gemm_i8_planned_workspace_bytes(64, 64, 4096, 64, 4)
+    assert need == 4 * 64 * 64 * 4
+    assert i8(64, 4, ws=p + 4096, wsb=need - 1) == ops.AC_ERR_WORKSPACE
+    # slices hold whole K tiles: 32 tiles over 5 slices are 7 per slice, which leaves 5 slices; over 12 are 3 -> 11
+    assert ops.ac_gemm_i8_planned_workspace_bytes(64, 64, 4096, 64, 5) == 5 * 64 * 64 * 4
+    assert ops.ac_gemm_i8_planned_workspace_bytes(64, 64, 4096, 64, 12) == 11 * 64 * 64 * 4
+    assert ops.ac_gemm_i8_planned_workspace_bytes(64, 64, 4096, 64, 1) == 0
+    assert ops.ac_gemm_i8_planned_workspace_bytes(64, 64, 4096, 7, 4) == 0
+    # a split over operands that cannot take the direct-to-LDS kernels (K not a multiple of 16)
+    assert L.ac_gemm_i8_planned(p, 1000, p + 256, 64, None, 0, p + 512, 64, 64, 64, 1000, 0, 0, p + 4096, 1 << 20, 64, 2, None) == ops.AC_ERR_PLAN
+    bf = lambda tile, splits, K=4096: L.ac_gemm_bf16_planned(p, K, p + 256, 64, p + 512, 64, 64, 64, K, 1.0, 0.0, tile, splits, None)
+    assert bf(32, 1) == ops.AC_ERR_PLAN
+    assert bf(128, 65) == ops.AC_ERR_PLAN         # 8192 bytes of K are 64 tiles of 128 bytes
+    assert bf(64, -1) == ops.AC_ERR_PLAN
+    assert L.ac_gemm_bf16_planned(p, 1004, p + 256, 64, p + 512, 64, 64, 64, 1004, 1.0, 0.0, 64, 2, None) == ops.AC_ERR_PLAN
+    assert "tile" in ops.status_string(ops.AC_ERR_PLAN)
+
+
+def test_auto_plans_are_host_arithmetic():
+    # the benchmark shapes: big square problems take the 256 tile; narrow ones fall back to 64
+    assert ops.ac_gemm_bf16_auto_plan(4096, 4096, 4096) == (256, 1)
+    assert ops.ac_gemm_i8_auto_plan(3136, 64, 576) == (64, 1)
+    tile, splits = ops.ac_gemm_i8_auto_plan(49, 2048, 4608, True)
+    assert tile == 64 and splits > 1
+    assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, False) == (64, 1)
+    assert ops.ac_gemm_i8_workspace_bytes(49, 2048, 4608) == ops.ac_gemm_i8_planned_workspace_bytes(49, 2048, 4608, tile, splits)
+    tile, splits = ops.ac_gemm_bf16_auto_plan(256, 256, 524288)
+    assert tile == 64 and splits > 1
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ops, "_lib", None)
     monkeypatch.setattr(ops, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libac_mi355x.so"))

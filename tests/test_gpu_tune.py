@@ -1,0 +1,113 @@
+"""GPU parity of the planned launches (every tile / K-split candidate against the oracle) and of the plan
+search built on them (Section 3.3: correctness gate first, then latency; Sections 3.5 / 5: schedule reuse)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import dev, host, rel_fro
+from paper_2505_18574_amd import inputs, ops, tune
+
+pytestmark = pytest.mark.gpu
+
+
+def workspace_for(M, N, K, plan):
+    n = ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, *plan)
+    return torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 1024, 1024), (49, 2048, 4608), (300, 272, 656), (512, 768, 768), (64, 64, 16)])
+def test_every_int8_plan_is_bit_exact(M, N, K):
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + N + K)
+    want = oracle.gemm_i8(A, B, bias, 10, 1)
+    Ad, Bd, bd = dev(A), dev(B), dev(bias)
+    plans = tune.all_plans("i8", M, N, K)
+    assert len(plans) >= 3
+    for plan in plans:
+        print("plan", plan, flush=True)
+        C = torch.full((M, N), 55, dtype=torch.int8, device="cuda")
+        ops.ac_gemm_i8_planned(Ad, Bd, bd, C, 10, 1, plan[0], plan[1], workspace=workspace_for(M, N, K, plan))
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(C), want, err_msg=f"plan {plan}")
+
+
+def test_int8_plan_with_matrix_bias_and_odd_split():
+    M, N, K = 100, 48, 2000
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=77, bias_matrix=True)
+    want = oracle.gemm_i8(A, B, bias, 9, 0)
+    for plan in [(64, 3), (128, 5), (256, 7), (64, 16)]:
+        C = torch.zeros((M, N), dtype=torch.int8, device="cuda")
+        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, 9, 0, plan[0], plan[1], workspace=workspace_for(M, N, K, plan))
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(C), want, err_msg=f"plan {plan}")
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 8192), (100, 72, 4104), (512, 384, 1024)])
+def test_every_bf16_plan_within_bound(M, N, K):
+    A, B = inputs.gemm_bf16_inputs(M, N, K, seed=M + K)
+    rng = np.random.default_rng(5)
+    C_in = rng.standard_normal((M, N)).astype(np.float32)
+    Aa = np.abs(inputs.bf16_bits_to_f32(A).astype(np.float64))
+    Ba = np.abs(inputs.bf16_bits_to_f32(B).astype(np.float64))
+    for alpha, beta in ((1.0, 0.0), (-0.5, 2.0)):
+        want = oracle.gemm_bf16(A, B, alpha, beta, C_in if beta else None)
+        bound = 4.0 * (K + 2) * 2.0 ** -24 * (abs(alpha) * (Aa @ Ba) + abs(beta) * np.abs(C_in)) + 1e-30
+        for plan in tune.all_plans("bf16", M, N, K):
+            print("plan", plan, alpha, beta, flush=True)
+            C = dev(C_in).clone() if beta else torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+            ops.ac_gemm_bf16_planned(dev(A), dev(B), C, alpha, beta, plan[0], plan[1])
+            torch.cuda.synchronize()
+            got = host(C)
+            assert rel_fro(got, want) <= 1e-3, plan
+            assert (np.abs(got - want) <= bound).all(), plan
+
+
+def test_split_refused_for_operands_off_the_fast_path():
+    A = torch.zeros((64, 1000), dtype=torch.int8, device="cuda")  # K not a multiple of 16
+    B = torch.zeros((1000, 64), dtype=torch.int8, device="cuda")
+    C = torch.zeros((64, 64), dtype=torch.int8, device="cuda")
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ops.AcError) as e:
+        ops.ac_gemm_i8_planned(A, B, None, C, 0, 0, 64, 2, workspace=ws)
+    assert e.value.status == ops.AC_ERR_PLAN
+    ops.ac_gemm_i8_planned(A, B, None, C, 0, 0, 64, 1)  # the unsplit plan runs on the generic kernel
+    torch.cuda.synchronize()
+
+
+def test_search_int8_with_oracle_gate_and_reuse():
+    """Beam search from the library's own plan, then reuse of the recorded plan on the two reuse targets of
+    the row-dominant family (Section 5, Table 2); the gate is the oracle, so every timed candidate is exact."""
+    book = tune.PlanBook()
+    base, *targets = [inputs.GEMM_I8_PAPER[i] for i in inputs.GEMM_I8_REUSE_FAMILIES[2]]
+    for case in (base, *targets):
+        A, B, bias = inputs.gemm_i8_case_inputs(case)
+        want = torch.from_numpy(oracle.gemm_i8(A, B, bias, case.shift, case.act)).cuda()
+        C = torch.empty((case.M, case.N), dtype=torch.int8, device="cuda")
+        gate = lambda got: bool(torch.equal(got, want))
+        start = book.related("i8", case.M, case.N, case.K) or None
+        res = tune.tune_gemm_i8(dev(A), dev(B), dev(bias), C, case.shift, case.act, gate=gate, start=start, iterations=2 if start else 4)
+        print(case.name, "best", res.best, f"{res.best_us:.2f} us", [(t.plan, t.correct, t.us and round(t.us, 2)) for t in res.trials], flush=True)
+        assert all(t.correct for t in res.trials)
+        auto = tune.normalise("i8", case.K, ops.ac_gemm_i8_auto_plan(case.M, case.N, case.K, True))
+        if start is None:
+            assert auto in [t.plan for t in res.trials]
+        assert res.best_us <= min(t.us for t in res.trials) + 1e-9
+        book.record("i8", case.M, case.N, case.K, res.best)
+        # the winner, run once more, still matches the oracle
+        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C.zero_(), case.shift, case.act, *res.best,
+                               workspace=workspace_for(case.M, case.N, case.K, res.best))
+        torch.cuda.synchronize()
+        assert torch.equal(C, want)
+    assert len(book.plans) == 3
+
+
+def test_search_bf16_exhaustive_default_gate():
+    M, N, K = 256, 256, 16384
+    A, B = inputs.gemm_bf16_inputs(M, N, K, seed=9)
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    res = tune.tune_gemm_bf16(dev(A), dev(B), C, exhaustive=True)
+    print("bf16", (M, N, K), "best", res.best, f"{res.best_us:.2f} us", [(t.plan, t.us and round(t.us, 2)) for t in res.trials], flush=True)
+    assert all(t.correct for t in res.trials) and len(res.trials) == len(tune.all_plans("bf16", M, N, K))
+    ops.ac_gemm_bf16_planned(dev(A), dev(B), C, 1.0, 0.0, *res.best)
+    torch.cuda.synchronize()
+    assert rel_fro(host(C), oracle.gemm_bf16(A, B)) <= 1e-3

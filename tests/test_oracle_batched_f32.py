@@ -1,4 +1,4 @@
-"""Pins for the batched small fp32 oracle and the TinyMPC forward recurrence (Section 5.1.3, Appendix D.2)."""
+"""Pins for the batched small fp32 oracle and the TinyMPC forward recurrence (Section 4.4.3, Appendix D.2)."""
 import numpy as np
 import pytest
 

@@ -1,4 +1,4 @@
-"""Pins for the int8 convolution oracle (direct definition; Section 5.1.2 workload)."""
+"""Pins for the int8 convolution oracle (direct definition; Section 4.4.2 workload)."""
 import numpy as np
 import pytest
 

@@ -1,4 +1,4 @@
-"""Pins for the int8 GEMM oracle (Fig. 2 contraction, Fig. 13 bias, Fig. 14 output stage)."""
+"""Pins for the int8 GEMM oracle (Fig. 2 contraction, Fig. 14 bias, Fig. 15 output stage)."""
 import numpy as np
 import pytest
 

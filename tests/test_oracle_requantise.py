@@ -1,4 +1,4 @@
-"""Pins for the oracle's scale-down / saturate / ReLU output stage (Appendix B, Figs. 13-14)."""
+"""Pins for the oracle's scale-down / saturate / ReLU output stage (Appendix C, Figs. 14-15)."""
 from fractions import Fraction
 
 import numpy as np

@@ -1,0 +1,75 @@
+"""Host logic of the plan search: candidate enumeration, the beam rule and schedule reuse (no device needed)."""
+import torch
+
+from paper_2505_18574_amd import tune
+
+
+def test_k_tiles_and_normalise():
+    assert tune.k_tiles("i8", 4096, 64) == 32 and tune.k_tiles("i8", 4096, 256) == 64
+    assert tune.k_tiles("bf16", 4096, 128) == 64 and tune.k_tiles("bf16", 4100, 256) == 129
+    # 32 K tiles over 12 slices: 3 tiles each, so only 11 slices hold work
+    assert tune.normalise("i8", 4096, (64, 12)) == (64, 11)
+    assert tune.normalise("i8", 4096, (64, 1)) == (64, 1)
+    assert tune.normalise("i8", 64, (256, 8)) == (256, 1)
+
+
+def test_all_plans_and_neighbours():
+    plans = tune.all_plans("i8", 128, 1024, 1024)
+    assert (64, 1) in plans and (128, 8) in plans and (256, 16) in plans
+    assert all(tune.valid("i8", 128, 1024, 1024, p) for p in plans)
+    assert (64, 16) not in plans  # 1024 bytes of K are 8 tiles of 128 bytes
+    assert len(set(plans)) == len(plans)
+    nb = tune.neighbours("i8", 128, 1024, 1024, (128, 2))
+    assert set(nb) == {(64, 2), (256, 2), (128, 1), (128, 4)}
+    assert tune.neighbours("bf16", 4096, 4096, 16, (256, 1)) == [(128, 1)]  # one K tile: nothing to split
+    # a split that would need more than the workspace cap is not offered
+    assert not tune.valid("i8", 16384, 16384, 4096, (64, 2))
+
+
+class FakeProblem(tune._Problem):
+    """A cost model in place of the device: latency by plan, and a set of plans whose output is 'wrong'."""
+
+    def __init__(self, cost, wrong=()):
+        self.launched = []
+        out = torch.zeros(1)
+
+        def run(plan):
+            self.launched.append(plan)
+            out[0] = -1.0 if plan in wrong else 1.0
+
+        super().__init__("i8", 128, 1024, 1024, run, lambda: out.fill_(1.0), out, exact=True,
+                         sync=lambda: None, measure=lambda fn: cost(self.launched[-1]))
+
+
+def test_beam_keeps_correct_and_faster_candidates_only():
+    cost = lambda p: {64: 30.0, 128: 20.0, 256: 40.0}[p[0]] / (1 + 0.5 * (p[1] > 1)) + p[1]
+    # (128, 2) would be the fastest plan but produces a wrong result: it must never be chosen
+    prob = FakeProblem(cost, wrong={(128, 2)})
+    res = tune._search(prob, None, [(64, 1)], beam=2, iterations=6, exhaustive=False)
+    assert res.best != (128, 2)
+    assert {t.plan: t.correct for t in res.trials}[(128, 2)] is False
+    want = min((p for p in tune.all_plans("i8", 128, 1024, 1024) if p != (128, 2)), key=cost)
+    full = tune._search(FakeProblem(cost, wrong={(128, 2)}), None, [], 1, 0, exhaustive=True)
+    assert full.best == want and abs(full.best_us - cost(want)) < 1e-9
+    assert res.best_us <= cost((64, 1))  # the beam never ends worse than its seed
+
+
+def test_beam_stops_when_no_child_improves():
+    prob = FakeProblem(lambda p: 10.0 + abs(p[0] - 128) + p[1])  # (128, 1) is a strict local and global minimum
+    res = tune._search(prob, None, [(128, 1)], beam=3, iterations=5, exhaustive=False)
+    assert res.best == (128, 1)
+    assert len(res.trials) == 1 + len(tune.neighbours("i8", 128, 1024, 1024, (128, 1)))
+
+
+def test_plan_book_reuse_rule(tmp_path):
+    book = tune.PlanBook()
+    book.record("i8", 1024, 1024, 1024, (128, 1))
+    book.record("i8", 12544, 64, 256, (64, 1))
+    book.record("bf16", 512, 512, 512, (64, 2))
+    assert book.related("i8", 512, 512, 512) == [(128, 1)]        # same aspect ratio
+    assert book.related("i8", 6272, 64, 256) == [(64, 1)]         # two dimensions in common
+    assert book.related("i8", 6272, 128, 64) == []
+    assert book.related("bf16", 1024, 1024, 1024) == [(64, 2)]
+    path = str(tmp_path / "plans.json")
+    book.save(path)
+    assert tune.PlanBook.load(path).plans == book.plans

@@ -213,36 +213,50 @@ def cpu_baseline():
             "sample": "; ".join(parts), "seconds": round(total_s, 3)}
 
 
-def supplementary(stream):
+def supplementary(stream, only=None):
     """Scaled-up runs of the same int8 kernels (NOT workload configurations): they show the asymptotic MFMA
-    fraction that the small workload shapes cannot reach per launch."""
+    fraction that the small workload shapes cannot reach per launch.  `only`: just the lines whose name contains it."""
     out = []
+    want = lambda name: only is None or only in name
     with torch.cuda.stream(stream):
-        M = N = K = 8192
         g = torch.Generator(device="cuda").manual_seed(1)
-        A = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda", generator=g)
-        B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda", generator=g)
-        bias = torch.randint(-(1 << 15), 1 << 15, (N,), dtype=torch.int32, device="cuda", generator=g)
-        C = torch.empty((M, N), dtype=torch.int8, device="cuda")
-        w = Workload("supplementary_gemm_i8_8192", "gemm_i8", "i8", 2 * M * N * K, 0, lambda: ops.ac_gemm_i8(A, B, bias, C, 12, 1), "")
-        ms = isolated_time(w, stream, reps=5, rounds=3)
-        out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"]})
+        if want("supplementary_gemm_i8_8192"):
+            M = N = K = 8192
+            A = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda", generator=g)
+            B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda", generator=g)
+            bias = torch.randint(-(1 << 15), 1 << 15, (N,), dtype=torch.int32, device="cuda", generator=g)
+            C = torch.empty((M, N), dtype=torch.int8, device="cuda")
+            w = Workload("supplementary_gemm_i8_8192", "gemm_i8", "i8", 2 * M * N * K, 0, lambda: ops.ac_gemm_i8(A, B, bias, C, 12, 1), "")
+            ms = isolated_time(w, stream, reps=5, rounds=3)
+            out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"]})
+            del A, B, C
         for case in inputs.CONV_I8:
             Nb = 256
+            name = "supplementary_" + case.name + "_Nb256"
+            if not want(name):
+                continue
             x = torch.randint(-128, 128, (Nb, case.H, case.W, case.Cin), dtype=torch.int8, device="cuda", generator=g)
             wt = torch.randint(-128, 128, (case.KH, case.KW, case.Cin, case.Cout), dtype=torch.int8, device="cuda", generator=g)
             bs = torch.randint(-(1 << 15), 1 << 15, (case.Cout,), dtype=torch.int32, device="cuda", generator=g)
             o = torch.empty((Nb, case.OH, case.OW, case.Cout), dtype=torch.int8, device="cuda")
             opsn = case.ops * Nb // case.Nb
-            ww = Workload("supplementary_" + case.name + "_Nb256", "conv2d_i8", "i8", opsn, 0,
+            ww = Workload(name, "conv2d_i8", "i8", opsn, 0,
                           lambda x=x, wt=wt, bs=bs, o=o, c=case: ops.ac_conv2d_i8(x, wt, bs, o, c.stride, c.pad, c.shift, c.act), "")
             ms = isolated_time(ww, stream, reps=5, rounds=3)
             out.append({"name": ww.name, "ms": ms, "tops": opsn / ms / 1e9, "frac_mfma_peak": opsn / ms / 1e9 / PEAK["i8"]})
             del x, wt, bs, o
-        del A, B, C
-        # GEMM shapes the paper names outside the workload configurations (reuse-study families, the GPU and
-        # accelerator studies' large GEMMs), on device-generated data of the same distributions
+    return out + supplementary_paper_shapes(stream, only)
+
+
+def supplementary_paper_shapes(stream, only):
+    """GEMM shapes the paper names outside the workload configurations (reuse-study families, the GPU and
+    accelerator studies' large GEMMs), on device-generated data of the same distributions."""
+    out = []
+    with torch.cuda.stream(stream):
+        g = torch.Generator(device="cuda").manual_seed(2)
         for case in inputs.GEMM_I8_PAPER:
+            if only is not None and only not in "paper_shape_" + case.name:
+                continue
             A = torch.randint(-128, 128, (case.M, case.K), dtype=torch.int8, device="cuda", generator=g)
             B = torch.randint(-128, 128, (case.K, case.N), dtype=torch.int8, device="cuda", generator=g)
             bias = torch.randint(-(1 << 15), 1 << 15, (case.N,), dtype=torch.int32, device="cuda", generator=g)
@@ -253,6 +267,8 @@ def supplementary(stream):
             out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"],
                         "plan": list(ops.ac_gemm_i8_auto_plan(case.M, case.N, case.K, False))})
         for case in inputs.GEMM_BF16_PAPER:
+            if only is not None and only not in "paper_shape_" + case.name:
+                continue
             A = torch.randn((case.M, case.K), device="cuda", generator=g).to(torch.bfloat16)
             B = torch.randn((case.K, case.N), device="cuda", generator=g).to(torch.bfloat16)
             C = torch.empty((case.M, case.N), dtype=torch.float32, device="cuda")
@@ -297,6 +313,12 @@ def main():
     if args.only:
         wl = [w for w in wl if args.only in w.name]
     stream = torch.cuda.Stream()
+    if args.only and not wl:  # a supplementary line by name (profiling aid): time it and stop
+        lines = supplementary(stream, args.only)
+        if not lines:
+            sys.exit(f"--only {args.only}: no workload or supplementary line of that name")
+        print(json.dumps({"supplementary_not_workloads": lines}))
+        return
     with torch.cuda.stream(stream):
         run_pass(wl)  # first launch of every kernel outside any capture
         stream.synchronize()

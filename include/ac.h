@@ -103,6 +103,19 @@ ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_
                            int32_t M, int32_t N, int32_t K, void* stream);
 
 /*
+ * ac_gemm_i8 with transposed operands (the A_transpose / B_transpose fields of config_ex, Appendix C Fig. 14).
+ *   trans_a != 0: A points to A^T, a K x M row-major array with row stride lda >= M
+ *   trans_b != 0: B points to B^T, an N x K row-major array with row stride ldb >= K
+ * Everything else (bias, output stage, C, error behaviour) as for ac_gemm_i8; with both flags zero the call
+ * is ac_gemm_i8 without a workspace.  Transposed operands run on a kernel of their own, which stages each
+ * operand in LDS in its memory order and transposes in the LDS read; it takes any alignment.
+ */
+ac_status ac_gemm_i8_t(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                       const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                       int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
+                       int32_t trans_a, int32_t trans_b, void* stream);
+
+/*
  * int8 2-D convolution (the convolution workload of Section 4.4.2) computed
  * as an implicit GEMM with M = Nb*OH*OW, N = Cout, K = KH*KW*Cin, followed by
  * the same output stage as ac_gemm_i8:

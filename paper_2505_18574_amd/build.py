@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libac_mi355x.so")
 
-SOURCES = ["api.cpp", "gemm_i8.hip", "gemm_bf16.hip", "batched_f32.hip", "tinympc_f32.hip"]
+SOURCES = ["api.cpp", "gemm_i8.hip", "gemm_i8_trans.hip", "gemm_bf16.hip", "batched_f32.hip", "tinympc_f32.hip"]
 
 # Packed-fp32 VALU forms are switched off for every device compile.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -129,6 +129,26 @@ ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
   return gemm_i8_entry(A, lda, B, ldb, bias, bias_ld, C, ldc, M, N, K, shift, act, workspace, workspace_bytes, false, 0, 0, stream);
 }
 
+ac_status ac_gemm_i8_t(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                       const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                       int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
+                       int32_t trans_a, int32_t trans_b, void* stream) {
+  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (ac_status s = check_stage(shift, act)) return s;
+  if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return AC_ERR_STRIDE;
+  if (bias_ld < 0 || (bias && bias_ld != 0 && bias_ld < N)) return AC_ERR_STRIDE;
+  if (M == 0 || N == 0) return AC_OK;
+  if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
+  if ((const void*)C == (const void*)A || (const void*)C == (const void*)B || (const void*)C == (const void*)bias)
+    return AC_ERR_ALIAS;
+  ac::GemmParams p = {};
+  p.A = A; p.B = B; p.C = C; p.bias = bias;
+  p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.bias_ld = bias_ld;
+  p.M = M; p.N = N; p.K = K; p.shift = shift; p.act = act;
+  p.splits = 1;
+  return ac::launch_gemm_i8_trans(p, trans_a != 0, trans_b != 0, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
 ac_status ac_gemm_i8_planned(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                              const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
                              int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,

@@ -77,6 +77,7 @@ bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan);
 hipError_t launch_tinympc_forward(const TinyMpcParams& p, hipStream_t stream);
 hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
 hipError_t launch_gemm_i8_acc32(const GemmParams& p, hipStream_t stream);
+hipError_t launch_gemm_i8_trans(const GemmParams& p, bool trans_a, bool trans_b, hipStream_t stream);
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream);
 hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
 hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream);

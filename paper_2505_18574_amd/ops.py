@@ -25,7 +25,7 @@ AC_ACT_NONE, AC_ACT_RELU = 0, 1
 # every symbol include/ac.h declares
 EXPORTS = ("ac_gemm_i8", "ac_gemm_i8_workspace_bytes", "ac_conv2d_i8", "ac_gemm_bf16", "ac_batched_gemm_f32",
            "ac_tinympc_forward_f32", "ac_gemm_i8_acc32",
-           "ac_gemm_i8_planned", "ac_gemm_i8_planned_workspace_bytes", "ac_gemm_bf16_planned",
+           "ac_gemm_i8_t", "ac_gemm_i8_planned", "ac_gemm_i8_planned_workspace_bytes", "ac_gemm_bf16_planned",
            "ac_gemm_i8_auto_plan", "ac_gemm_bf16_auto_plan",
            "ac_status_string", "ac_version")
 
@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.ac_gemm_i8_acc32.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp]
         L.ac_tinympc_forward_f32.restype = i32
         L.ac_tinympc_forward_f32.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, vp]
+        L.ac_gemm_i8_t.restype = i32
+        L.ac_gemm_i8_t.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, i32, i32, vp]
         L.ac_gemm_i8_planned.restype = i32
         L.ac_gemm_i8_planned.argtypes = L.ac_gemm_i8.argtypes[:-1] + [i32, i32, vp]
         L.ac_gemm_i8_planned_workspace_bytes.restype = sz
@@ -162,6 +164,32 @@ def ac_gemm_i8(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, workspace=None
     st = lib().ac_gemm_i8(*_gemm_i8_args(A, B, bias, C), shift, act, wp, wb, _stream(stream))
     if st != AC_OK:
         raise AcError(st, "ac_gemm_i8")
+    return C
+
+
+def ac_gemm_i8_t(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, trans_a: bool = False, trans_b: bool = False, stream=None):
+    """ac_gemm_i8 with A given as A^T (K x M) when trans_a and B as B^T (N x K) when trans_b.  Returns C."""
+    _check2d(A, torch.int8, "A")
+    _check2d(B, torch.int8, "B")
+    _check2d(C, torch.int8, "C")
+    K, M = (A.shape if trans_a else A.shape[::-1])
+    N, K2 = (B.shape if trans_b else B.shape[::-1])
+    if K2 != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    bias_ld = 0
+    if bias is not None:
+        if bias.dtype != torch.int32 or not bias.is_cuda:
+            raise ValueError("bias: expected int32 device tensor")
+        if bias.dim() == 2:
+            if tuple(bias.shape) != (M, N) or bias.stride(1) != 1:
+                raise ValueError("bias matrix must be M x N row-major")
+            bias_ld = bias.stride(0)
+        elif tuple(bias.shape) != (N,) or (N > 1 and bias.stride(0) != 1):
+            raise ValueError("bias vector must have N contiguous entries")
+    st = lib().ac_gemm_i8_t(_ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(bias), bias_ld, _ptr(C), C.stride(0),
+                            M, N, K, shift, act, int(bool(trans_a)), int(bool(trans_b)), _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_gemm_i8_t")
     return C
 
 

@@ -85,6 +85,18 @@ def test_planned_entry_validation_without_gpu():
     assert "tile" in ops.status_string(ops.AC_ERR_PLAN)
 
 
+def test_transposed_entry_validation_without_gpu():
+    L = ops.lib()
+    p = 0x1000  # never dereferenced
+    t = lambda lda, ldb, ta, tb: L.ac_gemm_i8_t(p, lda, p + 256, ldb, None, 0, p + 512, 8, 4, 8, 16, 0, 0, ta, tb, None)
+    assert t(15, 8, 0, 0) == ops.AC_ERR_STRIDE   # plain A: lda >= K = 16
+    assert t(3, 8, 1, 0) == ops.AC_ERR_STRIDE    # A^T is K x M: lda >= M = 4
+    assert t(4, 15, 1, 1) == ops.AC_ERR_STRIDE   # B^T is N x K: ldb >= K = 16
+    assert L.ac_gemm_i8_t(p, 4, p + 256, 16, None, 0, p + 512, 8, 4, 8, 16, 40, 0, 1, 1, None) == ops.AC_ERR_SHIFT
+    assert L.ac_gemm_i8_t(p, 4, p + 256, 16, None, 0, None, 8, 4, 8, 16, 0, 0, 1, 1, None) == ops.AC_ERR_NULL
+    assert L.ac_gemm_i8_t(None, 4, None, 16, None, 0, None, 8, 0, 8, 16, 0, 0, 1, 1, None) == ops.AC_OK
+
+
 def test_auto_plans_are_host_arithmetic():
     # the benchmark shapes: big square problems take the 256 tile; narrow ones fall back to 64
     assert ops.ac_gemm_bf16_auto_plan(4096, 4096, 4096) == (256, 1)

@@ -215,8 +215,11 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           aligned with ldc a multiple of 4.
  *           int8: slices leave int32 partial sums in `workspace`, which must hold
  *           ac_gemm_i8_planned_workspace_bytes() bytes; a second kernel sums them and applies the output stage.
- *           bf16: a first kernel sets C = beta * C, then every slice adds alpha * (its product) with fp32
- *           atomic adds, in no fixed order.
+ *           bf16, with a workspace of ac_gemm_bf16_planned_workspace_bytes() bytes: slices leave fp32 partial
+ *           products there and a second kernel sums them in slice order and applies alpha / beta (the result
+ *           is the same on every run).  bf16, workspace NULL / 0: a first kernel sets C = beta * C, then every
+ *           slice adds alpha * (its product) with fp32 atomic adds, in no fixed order (slow for large M * N).
+ *           Workspace rules as for ac_gemm_i8: 16-byte aligned, large enough, else AC_ERR_WORKSPACE.
  *   AC_ERR_PLAN: tile not one of the three, splits < 1 or larger than the number of K tiles, or splits > 1
  *           with operands that do not qualify.  Everything else as for the unplanned call.
  * ac_gemm_*_auto_plan report what the unplanned call would choose for a shape (pure host arithmetic).
@@ -228,7 +231,9 @@ ac_status ac_gemm_i8_planned(const int8_t* A, int64_t lda, const int8_t* B, int6
 size_t ac_gemm_i8_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits);
 ac_status ac_gemm_bf16_planned(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
                                float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
-                               float alpha, float beta, int32_t tile, int32_t splits, void* stream);
+                               float alpha, float beta, void* workspace, size_t workspace_bytes,
+                               int32_t tile, int32_t splits, void* stream);
+size_t ac_gemm_bf16_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits);
 void ac_gemm_i8_auto_plan(int32_t M, int32_t N, int32_t K, int32_t have_workspace, int32_t* tile, int32_t* splits);
 void ac_gemm_bf16_auto_plan(int32_t M, int32_t N, int32_t K, int32_t* tile, int32_t* splits);
 

@@ -51,6 +51,12 @@ size_t ac_gemm_i8_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32
   return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t);
 }
 
+size_t ac_gemm_bf16_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits) {
+  ac::GemmPlan plan;
+  if (M <= 0 || N <= 0 || K <= 0 || !ac::make_plan_bf16(K, tile, splits, &plan) || plan.splits <= 1) return 0;
+  return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float);
+}
+
 void ac_gemm_i8_auto_plan(int32_t M, int32_t N, int32_t K, int32_t have_workspace, int32_t* tile, int32_t* splits) {
   const ac::GemmPlan plan = ac::plan_gemm_i8(M < 0 ? 0 : M, N < 0 ? 0 : N, K < 0 ? 0 : K, have_workspace != 0);
   if (tile) *tile = plan.tile;
@@ -100,11 +106,16 @@ ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t l
 
 ac_status gemm_bf16_entry(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
                           float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
-                          float alpha, float beta, bool planned, int32_t tile, int32_t splits, void* stream) {
+                          float alpha, float beta, void* workspace, size_t workspace_bytes,
+                          bool planned, int32_t tile, int32_t splits, void* stream) {
   if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
   if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
   ac::GemmPlan plan;
   if (planned && !ac::make_plan_bf16(K, tile, splits, &plan)) return AC_ERR_PLAN;
+  if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;
+  if (workspace && (((uintptr_t)workspace & 15) != 0 ||
+                    workspace_bytes < ac_gemm_bf16_planned_workspace_bytes(M, N, K, tile, splits)))
+    return AC_ERR_WORKSPACE;
   if (M == 0 || N == 0) return AC_OK;
   if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
   if ((const void*)C == (const void*)A || (const void*)C == (const void*)B) return AC_ERR_ALIAS;
@@ -114,6 +125,7 @@ ac_status gemm_bf16_entry(const uint16_t* A, int64_t lda, const uint16_t* B, int
   p.lda = lda; p.ldb = ldb; p.ldc = ldc;
   p.M = M; p.N = N; p.K = K; p.alpha = alpha; p.beta = beta;
   p.splits = 1;
+  p.partial = (int32_t*)workspace;
   if (planned && plan.splits > 1 && !ac::gemm_bf16_fast_path(p)) return AC_ERR_PLAN;
   return ac::launch_gemm_bf16(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }
@@ -209,13 +221,14 @@ ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, i
 ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
                        float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
                        float alpha, float beta, void* stream) {
-  return gemm_bf16_entry(A, lda, B, ldb, C, ldc, M, N, K, alpha, beta, false, 0, 0, stream);
+  return gemm_bf16_entry(A, lda, B, ldb, C, ldc, M, N, K, alpha, beta, nullptr, 0, false, 0, 0, stream);
 }
 
 ac_status ac_gemm_bf16_planned(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
                                float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
-                               float alpha, float beta, int32_t tile, int32_t splits, void* stream) {
-  return gemm_bf16_entry(A, lda, B, ldb, C, ldc, M, N, K, alpha, beta, true, tile, splits, stream);
+                               float alpha, float beta, void* workspace, size_t workspace_bytes,
+                               int32_t tile, int32_t splits, void* stream) {
+  return gemm_bf16_entry(A, lda, B, ldb, C, ldc, M, N, K, alpha, beta, workspace, workspace_bytes, true, tile, splits, stream);
 }
 
 ac_status ac_batched_gemm_f32(const float* A, const float* B, float* C,

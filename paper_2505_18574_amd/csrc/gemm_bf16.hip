@@ -42,6 +42,22 @@ __global__ void __launch_bounds__(256) scale_c_f32_kernel(float* C, int64_t ldc,
   *c = beta == 0.f ? 0.f : beta * *c;
 }
 
+// Output stage of a split-K launch through a workspace: C = alpha * (sum of the slices, in slice order) + beta * C.
+__global__ void __launch_bounds__(256) splitk_reduce_f32_kernel(const GemmParams p) {
+  const int64_t quads_per_row = p.N / 4;  // fast path: N is a multiple of 8
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= (int64_t)p.M * quads_per_row) return;
+  const int m = (int)(q / quads_per_row);
+  const int n = (int)(q - (int64_t)m * quads_per_row) * 4;
+  const float* part = (const float*)p.partial;
+  v4f s = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < p.splits; k++) s += *(const v4f*)(part + ((int64_t)k * p.M + m) * p.N + n);
+  float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
+  v4f o = p.alpha * s;
+  if (p.beta != 0.f) o += p.beta * *(const v4f*)dst;
+  *(v4f*)dst = o;
+}
+
 bool gemm_bf16_fast_path(const GemmParams& p) {
   return (((uintptr_t)p.A & 15) == 0) && (((uintptr_t)p.B & 15) == 0) && (p.lda % 8 == 0) && (p.ldb % 8 == 0) &&
          (((uintptr_t)p.C & 15) == 0) && (p.ldc % 4 == 0) && (p.K % 8 == 0) && (p.N % 8 == 0);
@@ -61,7 +77,17 @@ hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const Gemm
   p.splits = plan.splits;
   p.kt_per_split = plan.kt_per_split;
   if (fast) {
-    if (plan.splits > 1) {
+    if (plan.splits > 1 && p.partial != nullptr) {  // slices through the caller's workspace, summed in a fixed order
+      hipError_t e;
+      if (plan.tile == 256) e = launch_dtl<TypeBF16, EpiloguePartialF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
+      else if (plan.tile == 128) e = launch_dtl<TypeBF16, EpiloguePartialF32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+      else e = launch_dtl<TypeBF16, EpiloguePartialF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
+      if (e != hipSuccess) return e;
+      const int64_t quads = (int64_t)p.M * (p.N / 4);
+      hipLaunchKernelGGL(splitk_reduce_f32_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, p);
+      return hipGetLastError();
+    }
+    if (plan.splits > 1) {  // no workspace: slices add into C with fp32 atomics
       const int64_t n = (int64_t)p.M * p.N;
       hipLaunchKernelGGL(scale_c_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (float*)p.C, p.ldc, p.M, p.N, p.beta);
       hipError_t e = hipGetLastError();

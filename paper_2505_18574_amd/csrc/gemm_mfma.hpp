@@ -320,6 +320,35 @@ struct EpilogueAtomicF32 {
   }
 };
 
+// Split-K partial products in fp32: slice `split` stores its raw accumulators to partial[split][M][N] (the
+// int32 workspace pointer reinterpreted); splitk_reduce_f32_kernel sums the slices in slice order and applies
+// alpha / beta, so the result does not depend on which slice finishes first.
+struct EpiloguePartialF32 {
+  struct Pre {};
+  static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
+  template <bool VEC>
+  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a, int split) {
+    if (m >= p.M || n >= p.N) return;
+    float* dst = (float*)p.partial + ((int64_t)split * p.M + m) * p.N + n;
+    if (VEC && n + 3 < p.N) {
+      *(v4f*)dst = (v4f){a[0], a[1], a[2], a[3]};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+        if (n + e < p.N) dst[e] = a[e];
+    }
+  }
+  template <class ACC>
+  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+      float a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      store4<true>(p, m, n, a4, split);
+    }
+  }
+};
+
 // A-operand addressing ----------------------------------------------------------
 // AMODE 0: A is an M x K matrix.  AMODE 1: A(m, k) is gathered from an NHWC image
 // (m -> (image, oh, ow), k -> (kh, kw, ci)), zero outside the image.

@@ -26,6 +26,7 @@ AC_ACT_NONE, AC_ACT_RELU = 0, 1
 EXPORTS = ("ac_gemm_i8", "ac_gemm_i8_workspace_bytes", "ac_conv2d_i8", "ac_gemm_bf16", "ac_batched_gemm_f32",
            "ac_tinympc_forward_f32", "ac_gemm_i8_acc32",
            "ac_gemm_i8_t", "ac_gemm_i8_planned", "ac_gemm_i8_planned_workspace_bytes", "ac_gemm_bf16_planned",
+           "ac_gemm_bf16_planned_workspace_bytes",
            "ac_gemm_i8_auto_plan", "ac_gemm_bf16_auto_plan",
            "ac_status_string", "ac_version")
 
@@ -69,7 +70,9 @@ def lib() -> ctypes.CDLL:
         L.ac_gemm_i8_planned_workspace_bytes.restype = sz
         L.ac_gemm_i8_planned_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
         L.ac_gemm_bf16_planned.restype = i32
-        L.ac_gemm_bf16_planned.argtypes = L.ac_gemm_bf16.argtypes[:-1] + [i32, i32, vp]
+        L.ac_gemm_bf16_planned.argtypes = L.ac_gemm_bf16.argtypes[:-1] + [vp, sz, i32, i32, vp]
+        L.ac_gemm_bf16_planned_workspace_bytes.restype = sz
+        L.ac_gemm_bf16_planned_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
         pi32 = ctypes.POINTER(i32)
         L.ac_gemm_i8_auto_plan.restype = None
         L.ac_gemm_i8_auto_plan.argtypes = [i32, i32, i32, i32, pi32, pi32]
@@ -100,6 +103,10 @@ def ac_gemm_i8_workspace_bytes(M: int, N: int, K: int) -> int:
 
 def ac_gemm_i8_planned_workspace_bytes(M: int, N: int, K: int, tile: int, splits: int) -> int:
     return int(lib().ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits))
+
+
+def ac_gemm_bf16_planned_workspace_bytes(M: int, N: int, K: int, tile: int, splits: int) -> int:
+    return int(lib().ac_gemm_bf16_planned_workspace_bytes(M, N, K, tile, splits))
 
 
 def ac_gemm_i8_auto_plan(M: int, N: int, K: int, have_workspace: bool = True):
@@ -246,9 +253,11 @@ def ac_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, stream=None):
     return C
 
 
-def ac_gemm_bf16_planned(A, B, C, alpha: float, beta: float, tile: int, splits: int, stream=None):
-    """ac_gemm_bf16 with the block tile (64, 128, 256) and the K split named by the caller.  Returns C."""
-    st = lib().ac_gemm_bf16_planned(*_gemm_bf16_args(A, B, C), float(alpha), float(beta), tile, splits, _stream(stream))
+def ac_gemm_bf16_planned(A, B, C, alpha: float, beta: float, tile: int, splits: int, workspace=None, stream=None):
+    """ac_gemm_bf16 with the block tile (64, 128, 256) and the K split named by the caller; a split sums through
+    `workspace` when one is given, else with atomic adds into C.  Returns C."""
+    wp, wb = _ws(workspace)
+    st = lib().ac_gemm_bf16_planned(*_gemm_bf16_args(A, B, C), float(alpha), float(beta), wp, wb, tile, splits, _stream(stream))
     if st != AC_OK:
         raise AcError(st, "ac_gemm_bf16_planned")
     return C

@@ -24,7 +24,7 @@ from . import ops
 Plan = Tuple[int, int]  # (tile, splits)
 TILES = (64, 128, 256)
 MAX_WORKGROUPS = 8192          # more slices than this only add reduction traffic
-MAX_WORKSPACE_BYTES = 1 << 30  # int8 partial sums the tuner is willing to allocate
+MAX_WORKSPACE_BYTES = 1 << 30  # partial sums (int32 / fp32, splits * M * N * 4 bytes) the tuner is willing to allocate
 
 
 def k_tiles(kind: str, K: int, tile: int) -> int:
@@ -51,7 +51,7 @@ def valid(kind: str, M: int, N: int, K: int, plan: Plan) -> bool:
     workgroups = ((M + tile - 1) // tile) * ((N + tile - 1) // tile) * splits
     if splits > 1 and workgroups > MAX_WORKGROUPS:
         return False
-    if kind == "i8" and splits > 1 and splits * M * N * 4 > MAX_WORKSPACE_BYTES:
+    if splits > 1 and splits * M * N * 4 > MAX_WORKSPACE_BYTES:
         return False
     return True
 
@@ -66,6 +66,22 @@ def all_plans(kind: str, M: int, N: int, K: int) -> List[Plan]:
             if q not in out:
                 out.append(q)
             s *= 2
+    return out
+
+
+def seed_plans(kind: str, M: int, N: int, K: int, auto: Plan, workgroups: int = 256) -> List[Plan]:
+    """Starting points of the beam: the library's own plan, plus for every tile the smallest power-of-two split
+    that gives every compute unit a workgroup (the beam only ever moves to a faster neighbour, so it needs a
+    start on each side of the tile-size trade-off)."""
+    out = [normalise(kind, K, auto)]
+    for tile in TILES:
+        tiles = ((M + tile - 1) // tile) * ((N + tile - 1) // tile)
+        s = 1
+        while tiles * s < workgroups and valid(kind, M, N, K, (tile, s * 2)):
+            s *= 2
+        q = normalise(kind, K, (tile, s))
+        if valid(kind, M, N, K, q) and q not in out:
+            out.append(q)
     return out
 
 
@@ -191,18 +207,25 @@ def _search(prob: _Problem, gate, start: Sequence[Plan], beam: int, iterations: 
     return TuneResult(best.plan, best.us, list(seen.values()))
 
 
-def _i8_problem(A, B, bias, C, shift: int, act: int) -> _Problem:
-    M, K = A.shape
-    N = B.shape[1]
-    ws_cache: Dict[int, torch.Tensor] = {}
+def _workspace_pool(device):
+    """workspace(nbytes) -> a device buffer of that size (None for 0), keeping only the latest one alive."""
+    cache: Dict[int, torch.Tensor] = {}
 
     def workspace(nbytes: int):
         if nbytes == 0:
             return None
-        if nbytes not in ws_cache:
-            ws_cache.clear()
-            ws_cache[nbytes] = torch.empty(nbytes, dtype=torch.uint8, device=A.device)
-        return ws_cache[nbytes]
+        if nbytes not in cache:
+            cache.clear()
+            cache[nbytes] = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        return cache[nbytes]
+
+    return workspace
+
+
+def _i8_problem(A, B, bias, C, shift: int, act: int) -> _Problem:
+    M, K = A.shape
+    N = B.shape[1]
+    workspace = _workspace_pool(A.device)
 
     def run(plan: Plan):
         ws = workspace(ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, plan[0], plan[1]))
@@ -219,18 +242,23 @@ def _bf16_problem(A, B, C, alpha: float, beta: float) -> _Problem:
         raise ValueError("tune with beta == 0: the candidates overwrite C between runs")
     M, K = A.shape
     N = B.shape[1]
-    run = lambda plan: ops.ac_gemm_bf16_planned(A, B, C, alpha, beta, plan[0], plan[1])
+    workspace = _workspace_pool(A.device)
+
+    def run(plan: Plan):  # K slices are summed through a workspace (same result on every run), not with atomics
+        ws = workspace(ops.ac_gemm_bf16_planned_workspace_bytes(M, N, K, plan[0], plan[1]))
+        ops.ac_gemm_bf16_planned(A, B, C, alpha, beta, plan[0], plan[1], workspace=ws)
+
     reference = lambda: ops.ac_gemm_bf16(A, B, C, alpha, beta)
     return _Problem("bf16", M, N, K, run, reference, C, exact=False)
 
 
 def tune_gemm_i8(A, B, bias, C, shift: int, act: int, gate=None, start: Optional[Iterable[Plan]] = None,
                  beam: int = 3, iterations: int = 4, exhaustive: bool = False) -> TuneResult:
-    """Best (tile, splits) for this int8 GEMM.  `start`: plans to seed the beam with (default: the library's
-    own choice); pass the plan recorded for a related shape to reuse it.  `gate(C) -> bool` decides whether a
+    """Best (tile, splits) for this int8 GEMM.  `start`: plans to seed the beam with (default: seed_plans());
+    pass the plan recorded for a related shape to reuse it.  `gate(C) -> bool` decides whether a
     candidate's output is correct.  C is overwritten."""
     prob = _i8_problem(A, B, bias, C, shift, act)
-    seeds = list(start) if start is not None else [ops.ac_gemm_i8_auto_plan(prob.M, prob.N, prob.K, True)]
+    seeds = list(start) if start is not None else seed_plans("i8", prob.M, prob.N, prob.K, ops.ac_gemm_i8_auto_plan(prob.M, prob.N, prob.K, True))
     return _search(prob, gate, seeds, beam, iterations, exhaustive)
 
 
@@ -238,7 +266,7 @@ def tune_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, gate=None, st
                    beam: int = 3, iterations: int = 4, exhaustive: bool = False) -> TuneResult:
     """Best (tile, splits) for this bf16 GEMM; arguments as for tune_gemm_i8."""
     prob = _bf16_problem(A, B, C, alpha, beta)
-    seeds = list(start) if start is not None else [ops.ac_gemm_bf16_auto_plan(prob.M, prob.N, prob.K)]
+    seeds = list(start) if start is not None else seed_plans("bf16", prob.M, prob.N, prob.K, ops.ac_gemm_bf16_auto_plan(prob.M, prob.N, prob.K))
     return _search(prob, gate, seeds, beam, iterations, exhaustive)
 
 

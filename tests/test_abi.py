@@ -77,11 +77,17 @@ def test_planned_entry_validation_without_gpu():
     assert ops.ac_gemm_i8_planned_workspace_bytes(64, 64, 4096, 7, 4) == 0
     # a split over operands that cannot take the direct-to-LDS kernels (K not a multiple of 16)
     assert L.ac_gemm_i8_planned(p, 1000, p + 256, 64, None, 0, p + 512, 64, 64, 64, 1000, 0, 0, p + 4096, 1 << 20, 64, 2, None) == ops.AC_ERR_PLAN
-    bf = lambda tile, splits, K=4096: L.ac_gemm_bf16_planned(p, K, p + 256, 64, p + 512, 64, 64, 64, K, 1.0, 0.0, tile, splits, None)
+    bf = lambda tile, splits, K=4096, ws=None, wsb=0: L.ac_gemm_bf16_planned(
+        p, K, p + 256, 64, p + 512, 64, 64, 64, K, 1.0, 0.0, ws, wsb, tile, splits, None)
     assert bf(32, 1) == ops.AC_ERR_PLAN
     assert bf(128, 65) == ops.AC_ERR_PLAN         # 8192 bytes of K are 64 tiles of 128 bytes
     assert bf(64, -1) == ops.AC_ERR_PLAN
-    assert L.ac_gemm_bf16_planned(p, 1004, p + 256, 64, p + 512, 64, 64, 64, 1004, 1.0, 0.0, 64, 2, None) == ops.AC_ERR_PLAN
+    assert L.ac_gemm_bf16_planned(p, 1004, p + 256, 64, p + 512, 64, 64, 64, 1004, 1.0, 0.0, None, 0, 64, 2, None) == ops.AC_ERR_PLAN
+    need = ops.ac_gemm_bf16_planned_workspace_bytes(64, 64, 4096, 128, 4)
+    assert need == 4 * 64 * 64 * 4
+    assert bf(128, 4, ws=p + 4096, wsb=need - 4) == ops.AC_ERR_WORKSPACE
+    assert bf(128, 4, ws=p + 4100, wsb=need) == ops.AC_ERR_WORKSPACE   # misaligned
+    assert bf(128, 4, ws=None, wsb=64) == ops.AC_ERR_WORKSPACE
     assert "tile" in ops.status_string(ops.AC_ERR_PLAN)
 
 

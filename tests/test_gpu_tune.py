@@ -53,13 +53,21 @@ def test_every_bf16_plan_within_bound(M, N, K):
         want = oracle.gemm_bf16(A, B, alpha, beta, C_in if beta else None)
         bound = 4.0 * (K + 2) * 2.0 ** -24 * (abs(alpha) * (Aa @ Ba) + abs(beta) * np.abs(C_in)) + 1e-30
         for plan in tune.all_plans("bf16", M, N, K):
-            print("plan", plan, alpha, beta, flush=True)
-            C = dev(C_in).clone() if beta else torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
-            ops.ac_gemm_bf16_planned(dev(A), dev(B), C, alpha, beta, plan[0], plan[1])
-            torch.cuda.synchronize()
-            got = host(C)
-            assert rel_fro(got, want) <= 1e-3, plan
-            assert (np.abs(got - want) <= bound).all(), plan
+            for with_ws in (False, True):  # slices added into C with atomics / summed through a workspace
+                print("plan", plan, alpha, beta, with_ws, flush=True)
+                nbytes = ops.ac_gemm_bf16_planned_workspace_bytes(M, N, K, *plan) if with_ws else 0
+                ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
+                C = dev(C_in).clone() if beta else torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+                ops.ac_gemm_bf16_planned(dev(A), dev(B), C, alpha, beta, plan[0], plan[1], workspace=ws)
+                torch.cuda.synchronize()
+                got = host(C)
+                assert rel_fro(got, want) <= 1e-3, plan
+                assert (np.abs(got - want) <= bound).all(), plan
+                if with_ws and nbytes:  # the workspace path sums in slice order: two runs agree bit for bit
+                    C2 = dev(C_in).clone() if beta else torch.empty((M, N), dtype=torch.float32, device="cuda")
+                    ops.ac_gemm_bf16_planned(dev(A), dev(B), C2, alpha, beta, plan[0], plan[1], workspace=ws)
+                    torch.cuda.synchronize()
+                    assert torch.equal(C, C2), plan
 
 
 def test_split_refused_for_operands_off_the_fast_path():
@@ -108,6 +116,8 @@ def test_search_bf16_exhaustive_default_gate():
     res = tune.tune_gemm_bf16(dev(A), dev(B), C, exhaustive=True)
     print("bf16", (M, N, K), "best", res.best, f"{res.best_us:.2f} us", [(t.plan, t.us and round(t.us, 2)) for t in res.trials], flush=True)
     assert all(t.correct for t in res.trials) and len(res.trials) == len(tune.all_plans("bf16", M, N, K))
-    ops.ac_gemm_bf16_planned(dev(A), dev(B), C, 1.0, 0.0, *res.best)
+    nbytes = ops.ac_gemm_bf16_planned_workspace_bytes(M, N, K, *res.best)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
+    ops.ac_gemm_bf16_planned(dev(A), dev(B), C, 1.0, 0.0, *res.best, workspace=ws)
     torch.cuda.synchronize()
     assert rel_fro(host(C), oracle.gemm_bf16(A, B)) <= 1e-3

@@ -26,6 +26,16 @@ def test_all_plans_and_neighbours():
     assert not tune.valid("i8", 16384, 16384, 4096, (64, 2))
 
 
+def test_seed_plans_cover_every_tile():
+    # one 256 x 256 output tile with a very deep K: each tile size starts from the split that fills 256 CUs
+    seeds = tune.seed_plans("bf16", 256, 256, 524288, (64, 16))
+    assert seeds == [(64, 16), (128, 64), (256, 256)]
+    # a shape with plenty of tiles starts unsplit on every tile size; the library's plan comes first, once
+    assert tune.seed_plans("i8", 4096, 4096, 4096, (256, 1)) == [(256, 1), (64, 1), (128, 1)]
+    # splits never exceed the K tiles of the tile's kernel
+    assert tune.seed_plans("i8", 64, 64, 256, (64, 1)) == [(64, 1), (64, 2), (128, 2), (256, 4)]
+
+
 class FakeProblem(tune._Problem):
     """A cost model in place of the device: latency by plan, and a set of plans whose output is 'wrong'."""
 

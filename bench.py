@@ -9,6 +9,11 @@ so that host launch overhead does not hide the kernels.
 
 Prints ONE JSON line: whole-step throughput, per-workload rates and roofline fractions, the roofline
 record of the dominant kernel, and the CPU oracle timed on a bounded sample of the same workloads.
+
+Per workload: `ms_in_pass` is the latency of a single eager launch inside a pass (device events around it:
+includes the host's launch gap, which dominates the microsecond-sized int8 kernels); `ms_isolated_warm` /
+`ms_isolated_warm_min` are the median / minimum over five timed regions of at least 20 ms of back-to-back
+launches of that workload replayed from a HIP graph.
 """
 from __future__ import annotations
 
@@ -125,23 +130,38 @@ def per_kernel_times(wl, steps, stream):
     return acc / steps  # ms
 
 
-def isolated_time(w, stream, reps=20, rounds=5):
-    """Back-to-back launches of one workload, replayed from a graph: median ms per launch (warm caches)."""
+MIN_REGION_MS = 20.0  # every timed region of isolated_time is at least this long
+
+
+def isolated_stats(w, stream, reps=20, rounds=5):
+    """Back-to-back launches of one workload (warm caches): 10 warm-up launches, then `rounds` timed regions,
+    each a HIP graph of `reps` launches replayed until the region is at least MIN_REGION_MS long, between two
+    events on the launch stream.  Returns (median, min) ms per launch over the rounds."""
     with torch.cuda.stream(stream):
-        w.launch()
+        for _ in range(10):
+            w.launch()
         stream.synchronize()
         g = capture(lambda: [w.launch() for _ in range(reps)], stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
         g.replay()
+        e1.record(stream)
         stream.synchronize()
+        replays = max(1, int(np.ceil(MIN_REGION_MS / max(e0.elapsed_time(e1), 1e-3))))
         ts = []
         for _ in range(rounds):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            g.replay()
+            for _ in range(replays):
+                g.replay()
             e1.record(stream)
             stream.synchronize()
-            ts.append(e0.elapsed_time(e1) / reps)
-    return float(np.median(ts))
+            ts.append(e0.elapsed_time(e1) / (reps * replays))
+    return float(np.median(ts)), float(np.min(ts))
+
+
+def isolated_time(w, stream, reps=20, rounds=5):
+    return isolated_stats(w, stream, reps, rounds)[0]
 
 
 def kernel_source_digest():
@@ -344,14 +364,14 @@ def main():
 
     per = []
     for w, ms in zip(wl, kt):
-        iso = isolated_time(w, stream)
+        iso, iso_min = isolated_stats(w, stream)
         rate = w.ops / ms / 1e9
         peak = PEAK[w.dtype]
         t_mfma_us = w.ops / (peak * 1e12) * 1e6
         t_hbm_us = w.bytes / (HBM_PEAK_GBS * 1e9) * 1e6
         per.append({
             "name": w.name, "dtype": w.dtype, "ops": w.ops, "bytes": w.bytes,
-            "ms_in_pass": round(float(ms), 5), "ms_isolated_warm": round(iso, 5),
+            "ms_in_pass": round(float(ms), 5), "ms_isolated_warm": round(iso, 5), "ms_isolated_warm_min": round(iso_min, 5),
             "tops_in_pass": round(rate, 2), "tops_isolated_warm": round(w.ops / iso / 1e9, 2),
             "frac_mfma_peak": round(rate / peak, 4) if w.dtype != "f32" else None,
             "gbs_in_pass": round(w.bytes / ms / 1e6, 1), "frac_hbm_peak": round(w.bytes / ms / 1e6 / HBM_PEAK_GBS, 4),

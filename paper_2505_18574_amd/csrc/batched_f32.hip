@@ -8,7 +8,6 @@
 // stores are coalesced as well.
 #include "common.hpp"
 
-#include <stdlib.h>
 
 namespace ac {
 
@@ -246,16 +245,10 @@ hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream) {
   auto al = [](const void* q) { return q == nullptr || ((uintptr_t)q & 15) == 0; };
   const bool vec = al(p.A) && al(p.B) && al(p.C) && al(p.x) && al(p.d);
   const int n = p.n;
-  // items per workgroup: 32 for the 12 x 12 case (39 KB of LDS, 4 workgroups per CU), 16 otherwise
-  static const int g12 = getenv("AC_BATCHED_G") ? atoi(getenv("AC_BATCHED_G")) : 32;
-  const int G = n == 12 ? g12 : 16;
-  const size_t lds = (size_t)G * (2 * n * n + 2 * n) * sizeof(float);
-  const int64_t blocks = (p.batch + G - 1) / G;
-  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  dim3 grid((unsigned)blocks), block(256);
-  static const int stream12 = getenv("AC_BATCHED_STREAM") ? atoi(getenv("AC_BATCHED_STREAM")) : 2;
-  if (n == 12 && vec && stream12) {
-    // 3 workgroups of 4 waves per CU (LDS: 40 KB each); persistent over groups of 4 items
+  if (n == 12 && vec) {
+    // streaming kernel: two persistent workgroups of B12_WAVES waves per CU, each wave walking over groups of
+    // B12_GROUP items through its own pair of LDS windows
+    constexpr int WGS_PER_CU = 2;
     static int cus = 0;
     if (cus == 0) {
       int dev = 0;
@@ -263,17 +256,18 @@ hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream) {
     }
     const int64_t ngroups = (p.batch + B12_GROUP - 1) / B12_GROUP;
     int64_t wgs = (ngroups + B12_WAVES - 1) / B12_WAVES;
-    if (wgs > (int64_t)cus * stream12) wgs = (int64_t)cus * stream12;  // stream12 = workgroups per CU
+    if (wgs > (int64_t)cus * WGS_PER_CU) wgs = (int64_t)cus * WGS_PER_CU;
     hipLaunchKernelGGL(batched12_stream_kernel, dim3((unsigned)wgs), dim3(64 * B12_WAVES), B12_WAVES * 2 * B12_WIN, stream, p);
-  } else if (n == 12 && vec && G == 16) {
-    hipLaunchKernelGGL((batched_f32_kernel<12, 16, true>), grid, block, lds, stream, p);
-  } else if (n == 12 && vec && G == 64) {
-    static bool cfg = false;
-    if (!cfg) { (void)hipFuncSetAttribute((const void*)batched_f32_kernel<12, 64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); cfg = true; }
-    hipLaunchKernelGGL((batched_f32_kernel<12, 64, true>), grid, block, lds, stream, p);
-  } else if (n == 12) {
-    if (vec) hipLaunchKernelGGL((batched_f32_kernel<12, 32, true>), grid, block, lds, stream, p);
-    else hipLaunchKernelGGL((batched_f32_kernel<12, 32, false>), grid, block, lds, stream, p);
+    return hipGetLastError();
+  }
+  // LDS-staged kernel: 32 items per workgroup for unaligned 12 x 12 operands (39 KB of LDS), 16 for other n
+  const int G = n == 12 ? 32 : 16;
+  const size_t lds = (size_t)G * (2 * n * n + 2 * n) * sizeof(float);
+  const int64_t blocks = (p.batch + G - 1) / G;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks), block(256);
+  if (n == 12) {
+    hipLaunchKernelGGL((batched_f32_kernel<12, 32, false>), grid, block, lds, stream, p);
   } else {
     if (vec) hipLaunchKernelGGL((batched_f32_kernel<0, 16, true>), grid, block, lds, stream, p);
     else hipLaunchKernelGGL((batched_f32_kernel<0, 16, false>), grid, block, lds, stream, p);

@@ -7,7 +7,7 @@ namespace ac {
 // work (the 256 tile with its eight-wave schedule already wins at one tile on every second unit).  When even
 // 64 x 64 tiles leave most of the chip idle and K is deep, K is cut into slices that add into C (see
 // EpilogueAtomicF32).  The slice count minimises a two-term estimate measured on this chip: a 64 x 64
-// workgroup alone on its compute unit advances one K tile in about 0.28 us, and the fp32 atomic adds of one
+// workgroup alone on its compute unit advances one K tile in about 0.24 us, and the fp32 atomic adds of one
 // slice retire at about 43 elements per nanosecond, so every extra slice costs M * N / 43000 us.
 GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K) {
   auto tiles = [&](int t) { return (int64_t)((M + t - 1) / t) * ((N + t - 1) / t); };
@@ -20,10 +20,10 @@ GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K) {
     const int64_t t = tiles(64);
     const int64_t nkt = ((int64_t)K * 2 + plan.ktb - 1) / plan.ktb;
     const double slice_us = (double)M * N / 43000.0;
-    double best = 0.28 * (double)nkt * (double)((t + 255) / 256);
+    double best = 0.24 * (double)nkt * (double)((t + 255) / 256);
     int best_s = 1;
     for (int s = 2; s * t <= 256 && s <= nkt; s *= 2) {  // at most one workgroup per compute unit
-      const double est = 0.28 * (double)((nkt + s - 1) / s) + 2.0 + slice_us * s;
+      const double est = 0.24 * (double)((nkt + s - 1) / s) + 2.0 + slice_us * s;
       if (est < best) {
         best = est;
         best_s = s;

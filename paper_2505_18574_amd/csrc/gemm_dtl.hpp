@@ -343,12 +343,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     }
     if (grp == 0) block_sync();    // every wave executes the same number of barriers
   } else {
-  // Tile t lives in LDS stage t % STAGES.  The fragments of the next K-step are read while the MFMAs of the
-  // current one run (two register sets).  The one barrier per tile sits in the last K-step of tile kt, after
-  // this wave has read its last fragments of that tile: past it, tile kt + 1 is visible to everyone, and the
-  // stage of tile kt is free to receive tile kt + STAGES.
-  static_assert(G::KSTEPS % 2 == 0, "fragment double buffering assumes an even number of K-steps per tile");
-  Frag fr[2];
+  // Tile t lives in LDS stage t % STAGES.  One fragment set per K-step of a tile stays in registers; as soon
+  // as the MFMAs of K-step s of tile kt are issued, the set is refilled with K-step s of tile kt + 1, so an LDS
+  // read has the MFMAs of the other K-steps of a tile to land in (with a fragment double buffer per K-step it
+  // had one K-step, less than the LDS latency on the small tiles).  One barrier per tile, at the top: past it
+  // every wave has received its fragments of tile kt (block_sync waits for the wave's own LDS reads), so the
+  // stage of tile kt can take tile kt + STAGES, and tile kt + 1 is visible to everyone.
+  Frag fr[G::KSTEPS];
 #pragma unroll
   for (int s = 0; s < STAGES; s++)
     if (s < nkt) issue_loads(s, s);
@@ -356,41 +357,28 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     if (STAGES - 1 < nkt) wait_vm<(STAGES - 1) * PER_TILE>();
     else wait_vm<0>();
     block_sync();
-    read_frags(0, 0, fr[0]);
+#pragma unroll
+    for (int ks = 0; ks < G::KSTEPS; ks++) read_frags(0, ks, fr[ks]);
   }
   int buf = 0;
-  for (int kt = 0; kt + 1 < nkt; kt++) {  // every tile but the last: ends by handing over to tile kt + 1
+  for (int kt = 0; kt + 1 < nkt; kt++) {  // every tile but the last
     const int nbuf = buf + 1 == STAGES ? 0 : buf + 1;
+    // tile kt + 1 must have landed: only the (STAGES - 2) younger tiles may still be in flight
+    if (kt + STAGES - 1 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
+    else wait_vm<0>();
+    block_sync();
+    if (kt + STAGES < nkt) issue_loads(kt + STAGES, buf);
 #pragma unroll
     for (int ks = 0; ks < G::KSTEPS; ks++) {
-      const Frag& cur = fr[ks & 1];
-      if (ks + 1 < G::KSTEPS) {
-        read_frags(buf, ks + 1, fr[(ks + 1) & 1]);
-        mfma_rows(cur, 0, G::TM);
-      } else {
-        // Half of this K-step's MFMAs are queued before the barrier (they keep the matrix pipe busy while
-        // the waves gather), the other half after the next tile's first fragments have been requested
-        // (they cover the LDS latency).  The scheduling fences keep the compiler from regrouping them.
-        mfma_rows(cur, 0, G::TM / 2);
-        __builtin_amdgcn_sched_barrier(0);
-        // tile kt + 1 must have landed: only the (STAGES - 2) younger tiles may still be in flight
-        if (kt + STAGES - 1 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
-        else wait_vm<0>();
-        block_sync();
-        if (kt + STAGES < nkt) issue_loads(kt + STAGES, buf);
-        read_frags(nbuf, 0, fr[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_rows(cur, G::TM / 2, G::TM);
-      }
+      mfma_rows(fr[ks], 0, G::TM);
+      __builtin_amdgcn_sched_barrier(0);  // keep the refill behind the MFMAs that still read the old fragments
+      read_frags(nbuf, ks, fr[ks]);
     }
     buf = nbuf;
   }
   if (nkt > 0) {  // last tile
 #pragma unroll
-    for (int ks = 0; ks < G::KSTEPS; ks++) {
-      if (ks + 1 < G::KSTEPS) read_frags(buf, ks + 1, fr[(ks + 1) & 1]);
-      mfma_rows(fr[ks & 1], 0, G::TM);
-    }
+    for (int ks = 0; ks < G::KSTEPS; ks++) mfma_rows(fr[ks], 0, G::TM);
   }
   }
 

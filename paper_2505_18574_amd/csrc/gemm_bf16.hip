@@ -80,7 +80,7 @@ hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const Gemm
     if (plan.splits > 1 && p.partial != nullptr) {  // slices through the caller's workspace, summed in a fixed order
       hipError_t e;
       if (plan.tile == 256) e = launch_dtl<TypeBF16, EpiloguePartialF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-      else if (plan.tile == 128) e = launch_dtl<TypeBF16, EpiloguePartialF32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+      else if (plan.tile == 128) e = launch_dtl<TypeBF16, EpiloguePartialF32, 128, 128, 2, 4, 0, 3, 128>(p, stream);
       else e = launch_dtl<TypeBF16, EpiloguePartialF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
       if (e != hipSuccess) return e;
       const int64_t quads = (int64_t)p.M * (p.N / 4);
@@ -93,12 +93,12 @@ hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const Gemm
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       if (plan.tile == 256) return launch_dtl<TypeBF16, EpilogueAtomicF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-      if (plan.tile == 128) return launch_dtl<TypeBF16, EpilogueAtomicF32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+      if (plan.tile == 128) return launch_dtl<TypeBF16, EpilogueAtomicF32, 128, 128, 2, 4, 0, 3, 128>(p, stream);
       return launch_dtl<TypeBF16, EpilogueAtomicF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
     }
     // large tile: eight waves in ping-pong over four 32 KB LDS stages
     if (plan.tile == 256) return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-    if (plan.tile == 128) return launch_dtl<TypeBF16, EpilogueF32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+    if (plan.tile == 128) return launch_dtl<TypeBF16, EpilogueF32, 128, 128, 2, 4, 0, 3, 128>(p, stream);
     return launch_dtl<TypeBF16, EpilogueF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
   }
 #define AC_BF16_LAUNCH(TILE)                                                                        \

@@ -89,7 +89,7 @@ hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast
     if (plan.splits > 1) {
       hipError_t e;
       if (plan.tile == 256) e = launch_dtl<TypeI8, EpiloguePartialI32, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
-      else if (plan.tile == 128) e = launch_dtl<TypeI8, EpiloguePartialI32, 128, 128, 2, 2, AMODE, 3, 128>(p, stream);
+      else if (plan.tile == 128) e = launch_dtl<TypeI8, EpiloguePartialI32, 128, 128, 2, 4, AMODE, 3, 128>(p, stream);
       else e = launch_dtl<TypeI8, EpiloguePartialI32, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
       if (e != hipSuccess) return e;
       const int64_t quads = (int64_t)p.M * (p.N / 4);
@@ -97,7 +97,7 @@ hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast
       return hipGetLastError();
     }
     if (plan.tile == 256) return launch_dtl<TypeI8, EpilogueI8, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
-    if (plan.tile == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 2, AMODE, 3, 128>(p, stream);
+    if (plan.tile == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 4, AMODE, 3, 128>(p, stream);
     return launch_dtl<TypeI8, EpilogueI8, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
   }
 #define AC_I8_CASE(TILE, WM, WN)                                                                         \
@@ -131,7 +131,7 @@ hipError_t launch_gemm_i8_acc32(const GemmParams& p0, hipStream_t stream) {
   const GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, false);
   if (fast) {
     if (plan.tile == 256) return launch_dtl<TypeI8, EpilogueRawI32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-    if (plan.tile == 128) return launch_dtl<TypeI8, EpilogueRawI32, 128, 128, 2, 2, 0, 3, 128>(p, stream);
+    if (plan.tile == 128) return launch_dtl<TypeI8, EpilogueRawI32, 128, 128, 2, 4, 0, 3, 128>(p, stream);
     return launch_dtl<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
   }
   return aligned ? launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, true>(p, stream)

@@ -1,0 +1,83 @@
+"""GPU parity on seeded random shapes: every kernel family (direct-to-LDS tiles of all three sizes, split-K,
+the generic fallback, the transposed-operand kernel) is reached by shapes the directed tests do not name."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import dev, host, rel_fro
+from paper_2505_18574_amd import inputs, ops
+
+pytestmark = pytest.mark.gpu
+
+
+def random_shapes(seed, count, aligned):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        M = int(rng.integers(1, 700))
+        N = int(rng.integers(1, 700))
+        K = int(rng.integers(1, 1500))
+        if aligned:  # multiples of 16: the direct-to-LDS path
+            N, K = max(16, N // 16 * 16), max(16, K // 16 * 16)
+        out.append((M, N, K))
+    # a few large ones so that the 128 and 256 tiles and a split are chosen
+    out += [(2100, 2064, 208), (3100, 3088, 80), (40, 48, 4096)] if aligned else [(1500, 1700, 100)]
+    return out
+
+
+@pytest.mark.parametrize("aligned", [True, False])
+def test_int8_random_shapes(aligned):
+    for idx, (M, N, K) in enumerate(random_shapes(101 if aligned else 202, 24, aligned)):
+        A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=7000 + idx, bias_matrix=(idx % 5 == 0))
+        shift, act = int(idx % 13), int(idx % 2)
+        want = oracle.gemm_i8(A, B, bias if idx % 7 else None, shift, act)
+        C = torch.full((M, N), 91, dtype=torch.int8, device="cuda")
+        nbytes = ops.ac_gemm_i8_workspace_bytes(M, N, K)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes and idx % 2 == 0 else None
+        ops.ac_gemm_i8(dev(A), dev(B), dev(bias) if idx % 7 else None, C, shift, act, workspace=ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(C), want, err_msg=f"shape {(M, N, K)} shift {shift} act {act}")
+        # the same product with both operands transposed in memory
+        Ct = torch.full((M, N), 92, dtype=torch.int8, device="cuda")
+        ops.ac_gemm_i8_t(dev(np.ascontiguousarray(A.T)), dev(np.ascontiguousarray(B.T)), dev(bias) if idx % 7 else None, Ct,
+                         shift, act, trans_a=True, trans_b=True)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(Ct), want, err_msg=f"transposed, shape {(M, N, K)}")
+
+
+@pytest.mark.parametrize("aligned", [True, False])
+def test_bf16_random_shapes(aligned):
+    for idx, (M, N, K) in enumerate(random_shapes(303 if aligned else 404, 16, aligned)):
+        A, B = inputs.gemm_bf16_inputs(M, N, K, seed=8000 + idx)
+        alpha, beta = (1.0, 0.0) if idx % 3 else (0.75, -1.5)
+        C_in = np.random.default_rng(idx).standard_normal((M, N)).astype(np.float32)
+        want = oracle.gemm_bf16(A, B, alpha, beta, C_in if beta else None)
+        C = dev(C_in).clone() if beta else torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        ops.ac_gemm_bf16(dev(A), dev(B), C, alpha, beta)
+        torch.cuda.synchronize()
+        got = host(C)
+        assert rel_fro(got, want) <= 1e-3, (M, N, K)
+        Aa = np.abs(inputs.bf16_bits_to_f32(A).astype(np.float64))
+        Ba = np.abs(inputs.bf16_bits_to_f32(B).astype(np.float64))
+        bound = 4.0 * (K + 2) * 2.0 ** -24 * (abs(alpha) * (Aa @ Ba) + abs(beta) * np.abs(C_in)) + 1e-30
+        assert (np.abs(got - want) <= bound).all(), (M, N, K)
+
+
+def test_conv_random_geometries():
+    rng = np.random.default_rng(505)
+    for idx in range(14):
+        Nb, H, W = int(rng.integers(1, 4)), int(rng.integers(3, 20)), int(rng.integers(3, 20))
+        KH, KW = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, 2))
+        if idx % 2 == 0:  # fast path: channel counts in multiples of 16
+            Cin, Cout = 16 * int(rng.integers(1, 5)), 16 * int(rng.integers(1, 6))
+        else:
+            Cin, Cout = int(rng.integers(1, 40)), int(rng.integers(1, 50))
+        x, w, b = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=9000 + idx)
+        OH, OW = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+        out = torch.full((Nb, OH, OW, Cout), 17, dtype=torch.int8, device="cuda")
+        ops.ac_conv2d_i8(dev(x), dev(w), dev(b), out, stride, pad, 7, idx % 2)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(out), oracle.conv2d_i8(x, w, b, stride, pad, 7, idx % 2),
+                                      err_msg=f"conv {(Nb, H, W, Cin, Cout, KH, KW, stride, pad)}")

@@ -291,7 +291,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
 #pragma unroll
     for (int i = i0; i < i1; i++)
 #pragma unroll
-      for (int j = 0; j < G::TN; j++) acc[i][j] = T::mfma(f.b[j], f.a[i], acc[i][j]);
+      for (int j = 0; j < G::TN; j++) acc[i][j] = EPI::SWAP ? T::mfma(f.b[j], f.a[i], acc[i][j]) : T::mfma(f.a[i], f.b[j], acc[i][j]);
   };
 
   // ---- main loop ---------------------------------------------------------------------------------------
@@ -385,9 +385,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   // ---- epilogue: one call per 32x32 MFMA tile -----------------------------------------------------------
 #pragma unroll
   for (int i = 0; i < G::TM; i++) {
-    const int m = m0 + wm * G::WTM + i * 32 + (lane & 31);
+    const int mrow0 = m0 + wm * G::WTM + i * 32;
 #pragma unroll
-    for (int j = 0; j < G::TN; j++) EPI::tile(p, m, n0 + wn * G::WTN + j * 32, acc[i][j], lane, split, pre[j]);
+    for (int j = 0; j < G::TN; j++) EPI::tile(p, mrow0, n0 + wn * G::WTN + j * 32, acc[i][j], lane, split, pre[j]);
   }
   block_sync();  // all fragment reads of this tile are done before the next tile refills the LDS stages
   }  // tile loop

@@ -101,10 +101,28 @@ static __device__ __forceinline__ void tile_coords(int b, int nblocks, int tiles
 }
 
 // Epilogue policies -----------------------------------------------------------
-// Each receives, for one lane, 4 accumulators of row m at columns n .. n+3.
+// store4(): for one lane, 4 accumulators of row m at columns n .. n+3 (the generic kernel, which always swaps
+// the MFMA operands).  tile(): one 32x32 accumulator tile of the direct-to-LDS kernel, whose operand order the
+// policy chooses with SWAP:
+//   SWAP (B^T tile as the row operand): register r of lane l is row l % 32, column 8 (r/4) + 4 (l/32) + r % 4:
+//     a lane owns runs of 4 consecutive columns of one row.  Right for 1-byte outputs, which pack 4 (and, after
+//     a lane exchange, 16) of them per store.
+//   !SWAP: register r of lane l is row 8 (r/4) + 4 (l/32) + r % 4, column l % 32: the 32 lanes of a half-wave
+//     own 32 consecutive columns of one row, so a 4-byte-per-lane store writes a whole 128-byte row segment.
+//     Right for 4-byte outputs: with the swapped order a store instruction scatters 32-byte pieces over 32
+//     rows, which the memory system drains at half the rate (measured on a store-bound GEMM).
+// tile() receives the tile origin (mrow0, ncol0).
+
+// Applies f(r, m, n) to the 16 accumulators of an unswapped tile: r = register, (m, n) = its coordinates.
+template <class F>
+static __device__ __forceinline__ void for_each_unswapped(int mrow0, int ncol0, int lane, F f) {
+#pragma unroll
+  for (int r = 0; r < 16; r++) f(r, mrow0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), ncol0 + (lane & 31));
+}
 
 // int8 output stage: bias, v / 2^shift to nearest (halves to even), saturate, ReLU.
 struct EpilogueI8 {
+  static constexpr bool SWAP = true;
   static __device__ __forceinline__ int requant(int v, int shift, int act) {
     int fl = v >> shift;
     unsigned int rem = (unsigned int)v & ((1u << shift) - 1u);
@@ -157,7 +175,8 @@ struct EpilogueI8 {
     }
   }
   template <class ACC>
-  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int, const Pre& pre) {
+  static __device__ __forceinline__ void tile(const GemmParams& p, int mrow0, int ncol0, const ACC& acc, int lane, int, const Pre& pre) {
+    const int m = mrow0 + (lane & 31);
     if (m >= p.M || ncol0 >= p.N) return;
     int8_t* C = (int8_t*)p.C;
     const bool wide = ncol0 + 32 <= p.N && (p.ldc & 15) == 0 && (((uintptr_t)C) & 15) == 0;
@@ -198,34 +217,21 @@ struct EpilogueI8 {
 // Split-K partial sums: raw int32 accumulators of K slice `split` go to partial[split][M][N]; the output stage
 // runs in splitk_reduce_i8_kernel once every slice has been written.
 struct EpiloguePartialI32 {
-  template <bool VEC>
-  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a, int split) {
-    if (m >= p.M || n >= p.N) return;
-    int32_t* dst = p.partial + ((int64_t)split * p.M + m) * p.N + n;
-    if (VEC && n + 3 < p.N) {
-      *(v4i*)dst = (v4i){a[0], a[1], a[2], a[3]};
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; e++)
-        if (n + e < p.N) dst[e] = a[e];
-    }
-  }
+  static constexpr bool SWAP = false;
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
   template <class ACC>
-  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
-      decltype(acc[0] + 0) a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-      store4<true>(p, m, n, a4, split);
-    }
+  static __device__ __forceinline__ void tile(const GemmParams& p, int mrow0, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
+    for_each_unswapped(mrow0, ncol0, lane, [&](int r, int m, int n) {
+      if (m < p.M && n < p.N) p.partial[((int64_t)split * p.M + m) * p.N + n] = acc[r];
+    });
   }
 };
 
 // Raw accumulator output (the accumulator-type read of the paper's accelerator: no scaling, no activation):
 // C32[m][n] = acc + bias, int32, row stride ldc.
 struct EpilogueRawI32 {
+  static constexpr bool SWAP = false;
   template <bool VEC>
   static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
@@ -248,18 +254,20 @@ struct EpilogueRawI32 {
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
   template <class ACC>
-  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
-      int a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-      store4<true>(p, m, n, a4, split);
-    }
+  static __device__ __forceinline__ void tile(const GemmParams& p, int mrow0, int ncol0, const ACC& acc, int lane, int, const Pre&) {
+    for_each_unswapped(mrow0, ncol0, lane, [&](int r, int m, int n) {
+      if (m < p.M && n < p.N) {
+        int b = 0;
+        if (p.bias) b = p.bias_ld == 0 ? p.bias[n] : p.bias[(int64_t)m * p.bias_ld + n];
+        ((int32_t*)p.C)[(int64_t)m * p.ldc + n] = acc[r] + b;
+      }
+    });
   }
 };
 
 // fp32 output: C = alpha * acc + beta * C (C read only when beta != 0).
 struct EpilogueF32 {
+  static constexpr bool SWAP = false;
   template <bool VEC>
   static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
@@ -285,13 +293,15 @@ struct EpilogueF32 {
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
   template <class ACC>
-  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
-      decltype(acc[0] + 0) a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-      store4<true>(p, m, n, a4, split);
-    }
+  static __device__ __forceinline__ void tile(const GemmParams& p, int mrow0, int ncol0, const ACC& acc, int lane, int, const Pre&) {
+    for_each_unswapped(mrow0, ncol0, lane, [&](int r, int m, int n) {
+      if (m < p.M && n < p.N) {
+        float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
+        float o = p.alpha * acc[r];
+        if (p.beta != 0.f) o += p.beta * *dst;
+        *dst = o;
+      }
+    });
   }
 };
 
@@ -299,24 +309,14 @@ struct EpilogueF32 {
 // hardware fp32 atomic add; C was set to beta * C by scale_c_f32_kernel before the slices run.  The order in
 // which slices arrive is not fixed, so the last bits of a sum may differ between runs.
 struct EpilogueAtomicF32 {
+  static constexpr bool SWAP = false;
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
-  template <bool VEC>
-  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a, int = 0) {
-    if (m >= p.M || n >= p.N) return;
-    float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
-#pragma unroll
-    for (int e = 0; e < 4; e++)
-      if (n + e < p.N) unsafeAtomicAdd(dst + e, p.alpha * a[e]);
-  }
   template <class ACC>
-  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
-      float a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-      store4<true>(p, m, n, a4, split);
-    }
+  static __device__ __forceinline__ void tile(const GemmParams& p, int mrow0, int ncol0, const ACC& acc, int lane, int, const Pre&) {
+    for_each_unswapped(mrow0, ncol0, lane, [&](int r, int m, int n) {
+      if (m < p.M && n < p.N) unsafeAtomicAdd((float*)p.C + (int64_t)m * p.ldc + n, p.alpha * acc[r]);
+    });
   }
 };
 
@@ -324,28 +324,14 @@ struct EpilogueAtomicF32 {
 // int32 workspace pointer reinterpreted); splitk_reduce_f32_kernel sums the slices in slice order and applies
 // alpha / beta, so the result does not depend on which slice finishes first.
 struct EpiloguePartialF32 {
+  static constexpr bool SWAP = false;
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
-  template <bool VEC>
-  static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a, int split) {
-    if (m >= p.M || n >= p.N) return;
-    float* dst = (float*)p.partial + ((int64_t)split * p.M + m) * p.N + n;
-    if (VEC && n + 3 < p.N) {
-      *(v4f*)dst = (v4f){a[0], a[1], a[2], a[3]};
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; e++)
-        if (n + e < p.N) dst[e] = a[e];
-    }
-  }
   template <class ACC>
-  static __device__ __forceinline__ void tile(const GemmParams& p, int m, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
-      float a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-      store4<true>(p, m, n, a4, split);
-    }
+  static __device__ __forceinline__ void tile(const GemmParams& p, int mrow0, int ncol0, const ACC& acc, int lane, int split, const Pre&) {
+    for_each_unswapped(mrow0, ncol0, lane, [&](int r, int m, int n) {
+      if (m < p.M && n < p.N) ((float*)p.partial)[((int64_t)split * p.M + m) * p.N + n] = acc[r];
+    });
   }
 };
 

@@ -21,8 +21,11 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   if (plan.tile == 64) {
     const int64_t t = tiles(64);
     const int nkt = (K + plan.ktb - 1) / plan.ktb;
-    if (have_workspace && t <= 64 && nkt >= 16) {  // the second (reduce) launch costs about 3 us: only worth it for deep K
-      int want = (int)((256 + t - 1) / t);             // slices needed to cover the CUs
+    // The second (reduce) launch costs about 3 us: worth it only for a deep K on at most 32 tiles, and then with
+    // just enough slices to put a workgroup on every second CU (measured: 49 x 2048 x 4608 is fastest with 4
+    // slices, 196 x 1024 x 2304 unsplit).
+    if (have_workspace && t <= 32 && nkt >= 16) {
+      int want = (int)((128 + t - 1) / t);
       int per = (nkt + want - 1) / want;               // K tiles per slice ...
       if (per < 2) per = 2;                            // ... but at least two, so a slice amortises its fill
       plan.kt_per_split = per;

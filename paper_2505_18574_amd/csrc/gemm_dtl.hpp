@@ -193,16 +193,19 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   const unsigned char* b_base = (const unsigned char*)p.B + (int64_t)n0 * EB + kt0 * b_step;
 
   // convolution: (kh, kw, ci) of this lane's possible chunks, advanced by KTB bytes of K per tile
-  int c_kh[NVAR], c_kw[NVAR], c_ci[NVAR];
+  // c_off is the element offset (kh * W + kw) * Cin + ci of the chunk from the window's first pixel; it grows by
+  // KTB per tile and by (W - KW) * Cin more whenever kh steps
+  int c_kh[NVAR], c_kw[NVAR], c_ci[NVAR], c_off[NVAR];
 #pragma unroll
   for (int v = 0; v < NVAR; v++) {
-    c_kh[v] = c_kw[v] = c_ci[v] = 0;
+    c_kh[v] = c_kw[v] = c_ci[v] = c_off[v] = 0;
     if constexpr (AMODE == 1) {
       int kb = kt0 * G::KTB + a_chunk[v] * 16;
       int tap = kb / p.Cin;
       c_ci[v] = kb - tap * p.Cin;
       c_kh[v] = tap / p.KW;
       c_kw[v] = tap - c_kh[v] * p.KW;
+      c_off[v] = (c_kh[v] * p.W + c_kw[v]) * p.Cin + c_ci[v];
     }
   }
 
@@ -216,8 +219,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     if (AMODE == 0 && full) {
 #pragma unroll
       for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], As + (wave * G::A_INSTR + i) * 1024);
-#pragma unroll
-      for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], Bs + (wave * G::B_INSTR + i) * 1024);
     } else {
 #pragma unroll
       for (int i = 0; i < G::A_INSTR; i++) {
@@ -230,16 +231,19 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
           const ARow<1>& r = a_pix[i];
           const int ih = r.ih0 + c_kh[v], iw = r.iw0 + c_kw[v];
           if (r.ok && kb < kbytes && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
-            src = (const unsigned char*)p.A + r.base + (c_kh[v] * p.W + c_kw[v]) * p.Cin + c_ci[v];
+            src = (const unsigned char*)p.A + r.base + c_off[v];
         }
         load_to_lds16(src, As + (wave * G::A_INSTR + i) * 1024);
       }
+    }
+    if (full) {  // every k-row of the tile exists; columns beyond N were clamped when b_voff was set up
+#pragma unroll
+      for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], Bs + (wave * G::B_INSTR + i) * 1024);
+    } else {
 #pragma unroll
       for (int i = 0; i < G::B_INSTR; i++) {
         const int k = kt * G::BK + b_krow[i];
-        const unsigned char* src = zero;
-        if (k < p.K && (AMODE == 0 || n0 * EB + (int)(b_voff[i] - (unsigned)b_krow[i] * (unsigned)(p.ldb * EB)) < nbytes)) src = b_base + b_voff[i];
-        load_to_lds16(src, Bs + (wave * G::B_INSTR + i) * 1024);
+        load_to_lds16(k < p.K ? b_base + b_voff[i] : zero, Bs + (wave * G::B_INSTR + i) * 1024);
       }
     }
     a_base += G::KTB;
@@ -248,11 +252,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
 #pragma unroll
       for (int v = 0; v < NVAR; v++) {
         c_ci[v] += G::KTB;
+        c_off[v] += G::KTB;
         while (c_ci[v] >= p.Cin) {
           c_ci[v] -= p.Cin;
           if (++c_kw[v] == p.KW) {
             c_kw[v] = 0;
             ++c_kh[v];
+            c_off[v] += (p.W - p.KW) * p.Cin;
           }
         }
       }

@@ -302,6 +302,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch the pass eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-supplementary", action="store_true")
+    ap.add_argument("--no-isolated", action="store_true",
+                    help="skip the isolated per-workload timing, so that every dispatch of the run belongs to a whole pass (kernel-trace aid)")
     ap.add_argument("--copy-reference", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times (reference for scaling HBM counters)")
     ap.add_argument("--only", default=None, help="restrict the pass to workloads whose name contains this string (profiling aid)")
@@ -350,15 +352,17 @@ def main():
 
     per = []
     for w, ms in zip(wl, kt):
-        iso, iso_min = isolated_stats(w, stream)
+        iso, iso_min = (None, None) if args.no_isolated else isolated_stats(w, stream)
         rate = w.ops / ms / 1e9
         peak = PEAK[w.dtype]
         t_mfma_us = w.ops / (peak * 1e12) * 1e6
         t_hbm_us = w.bytes / (HBM_PEAK_GBS * 1e9) * 1e6
         per.append({
             "name": w.name, "dtype": w.dtype, "ops": w.ops, "bytes": w.bytes,
-            "ms_in_pass": round(float(ms), 5), "ms_isolated_warm": round(iso, 5), "ms_isolated_warm_min": round(iso_min, 5),
-            "tops_in_pass": round(rate, 2), "tops_isolated_warm": round(w.ops / iso / 1e9, 2),
+            "ms_in_pass": round(float(ms), 5),
+            "ms_isolated_warm": None if iso is None else round(iso, 5),
+            "ms_isolated_warm_min": None if iso is None else round(iso_min, 5),
+            "tops_in_pass": round(rate, 2), "tops_isolated_warm": None if iso is None else round(w.ops / iso / 1e9, 2),
             "frac_mfma_peak": round(rate / peak, 4) if w.dtype != "f32" else None,
             "gbs_in_pass": round(w.bytes / ms / 1e6, 1), "frac_hbm_peak": round(w.bytes / ms / 1e6 / HBM_PEAK_GBS, 4),
             "attainable_us": round(max(t_mfma_us, t_hbm_us), 3),

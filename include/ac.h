@@ -207,7 +207,7 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  * entry points run one named candidate so that a tuner can time each of them on the caller's own shape; the
  * results are those of ac_gemm_i8 / ac_gemm_bf16 (bit for bit for int8; for bf16 up to the summation order).
  *
- *   tile    edge of the square block tile: 64, 128 or 256
+ *   tile    block tile code: 64, 128, 256 = square tile of that edge; 192 = the tile of 256 rows x 128 columns
  *   splits  1 = no split; n > 1 cuts the K range into at most n slices of equal whole K tiles (64 bytes of K
  *           per tile for tile 256, 128 bytes otherwise), each slice a workgroup of its own.  Needs operands
  *           that qualify for the direct-to-LDS kernels: base pointers and row pitches of A and B multiples of
@@ -220,9 +220,11 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           is the same on every run).  bf16, workspace NULL / 0: a first kernel sets C = beta * C, then every
  *           slice adds alpha * (its product) with fp32 atomic adds, in no fixed order (slow for large M * N).
  *           Workspace rules as for ac_gemm_i8: 16-byte aligned, large enough, else AC_ERR_WORKSPACE.
- *   AC_ERR_PLAN: tile not one of the three, splits < 1 or larger than the number of K tiles, or splits > 1
+ *   AC_ERR_PLAN: unknown tile code, splits < 1 or larger than the number of K tiles, or splits > 1
  *           with operands that do not qualify.  Everything else as for the unplanned call.
  * ac_gemm_*_auto_plan report what the unplanned call would choose for a shape (pure host arithmetic).
+ * Operands that do not qualify for the direct-to-LDS kernels run on a generic kernel with square tiles, which
+ * takes code 192 as 128.
  */
 ac_status ac_gemm_i8_planned(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                              const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,

@@ -61,14 +61,18 @@ struct TinyMpcParams {
 // Block tile and K split of one GEMM launch.  Chosen by the library from the shape (plan_gemm_*), or named
 // by the caller through the planned entry points (make_plan_*), which is what a tuner drives.
 struct GemmPlan {
-  int tile;          // square block tile edge: 64, 128 or 256
+  int tile;          // block tile code: 64, 128, 256 = square tile of that edge; 192 = 256 rows x 128 columns
   int ktb;           // K bytes per tile of the kernel that serves this block tile
   int splits;        // K slices (1 = no split)
   int kt_per_split;  // K tiles per slice (0 when splits == 1)
 };
 GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace);
 GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K);
-// Explicit plans: false when the tile is not one of the three, or splits is outside 1 .. number of K tiles.
+// Rows / columns of a tile code (false for an unknown code).
+bool tile_dims(int32_t tile, int* bm, int* bn);
+// Tile code the library picks for an M x N output.
+int choose_tile(int32_t M, int32_t N);
+// Explicit plans: false when the tile code is unknown, or splits is outside 1 .. number of K tiles.
 bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan);
 bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan);
 

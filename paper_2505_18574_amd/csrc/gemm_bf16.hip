@@ -4,16 +4,14 @@
 namespace ac {
 
 // Block tile and K split for an M x N x K bf16 problem: the largest tile that still gives most compute units
-// work (the 256 tile with its eight-wave schedule already wins at one tile on every second unit).  When even
+// work (thresholds from exhaustive plan tables: 256 x 256 from 192 tiles, 128 x 128 from 128 tiles).  When even
 // 64 x 64 tiles leave most of the chip idle and K is deep, K is cut into slices that add into C (see
 // EpilogueAtomicF32).  The slice count minimises a two-term estimate measured on this chip: a 64 x 64
 // workgroup alone on its compute unit advances one K tile in about 0.24 us, and the fp32 atomic adds of one
 // slice retire at about 43 elements per nanosecond, so every extra slice costs M * N / 43000 us.
 GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K) {
   auto tiles = [&](int t) { return (int64_t)((M + t - 1) / t) * ((N + t - 1) / t); };
-  // a tile much larger than the problem wastes most of its MFMAs: require 3/4 of the tile edge in both dimensions
-  const bool ok256 = M >= 192 && N >= 192, ok128 = M >= 96 && N >= 96;
-  const int tile = (ok256 && tiles(256) >= 128) ? 256 : ((ok128 && tiles(128) >= 192) ? 128 : 64);
+  const int tile = choose_tile(M, N);
   GemmPlan plan;
   make_plan_bf16(K, tile, 1, &plan);
   if (tile == 64) {
@@ -78,10 +76,7 @@ hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const Gemm
   p.kt_per_split = plan.kt_per_split;
   if (fast) {
     if (plan.splits > 1 && p.partial != nullptr) {  // slices through the caller's workspace, summed in a fixed order
-      hipError_t e;
-      if (plan.tile == 256) e = launch_dtl<TypeBF16, EpiloguePartialF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-      else if (plan.tile == 128) e = launch_dtl<TypeBF16, EpiloguePartialF32, 128, 128, 2, 4, 0, 3, 128>(p, stream);
-      else e = launch_dtl<TypeBF16, EpiloguePartialF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
+      hipError_t e = launch_dtl_tile<TypeBF16, EpiloguePartialF32, 0>(plan.tile, p, stream);
       if (e != hipSuccess) return e;
       const int64_t quads = (int64_t)p.M * (p.N / 4);
       hipLaunchKernelGGL(splitk_reduce_f32_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, p);
@@ -92,20 +87,16 @@ hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const Gemm
       hipLaunchKernelGGL(scale_c_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (float*)p.C, p.ldc, p.M, p.N, p.beta);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
-      if (plan.tile == 256) return launch_dtl<TypeBF16, EpilogueAtomicF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-      if (plan.tile == 128) return launch_dtl<TypeBF16, EpilogueAtomicF32, 128, 128, 2, 4, 0, 3, 128>(p, stream);
-      return launch_dtl<TypeBF16, EpilogueAtomicF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
+      return launch_dtl_tile<TypeBF16, EpilogueAtomicF32, 0>(plan.tile, p, stream);
     }
-    // large tile: eight waves in ping-pong over four 32 KB LDS stages
-    if (plan.tile == 256) return launch_dtl<TypeBF16, EpilogueF32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-    if (plan.tile == 128) return launch_dtl<TypeBF16, EpilogueF32, 128, 128, 2, 4, 0, 3, 128>(p, stream);
-    return launch_dtl<TypeBF16, EpilogueF32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
+    return launch_dtl_tile<TypeBF16, EpilogueF32, 0>(plan.tile, p, stream);
   }
 #define AC_BF16_LAUNCH(TILE)                                                                        \
   (aligned ? launch_tile<TypeBF16, EpilogueF32, TILE, TILE, 2, 2, 0, true>(p, stream)               \
            : launch_tile<TypeBF16, EpilogueF32, TILE, TILE, 2, 2, 0, false>(p, stream))
-  switch (plan.tile) {
+  switch (plan.tile) {  // the generic kernel has square tiles only: 192 falls to 128
     case 256: return AC_BF16_LAUNCH(256);
+    case 192:
     case 128: return AC_BF16_LAUNCH(128);
     default: return AC_BF16_LAUNCH(64);
   }

@@ -427,4 +427,17 @@ static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// The four direct-to-LDS configurations by tile code.  256: eight waves in ping-pong over four 32 KB stages
+// (64 bytes of K per tile); 192 (256 x 128), 128 and 64: the rolling-refill loop with 128 bytes of K per tile,
+// eight waves of 64 x 64 / 64 x 32 or four waves of 32 x 32.
+template <class T, class EPI, int AMODE>
+static hipError_t launch_dtl_tile(int tile, const GemmParams& p, hipStream_t stream) {
+  switch (tile) {
+    case 256: return launch_dtl<T, EPI, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
+    case 192: return launch_dtl<T, EPI, 256, 128, 4, 2, AMODE, 3, 128>(p, stream);
+    case 128: return launch_dtl<T, EPI, 128, 128, 2, 4, AMODE, 3, 128>(p, stream);
+    default: return launch_dtl<T, EPI, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
+  }
+}
+
 }  // namespace ac

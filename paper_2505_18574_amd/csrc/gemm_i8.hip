@@ -3,7 +3,28 @@
 
 namespace ac {
 
-static int ktb_of_tile_i8(int tile) { return tile == 256 ? 64 : 128; }  // K bytes per tile of each kernel below
+static int ktb_of_tile(int tile) { return tile == 256 ? 64 : 128; }  // K bytes per tile of the kernel behind a tile code
+
+bool tile_dims(int32_t tile, int* bm, int* bn) {
+  switch (tile) {
+    case 64: *bm = *bn = 64; return true;
+    case 128: *bm = *bn = 128; return true;
+    case 192: *bm = 256; *bn = 128; return true;
+    case 256: *bm = *bn = 256; return true;
+    default: return false;
+  }
+}
+
+// Shared by both GEMM types: the largest tile that still gives most compute units a workgroup (thresholds from
+// exhaustive plan tables on this chip).  A tile much wider or taller than the problem wastes most of its MFMAs,
+// so a tile needs 3/4 of its edge in both dimensions.
+int choose_tile(int32_t M, int32_t N) {
+  auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+  if (M >= 192 && N >= 192 && tiles(256, 256) >= 192) return 256;
+  if (M >= 192 && N >= 96 && tiles(256, 128) >= 192) return 192;
+  if (M >= 96 && N >= 96 && tiles(128, 128) >= 128) return 128;
+  return 64;
+}
 
 // Pick block tile and K split for an M x N x K int8 problem.  The chip has 256 compute units: a launch
 // wants at least that many workgroups, and a bigger tile re-reads less of A and B.  Take the largest tile
@@ -14,10 +35,8 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   GemmPlan plan;
   plan.splits = 1;
   plan.kt_per_split = 0;
-  // a tile much wider (taller) than the problem wastes most of its MFMAs: require 3/4 of the tile edge
-  const bool ok256 = M >= 192 && N >= 192, ok128 = M >= 96 && N >= 96;
-  plan.tile = (ok256 && tiles(256) >= 192) ? 256 : ((ok128 && tiles(128) >= 192) ? 128 : 64);
-  plan.ktb = ktb_of_tile_i8(plan.tile);
+  plan.tile = choose_tile(M, N);
+  plan.ktb = ktb_of_tile(plan.tile);
   if (plan.tile == 64) {
     const int64_t t = tiles(64);
     const int nkt = (K + plan.ktb - 1) / plan.ktb;
@@ -60,13 +79,15 @@ static bool make_plan(int64_t kbytes, int tile, int ktb, int splits, GemmPlan* p
 }
 
 bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
-  if (tile != 64 && tile != 128 && tile != 256) return false;
-  return make_plan(K, tile, ktb_of_tile_i8(tile), splits, plan);
+  int bm, bn;
+  if (!tile_dims(tile, &bm, &bn)) return false;
+  return make_plan(K, tile, ktb_of_tile(tile), splits, plan);
 }
 
 bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
-  if (tile != 64 && tile != 128 && tile != 256) return false;
-  return make_plan((int64_t)K * 2, tile, tile == 256 ? 64 : 128, splits, plan);
+  int bm, bn;
+  if (!tile_dims(tile, &bm, &bn)) return false;
+  return make_plan((int64_t)K * 2, tile, ktb_of_tile(tile), splits, plan);
 }
 
 // Output stage of a split-K launch: sum the K slices, then bias / shift / saturate / ReLU, 4 outputs per thread.
@@ -90,24 +111,19 @@ hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast
   if (plan.splits > 1 && (!fast || p.partial == nullptr)) return hipErrorInvalidValue;
   if (fast) {  // direct-to-LDS kernels
     if (plan.splits > 1) {
-      hipError_t e;
-      if (plan.tile == 256) e = launch_dtl<TypeI8, EpiloguePartialI32, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
-      else if (plan.tile == 128) e = launch_dtl<TypeI8, EpiloguePartialI32, 128, 128, 2, 4, AMODE, 3, 128>(p, stream);
-      else e = launch_dtl<TypeI8, EpiloguePartialI32, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
+      hipError_t e = launch_dtl_tile<TypeI8, EpiloguePartialI32, AMODE>(plan.tile, p, stream);
       if (e != hipSuccess) return e;
       const int64_t quads = (int64_t)p.M * (p.N / 4);
       hipLaunchKernelGGL(splitk_reduce_i8_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, p);
       return hipGetLastError();
     }
-    if (plan.tile == 256) return launch_dtl<TypeI8, EpilogueI8, 256, 256, 2, 4, AMODE, 4, 64, true>(p, stream);
-    if (plan.tile == 128) return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 4, AMODE, 3, 128>(p, stream);
-    return launch_dtl<TypeI8, EpilogueI8, 64, 64, 2, 2, AMODE, 4, 128>(p, stream);
+    return launch_dtl_tile<TypeI8, EpilogueI8, AMODE>(plan.tile, p, stream);
   }
 #define AC_I8_CASE(TILE, WM, WN)                                                                         \
   case TILE:                                                                                             \
     return aligned ? launch_tile<TypeI8, EpilogueI8, TILE, TILE, WM, WN, AMODE, true>(p, stream)         \
                    : launch_tile<TypeI8, EpilogueI8, TILE, TILE, WM, WN, AMODE, false>(p, stream);
-  switch (plan.tile) {
+  switch (plan.tile == 192 ? 128 : plan.tile) {  // the generic kernel has square tiles only
     AC_I8_CASE(256, 2, 2)
     AC_I8_CASE(128, 2, 2)
     AC_I8_CASE(64, 2, 2)
@@ -132,11 +148,7 @@ hipError_t launch_gemm_i8_acc32(const GemmParams& p0, hipStream_t stream) {
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) && aligned16(p.C) && (p.ldc % 4 == 0);
   const bool fast = aligned && (p.K % 16 == 0) && (p.N % 16 == 0);
   const GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, false);
-  if (fast) {
-    if (plan.tile == 256) return launch_dtl<TypeI8, EpilogueRawI32, 256, 256, 2, 4, 0, 4, 64, true>(p, stream);
-    if (plan.tile == 128) return launch_dtl<TypeI8, EpilogueRawI32, 128, 128, 2, 4, 0, 3, 128>(p, stream);
-    return launch_dtl<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, 4, 128>(p, stream);
-  }
+  if (fast) return launch_dtl_tile<TypeI8, EpilogueRawI32, 0>(plan.tile, p, stream);
   return aligned ? launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, true>(p, stream)
                  : launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, false>(p, stream);
 }

@@ -201,7 +201,7 @@ def ac_gemm_i8_t(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, trans_a: boo
 
 
 def ac_gemm_i8_planned(A, B, bias, C, shift: int, act: int, tile: int, splits: int, workspace=None, stream=None):
-    """ac_gemm_i8 with the block tile (64, 128, 256) and the K split named by the caller.  Returns C."""
+    """ac_gemm_i8 with the block tile code (64, 128, 192, 256) and the K split named by the caller.  Returns C."""
     wp, wb = _ws(workspace)
     st = lib().ac_gemm_i8_planned(*_gemm_i8_args(A, B, bias, C), shift, act, wp, wb, tile, splits, _stream(stream))
     if st != AC_OK:
@@ -254,7 +254,7 @@ def ac_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, stream=None):
 
 
 def ac_gemm_bf16_planned(A, B, C, alpha: float, beta: float, tile: int, splits: int, workspace=None, stream=None):
-    """ac_gemm_bf16 with the block tile (64, 128, 256) and the K split named by the caller; a split sums through
+    """ac_gemm_bf16 with the block tile code (64, 128, 192, 256) and the K split named by the caller; a split sums through
     `workspace` when one is given, else with atomic adds into C.  Returns C."""
     wp, wb = _ws(workspace)
     st = lib().ac_gemm_bf16_planned(*_gemm_bf16_args(A, B, C), float(alpha), float(beta), wp, wb, tile, splits, _stream(stream))

@@ -21,8 +21,9 @@ import torch
 
 from . import ops
 
-Plan = Tuple[int, int]  # (tile, splits)
-TILES = (64, 128, 256)
+Plan = Tuple[int, int]  # (tile code, splits)
+TILES = (64, 128, 192, 256)  # tile codes in order of area; 192 is the 256 x 128 (rows x columns) tile
+TILE_DIMS = {64: (64, 64), 128: (128, 128), 192: (256, 128), 256: (256, 256)}
 MAX_WORKGROUPS = 8192          # more slices than this only add reduction traffic
 MAX_WORKSPACE_BYTES = 1 << 30  # partial sums (int32 / fp32, splits * M * N * 4 bytes) the tuner is willing to allocate
 
@@ -48,7 +49,8 @@ def valid(kind: str, M: int, N: int, K: int, plan: Plan) -> bool:
     tile, splits = plan
     if tile not in TILES or splits < 1 or (splits > 1 and splits > k_tiles(kind, K, tile)):
         return False
-    workgroups = ((M + tile - 1) // tile) * ((N + tile - 1) // tile) * splits
+    bm, bn = TILE_DIMS[tile]
+    workgroups = ((M + bm - 1) // bm) * ((N + bn - 1) // bn) * splits
     if splits > 1 and workgroups > MAX_WORKGROUPS:
         return False
     if splits > 1 and splits * M * N * 4 > MAX_WORKSPACE_BYTES:
@@ -75,7 +77,8 @@ def seed_plans(kind: str, M: int, N: int, K: int, auto: Plan, workgroups: int = 
     start on each side of the tile-size trade-off)."""
     out = [normalise(kind, K, auto)]
     for tile in TILES:
-        tiles = ((M + tile - 1) // tile) * ((N + tile - 1) // tile)
+        bm, bn = TILE_DIMS[tile]
+        tiles = ((M + bm - 1) // bm) * ((N + bn - 1) // bn)
         s = 1
         while tiles * s < workgroups and valid(kind, M, N, K, (tile, s * 2)):
             s *= 2
@@ -86,7 +89,7 @@ def seed_plans(kind: str, M: int, N: int, K: int, auto: Plan, workgroups: int = 
 
 
 def neighbours(kind: str, M: int, N: int, K: int, plan: Plan) -> List[Plan]:
-    """One step from `plan`: the next tile up or down, half or twice the split."""
+    """One step from `plan`: the next tile code up or down, half or twice the split."""
     tile, splits = plan
     i = TILES.index(tile)
     cand = [(TILES[j], splits) for j in (i - 1, i + 1) if 0 <= j < len(TILES)]

@@ -15,13 +15,13 @@ def test_k_tiles_and_normalise():
 
 def test_all_plans_and_neighbours():
     plans = tune.all_plans("i8", 128, 1024, 1024)
-    assert (64, 1) in plans and (128, 8) in plans and (256, 16) in plans
+    assert (64, 1) in plans and (128, 8) in plans and (192, 8) in plans and (256, 16) in plans
     assert all(tune.valid("i8", 128, 1024, 1024, p) for p in plans)
     assert (64, 16) not in plans  # 1024 bytes of K are 8 tiles of 128 bytes
     assert len(set(plans)) == len(plans)
     nb = tune.neighbours("i8", 128, 1024, 1024, (128, 2))
-    assert set(nb) == {(64, 2), (256, 2), (128, 1), (128, 4)}
-    assert tune.neighbours("bf16", 4096, 4096, 16, (256, 1)) == [(128, 1)]  # one K tile: nothing to split
+    assert set(nb) == {(64, 2), (192, 2), (128, 1), (128, 4)}
+    assert tune.neighbours("bf16", 4096, 4096, 16, (256, 1)) == [(192, 1)]  # one K tile: nothing to split
     # a split that would need more than the workspace cap is not offered
     assert not tune.valid("i8", 16384, 16384, 4096, (64, 2))
 
@@ -29,11 +29,11 @@ def test_all_plans_and_neighbours():
 def test_seed_plans_cover_every_tile():
     # one 256 x 256 output tile with a very deep K: each tile size starts from the split that fills 256 CUs
     seeds = tune.seed_plans("bf16", 256, 256, 524288, (64, 16))
-    assert seeds == [(64, 16), (128, 64), (256, 256)]
+    assert seeds == [(64, 16), (128, 64), (192, 128), (256, 256)]
     # a shape with plenty of tiles starts unsplit on every tile size; the library's plan comes first, once
-    assert tune.seed_plans("i8", 4096, 4096, 4096, (256, 1)) == [(256, 1), (64, 1), (128, 1)]
+    assert tune.seed_plans("i8", 4096, 4096, 4096, (256, 1)) == [(256, 1), (64, 1), (128, 1), (192, 1)]
     # splits never exceed the K tiles of the tile's kernel
-    assert tune.seed_plans("i8", 64, 64, 256, (64, 1)) == [(64, 1), (64, 2), (128, 2), (256, 4)]
+    assert tune.seed_plans("i8", 64, 64, 256, (64, 1)) == [(64, 1), (64, 2), (128, 2), (192, 2), (256, 4)]
 
 
 class FakeProblem(tune._Problem):
@@ -52,7 +52,7 @@ class FakeProblem(tune._Problem):
 
 
 def test_beam_keeps_correct_and_faster_candidates_only():
-    cost = lambda p: {64: 30.0, 128: 20.0, 256: 40.0}[p[0]] / (1 + 0.5 * (p[1] > 1)) + p[1]
+    cost = lambda p: {64: 30.0, 128: 20.0, 192: 35.0, 256: 40.0}[p[0]] / (1 + 0.5 * (p[1] > 1)) + p[1]
     # (128, 2) would be the fastest plan but produces a wrong result: it must never be chosen
     prob = FakeProblem(cost, wrong={(128, 2)})
     res = tune._search(prob, None, [(64, 1)], beam=2, iterations=6, exhaustive=False)

@@ -251,6 +251,22 @@ def supplementary(stream, only=None):
             ms = isolated_time(ww, stream, reps=5, rounds=3)
             out.append({"name": ww.name, "ms": ms, "tops": opsn / ms / 1e9, "frac_mfma_peak": opsn / ms / 1e9 / PEAK["i8"]})
             del x, wt, bs, o
+        # the batched TinyMPC forward pass (the paper's own fine-grained recurrence), one problem per batch item
+        name = "supplementary_tinympc_forward_262144x12x4x5"
+        if want(name):
+            batch, nx, nu, hz = 262144, 12, 4, 5
+            u01 = lambda *shape: torch.rand(shape, device="cuda", generator=g) * 2.0 - 1.0
+            Ad, Bd, Ki = u01(nx, nx) * 0.3, u01(nx, nu), u01(nu, nx) * 0.3
+            x0, dd = u01(batch, nx), u01(batch, hz, nu)
+            uo = torch.empty((batch, hz, nu), dtype=torch.float32, device="cuda")
+            xo = torch.empty((batch, hz + 1, nx), dtype=torch.float32, device="cuda")
+            nbytes = 4 * batch * (nx + 2 * hz * nu + (hz + 1) * nx)  # x0, d read; u, x written
+            flops = batch * hz * (2 * nu * nx + nu + 2 * nx * nx + 2 * nx * nu)
+            ww = Workload(name, "tinympc_forward_f32", "f32", flops, nbytes,
+                          lambda: ops.ac_tinympc_forward_f32(Ad, Bd, Ki, x0, dd, uo, xo), "")
+            ms = isolated_time(ww, stream, reps=5, rounds=3)
+            out.append({"name": name, "ms": ms, "gbs": nbytes / ms / 1e6, "frac_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS,
+                        "gflops": flops / ms / 1e6})
     return out + supplementary_paper_shapes(stream, only)
 
 

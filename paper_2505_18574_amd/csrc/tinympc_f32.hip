@@ -60,6 +60,106 @@ __global__ void __launch_bounds__(256) tinympc_forward_kernel(const TinyMpcParam
   }
 }
 
+// The paper's problem size (12 states, 4 controls, horizon 5) with coalesced output.  A problem's outputs are
+// 80 bytes of u and 288 bytes of trajectory, so a lane that stores its own rows touches a different memory
+// line with every store instruction of the wave.  Here a lane keeps its whole trajectory in registers, the
+// wave transposes it through a private LDS window, and the 64 problems of the wave leave as one contiguous
+// block of 16-byte stores (the problems of a wave are consecutive in memory).  No workgroup barrier after the
+// matrices are in place: a wave only ever reads window words it wrote itself.  The inputs (128 bytes per
+// problem) are loaded by their own lane: staging them through the window as well was measured slower.
+template <bool WITH_X>
+__global__ void __launch_bounds__(256) tinympc_forward_12_4_5_kernel(const TinyMpcParams p) {
+  constexpr int NX = 12, NU = 4, H = 5;
+  constexpr int XROW = (H + 1) * NX;  // 72 floats of trajectory per problem
+  constexpr int XPITCH = XROW + 4;    // LDS row pitch: keeps 16-byte alignment for the read-back
+  constexpr int UROW = H * NU;        // 20 floats of controls per problem
+  extern __shared__ __attribute__((aligned(16))) float tinympc_lds[];  // 4 windows, then the three matrices
+  float* sA = tinympc_lds + 4 * 64 * XPITCH;
+  float* sB = sA + NX * NX;
+  float* sK = sB + NX * NU;
+  for (int i = threadIdx.x; i < NX * NX; i += 256) sA[i] = p.Adyn[i];
+  for (int i = threadIdx.x; i < NX * NU; i += 256) sB[i] = p.Bdyn[i];
+  for (int i = threadIdx.x; i < NU * NX; i += 256) sK[i] = p.Kinf[i];
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t b0 = (int64_t)blockIdx.x * 256 + wave * 64;  // first problem of this wave
+  if (b0 >= p.batch) return;
+  const int nvalid = p.batch - b0 < 64 ? (int)(p.batch - b0) : 64;
+  const int64_t b = b0 + (lane < nvalid ? lane : 0);  // idle lanes recompute problem b0 and store nothing
+
+  float xs[H + 1][NX], us[H][NU], dv[UROW];
+  {
+    const v4f* x4 = (const v4f*)(p.x0 + b * NX);
+    const v4f* d4 = (const v4f*)(p.d + b * UROW);
+#pragma unroll
+    for (int q = 0; q < NX / 4; q++) {
+      const v4f v = x4[q];
+#pragma unroll
+      for (int e = 0; e < 4; e++) xs[0][4 * q + e] = v[e];
+    }
+#pragma unroll
+    for (int q = 0; q < UROW / 4; q++) {
+      const v4f v = d4[q];
+#pragma unroll
+      for (int e = 0; e < 4; e++) dv[4 * q + e] = v[e];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < H; i++) {
+#pragma unroll
+    for (int r = 0; r < NU; r++) {
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < NX; c++) s = __builtin_fmaf(sK[r * NX + c], xs[i][c], s);
+      us[i][r] = -s - dv[i * NU + r];
+    }
+    if (i + 1 < H || WITH_X) {
+#pragma unroll
+      for (int r = 0; r < NX; r++) {
+        float s = 0.f;
+#pragma unroll
+        for (int c = 0; c < NX; c++) s = __builtin_fmaf(sA[r * NX + c], xs[i][c], s);
+        float t = 0.f;
+#pragma unroll
+        for (int c = 0; c < NU; c++) t = __builtin_fmaf(sB[r * NU + c], us[i][c], t);
+        xs[i + 1][r] = s + t;
+      }
+    }
+  }
+
+  float* win = tinympc_lds + wave * 64 * XPITCH;
+  // controls: rows of 20 floats, then the block of nvalid * 20 floats in 16-byte pieces
+#pragma unroll
+  for (int i = 0; i < H; i++)
+#pragma unroll
+    for (int r = 0; r < NU; r++) win[lane * UROW + i * NU + r] = us[i][r];
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  {
+    v4f* dst = (v4f*)(p.u + b0 * UROW);
+    const int pieces = nvalid * (UROW / 4);
+#pragma unroll
+    for (int k = 0; k < UROW / 4; k++) {
+      const int q = k * 64 + lane;
+      if (q < pieces) dst[q] = *(const v4f*)(win + 4 * q);
+    }
+  }
+  if constexpr (WITH_X) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the read-back above is done before the window is reused
+#pragma unroll
+    for (int i = 0; i <= H; i++)
+#pragma unroll
+      for (int r = 0; r < NX; r++) win[lane * XPITCH + i * NX + r] = xs[i][r];
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    v4f* dst = (v4f*)(p.x_out + b0 * XROW);
+    const int pieces = nvalid * (XROW / 4);
+#pragma unroll
+    for (int k = 0; k < XROW / 4; k++) {
+      const int q = k * 64 + lane;  // 16-byte piece q of the block: problem q / 18, piece q % 18 of its row
+      if (q < pieces) dst[q] = *(const v4f*)(win + (q / (XROW / 4)) * XPITCH + (q % (XROW / 4)) * 4);
+    }
+  }
+}
+
 // Any 1 <= nx, nu <= 16: same algorithm with run-time sizes (state vectors padded to 16 registers).
 __global__ void __launch_bounds__(256) tinympc_forward_generic_kernel(const TinyMpcParams p) {
   constexpr int MAXN = 16;
@@ -124,7 +224,19 @@ __global__ void __launch_bounds__(256) tinympc_forward_generic_kernel(const Tiny
 hipError_t launch_tinympc_forward(const TinyMpcParams& p, hipStream_t stream) {
   const int64_t blocks = (p.batch + 255) / 256;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (p.nx == 12 && p.nu == 4) hipLaunchKernelGGL((tinympc_forward_kernel<12, 4>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  const bool aligned16 = ((((uintptr_t)p.x0) | ((uintptr_t)p.d) | ((uintptr_t)p.u) | ((uintptr_t)p.x_out)) & 15) == 0;
+  if (p.nx == 12 && p.nu == 4 && p.horizon == 5 && aligned16) {
+    constexpr int LDS = (4 * 64 * 76 + 12 * 12 + 12 * 4 + 4 * 12) * (int)sizeof(float);  // 78784 bytes: two workgroups per CU
+    static bool configured = false;
+    if (!configured) {
+      if (hipFuncSetAttribute((const void*)tinympc_forward_12_4_5_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess ||
+          hipFuncSetAttribute((const void*)tinympc_forward_12_4_5_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
+        return hipGetLastError();
+      configured = true;
+    }
+    if (p.x_out) hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<true>, dim3((unsigned)blocks), dim3(256), LDS, stream, p);
+    else hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<false>, dim3((unsigned)blocks), dim3(256), LDS, stream, p);
+  } else if (p.nx == 12 && p.nu == 4) hipLaunchKernelGGL((tinympc_forward_kernel<12, 4>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else hipLaunchKernelGGL(tinympc_forward_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();
 }

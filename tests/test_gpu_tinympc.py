@@ -40,11 +40,12 @@ def test_shapes(nx, nu, horizon, batch):
     np.testing.assert_array_equal(u2, u)
 
 
-def test_exact_small_integers():
+@pytest.mark.parametrize("horizon,batch", [(3, 77), (5, 77), (5, 700)])
+def test_exact_small_integers(horizon, batch):
     rng = np.random.default_rng(0)
     f = lambda shape, lo, hi: rng.integers(lo, hi + 1, size=shape).astype(np.float32)
     Adyn, Bdyn, Kinf = f((12, 12), -1, 1), f((12, 4), -1, 1), f((4, 12), -1, 1)
-    x0, d = f((77, 12), -2, 2), f((77, 3, 4), -2, 2)
+    x0, d = f((batch, 12), -2, 2), f((batch, horizon, 4), -2, 2)
     uw, xw = oracle.tinympc_forward(Adyn, Bdyn, Kinf, x0, d, return_x=True)
     assert np.abs(xw).max() < 2 ** 24  # every intermediate is an exactly representable integer
     u, xs = run_gpu(Adyn, Bdyn, Kinf, x0, d, want_x=True)
@@ -55,9 +56,11 @@ def test_exact_small_integers():
 def test_full_batch():
     Adyn, Bdyn, Kinf, x0, d = inputs.tinympc_inputs(262144, seed=6000)
     Adyn = (Adyn / 2).astype(np.float32)
-    uw = oracle.tinympc_forward(Adyn, Bdyn, Kinf, x0, d)
-    u, _ = run_gpu(Adyn, Bdyn, Kinf, x0, d, want_x=False)
-    assert rel_fro(u, uw) <= TOL
+    uw, xw = oracle.tinympc_forward(Adyn, Bdyn, Kinf, x0, d, return_x=True)
+    u, xs = run_gpu(Adyn, Bdyn, Kinf, x0, d, want_x=True)
+    assert rel_fro(u, uw) <= TOL and rel_fro(xs, xw) <= TOL
+    u2, _ = run_gpu(Adyn, Bdyn, Kinf, x0, d, want_x=False)
+    np.testing.assert_array_equal(u2, u)
 
 
 def test_empty_and_errors():

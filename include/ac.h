@@ -207,7 +207,11 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  * entry points run one named candidate so that a tuner can time each of them on the caller's own shape; the
  * results are those of ac_gemm_i8 / ac_gemm_bf16 (bit for bit for int8; for bf16 up to the summation order).
  *
- *   tile    block tile code: 64, 128, 256 = square tile of that edge; 192 = the tile of 256 rows x 128 columns
+ *   tile    block tile code: 64, 128, 256 = square tile of that edge; 192 = the tile of 256 rows x 128 columns;
+ *           int8 only: 320 / 160 = the weight-stationary kernel with 256- / 128-row tiles (a 64-column block of
+ *           B stays in LDS for all of K while tiles of A stream past it, the arrangement of the paper's best
+ *           accelerator schedule, Appendix D.1).  It takes splits == 1, operands that qualify for the
+ *           direct-to-LDS kernels (below), no bias or a bias row (bias_ld == 0), and K <= 1536 (320) / 2048 (160).
  *   splits  1 = no split; n > 1 cuts the K range into at most n slices of equal whole K tiles (64 bytes of K
  *           per tile for tile 256, 128 bytes otherwise), each slice a workgroup of its own.  Needs operands
  *           that qualify for the direct-to-LDS kernels: base pointers and row pitches of A and B multiples of
@@ -220,8 +224,11 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           is the same on every run).  bf16, workspace NULL / 0: a first kernel sets C = beta * C, then every
  *           slice adds alpha * (its product) with fp32 atomic adds, in no fixed order (slow for large M * N).
  *           Workspace rules as for ac_gemm_i8: 16-byte aligned, large enough, else AC_ERR_WORKSPACE.
- *   AC_ERR_PLAN: unknown tile code, splits < 1 or larger than the number of K tiles, or splits > 1
- *           with operands that do not qualify.  Everything else as for the unplanned call.
+ *   AC_ERR_PLAN: unknown tile code, splits < 1 or larger than the number of K tiles, or splits > 1 / a
+ *           weight-stationary tile with operands that do not qualify.  Everything else as for the unplanned call.
+ * ac_conv2d_i8_planned is ac_conv2d_i8 with the tile and K split of its implicit GEMM (M = Nb OH OW, N = Cout,
+ *           K = KH KW Cin) named by the caller; "qualify" there means 16-byte aligned in / w, Cin and Cout
+ *           multiples of 16, out 4-byte aligned; workspace size from ac_gemm_i8_planned_workspace_bytes(M, N, K, ...).
  * ac_gemm_*_auto_plan report what the unplanned call would choose for a shape (pure host arithmetic).
  * Operands that do not qualify for the direct-to-LDS kernels run on a generic kernel with square tiles, which
  * takes code 192 as 128.
@@ -231,6 +238,11 @@ ac_status ac_gemm_i8_planned(const int8_t* A, int64_t lda, const int8_t* B, int6
                              int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
                              void* workspace, size_t workspace_bytes, int32_t tile, int32_t splits, void* stream);
 size_t ac_gemm_i8_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits);
+ac_status ac_conv2d_i8_planned(const int8_t* in, const int8_t* w, const int32_t* bias, int8_t* out,
+                               int32_t Nb, int32_t H, int32_t W, int32_t Cin, int32_t Cout,
+                               int32_t KH, int32_t KW, int32_t stride, int32_t pad,
+                               int32_t shift, int32_t act,
+                               void* workspace, size_t workspace_bytes, int32_t tile, int32_t splits, void* stream);
 ac_status ac_gemm_bf16_planned(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
                                float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
                                float alpha, float beta, void* workspace, size_t workspace_bytes,

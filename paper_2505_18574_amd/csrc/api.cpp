@@ -101,6 +101,7 @@ ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t l
   p.splits = 1;
   p.partial = (int32_t*)workspace;
   if (planned && plan.splits > 1 && !ac::gemm_i8_fast_path(p)) return AC_ERR_PLAN;
+  if (planned && (tile == 320 || tile == 160) && !(ac::gemm_i8_fast_path(p) && ac::wstat_eligible(p, tile))) return AC_ERR_PLAN;
   return ac::launch_gemm_i8(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }
 
@@ -185,11 +186,11 @@ ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_
   return ac::launch_gemm_i8_acc32(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }
 
-ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, int8_t* out,
-                       int32_t Nb, int32_t H, int32_t W, int32_t Cin, int32_t Cout,
-                       int32_t KH, int32_t KW, int32_t stride, int32_t pad,
-                       int32_t shift, int32_t act,
-                       void* workspace, size_t workspace_bytes, void* stream) {
+static ac_status conv2d_i8_entry(const int8_t* in, const int8_t* w, const int32_t* bias, int8_t* out,
+                                 int32_t Nb, int32_t H, int32_t W, int32_t Cin, int32_t Cout,
+                                 int32_t KH, int32_t KW, int32_t stride, int32_t pad,
+                                 int32_t shift, int32_t act,
+                                 void* workspace, size_t workspace_bytes, bool planned, int32_t tile, int32_t splits, void* stream) {
   if (Nb < 0 || H < 0 || W < 0 || Cin < 0 || Cout < 0 || KH < 1 || KW < 1 || stride < 1 || pad < 0) return AC_ERR_SHAPE;
   if (ac_status s = check_stage(shift, act)) return s;
   if ((int64_t)KH > (int64_t)H + 2 * (int64_t)pad || (int64_t)KW > (int64_t)W + 2 * (int64_t)pad) return AC_ERR_SHAPE;
@@ -199,10 +200,13 @@ ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, i
   const int64_t in_elems = (int64_t)Nb * H * W * Cin;
   // the kernel indexes the image and the implicit GEMM with 32-bit offsets
   if (!fits_i32(M) || !fits_i32(K) || !fits_i32(in_elems + (int64_t)KH * W * Cin)) return AC_ERR_SHAPE;
+  ac::GemmPlan plan;
+  if (planned && !ac::make_plan_i8((int32_t)K, tile, splits, &plan)) return AC_ERR_PLAN;
   if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;
-  if (workspace && (((uintptr_t)workspace & 15) != 0 ||
-                    workspace_bytes < ac_gemm_i8_workspace_bytes((int32_t)M, Cout, (int32_t)K)))
-    return AC_ERR_WORKSPACE;
+  const size_t need = planned ? ac_gemm_i8_planned_workspace_bytes((int32_t)M, Cout, (int32_t)K, tile, splits)
+                              : ac_gemm_i8_workspace_bytes((int32_t)M, Cout, (int32_t)K);
+  if (workspace && (((uintptr_t)workspace & 15) != 0 || workspace_bytes < need)) return AC_ERR_WORKSPACE;
+  if (planned && need > 0 && !workspace) return AC_ERR_WORKSPACE;
   if (M == 0 || Cout == 0) return AC_OK;
   if (!out || (K > 0 && (!in || !w))) return AC_ERR_NULL;
   if ((const void*)out == (const void*)in || (const void*)out == (const void*)w || (const void*)out == (const void*)bias)
@@ -215,7 +219,31 @@ ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, i
   p.H = H; p.W = W; p.Cin = Cin; p.KW = KW; p.OH = (int32_t)OH; p.OW = (int32_t)OW; p.stride = stride; p.pad = pad;
   p.splits = 1;
   p.partial = (int32_t*)workspace;
-  return ac::launch_conv2d_i8(p, (hipStream_t)stream) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+  if (planned) {
+    // a K split or the weight-stationary kernel need the direct-to-LDS path: 16-byte aligned operands, channel
+    // counts in multiples of 16
+    const bool fast = (((uintptr_t)in | (uintptr_t)w) & 15) == 0 && Cin % 16 == 0 && Cout % 16 == 0 && ((uintptr_t)out & 3) == 0;
+    const bool ws = tile == 320 || tile == 160;
+    if ((plan.splits > 1 || ws) && !fast) return AC_ERR_PLAN;
+    if (ws && !ac::wstat_eligible(p, tile)) return AC_ERR_PLAN;
+  }
+  return ac::launch_conv2d_i8(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
+}
+
+ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, int8_t* out,
+                       int32_t Nb, int32_t H, int32_t W, int32_t Cin, int32_t Cout,
+                       int32_t KH, int32_t KW, int32_t stride, int32_t pad,
+                       int32_t shift, int32_t act,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  return conv2d_i8_entry(in, w, bias, out, Nb, H, W, Cin, Cout, KH, KW, stride, pad, shift, act, workspace, workspace_bytes, false, 0, 0, stream);
+}
+
+ac_status ac_conv2d_i8_planned(const int8_t* in, const int8_t* w, const int32_t* bias, int8_t* out,
+                               int32_t Nb, int32_t H, int32_t W, int32_t Cin, int32_t Cout,
+                               int32_t KH, int32_t KW, int32_t stride, int32_t pad,
+                               int32_t shift, int32_t act,
+                               void* workspace, size_t workspace_bytes, int32_t tile, int32_t splits, void* stream) {
+  return conv2d_i8_entry(in, w, bias, out, Nb, H, W, Cin, Cout, KH, KW, stride, pad, shift, act, workspace, workspace_bytes, true, tile, splits, stream);
 }
 
 ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,

@@ -1,5 +1,5 @@
 // int8 GEMM / implicit-GEMM convolution with the accelerator output stage: tile selection, split-K and launch.
-#include "gemm_dtl.hpp"
+#include "gemm_wstat.hpp"
 
 namespace ac {
 
@@ -11,6 +11,8 @@ bool tile_dims(int32_t tile, int* bm, int* bn) {
     case 128: *bm = *bn = 128; return true;
     case 192: *bm = 256; *bn = 128; return true;
     case 256: *bm = *bn = 256; return true;
+    case 320: *bm = 256; *bn = 64; return true;  // weight-stationary kernel
+    case 160: *bm = 128; *bn = 64; return true;
     default: return false;
   }
 }
@@ -26,6 +28,28 @@ int choose_tile(int32_t M, int32_t N) {
   return 64;
 }
 
+// The weight-stationary kernel takes direct-to-LDS operands (checked by the caller), no bias or a bias row, and a
+// K whose 64-column block of B fits in LDS beside the ring of A stages.
+bool wstat_eligible(const GemmParams& p, int tile) {
+  int bm;
+  if (!wstat_tile_rows(tile, &bm)) return false;
+  const int nkt = (p.K + 127) / 128;
+  return p.K >= 1 && nkt <= wstat_max_kt(tile) && (p.bias == nullptr || p.bias_ld == 0);
+}
+
+// Shapes the library hands to the weight-stationary kernel by itself (from timings of every tile code on this
+// chip): a narrow output (at most two 64-column blocks, so A passes through the compute units at most twice),
+// a K short enough to stay resident beside the deep ring, and enough 256-row tiles to give most compute units
+// a stream of their own.  Smaller problems are faster on the 64 x 64 tiles, wider ones on the big square tiles.
+// 0 = not this kernel.
+int choose_wstat_tile(int32_t M, int32_t N, int32_t K) {
+  if (M < 1 || N < 1 || N > 128 || K < 16) return 0;
+  const int nkt = (K + 127) / 128;
+  const int64_t nblk = (N + 63) / 64;
+  if (((M + 255) / 256) * nblk < 192) return 0;
+  return nkt <= wstat_max_kt(320) ? 320 : 0;
+}
+
 // Pick block tile and K split for an M x N x K int8 problem.  The chip has 256 compute units: a launch
 // wants at least that many workgroups, and a bigger tile re-reads less of A and B.  Take the largest tile
 // that still yields enough workgroups; when even the smallest tile leaves most CUs idle and K is deep, slice
@@ -37,6 +61,10 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   plan.kt_per_split = 0;
   plan.tile = choose_tile(M, N);
   plan.ktb = ktb_of_tile(plan.tile);
+  if (const int ws = choose_wstat_tile(M, N, K)) {
+    plan.tile = ws;
+    return plan;
+  }
   if (plan.tile == 64) {
     const int64_t t = tiles(64);
     const int nkt = (K + plan.ktb - 1) / plan.ktb;
@@ -81,12 +109,13 @@ static bool make_plan(int64_t kbytes, int tile, int ktb, int splits, GemmPlan* p
 bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
   int bm, bn;
   if (!tile_dims(tile, &bm, &bn)) return false;
+  if (wstat_tile_rows(tile, &bm) && splits != 1) return false;  // the weight-stationary kernel keeps all of K resident
   return make_plan(K, tile, ktb_of_tile(tile), splits, plan);
 }
 
 bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
   int bm, bn;
-  if (!tile_dims(tile, &bm, &bn)) return false;
+  if (!tile_dims(tile, &bm, &bn) || wstat_tile_rows(tile, &bm)) return false;
   return make_plan((int64_t)K * 2, tile, ktb_of_tile(tile), splits, plan);
 }
 
@@ -105,10 +134,19 @@ __global__ void __launch_bounds__(256) splitk_reduce_i8_kernel(const GemmParams 
 
 template <int AMODE>
 hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast, const GemmPlan* forced) {
-  const GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr);
+  GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr);
+  int ws_bm;
+  if (!forced && wstat_tile_rows(plan.tile, &ws_bm) && !(fast && wstat_eligible(p, plan.tile))) {
+    plan.tile = choose_tile(p.M, p.N);  // operands the weight-stationary kernel does not take: the tiled kernels
+    plan.ktb = ktb_of_tile(plan.tile);
+  }
   p.splits = plan.splits;
   p.kt_per_split = plan.kt_per_split;
   if (plan.splits > 1 && (!fast || p.partial == nullptr)) return hipErrorInvalidValue;
+  if (wstat_tile_rows(plan.tile, &ws_bm)) {
+    if (!fast || !wstat_eligible(p, plan.tile)) return hipErrorInvalidValue;
+    return launch_wstat_tile<AMODE>(plan.tile, p, stream);
+  }
   if (fast) {  // direct-to-LDS kernels
     if (plan.splits > 1) {
       hipError_t e = launch_dtl_tile<TypeI8, EpiloguePartialI32, AMODE>(plan.tile, p, stream);
@@ -147,8 +185,7 @@ hipError_t launch_gemm_i8_acc32(const GemmParams& p0, hipStream_t stream) {
   p.kt_per_split = 0;
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) && aligned16(p.C) && (p.ldc % 4 == 0);
   const bool fast = aligned && (p.K % 16 == 0) && (p.N % 16 == 0);
-  const GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, false);
-  if (fast) return launch_dtl_tile<TypeI8, EpilogueRawI32, 0>(plan.tile, p, stream);
+  if (fast) return launch_dtl_tile<TypeI8, EpilogueRawI32, 0>(choose_tile(p.M, p.N), p, stream);
   return aligned ? launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, true>(p, stream)
                  : launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, false>(p, stream);
 }
@@ -159,11 +196,11 @@ hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream, const GemmPla
   return dispatch_i8<0>(p, stream, aligned, gemm_i8_fast_path(p), forced);
 }
 
-hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream) {
+hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced) {
   // Fast path: channel counts in multiples of 16 so that a 16-byte K chunk stays inside one kernel tap.
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.Cin % 16 == 0) && (p.ldb % 16 == 0) &&
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
-  return dispatch_i8<1>(p, stream, aligned, aligned, nullptr);
+  return dispatch_i8<1>(p, stream, aligned, aligned, forced);
 }
 
 }  // namespace ac

@@ -134,7 +134,7 @@ struct EpilogueI8 {
     if (act) q = q < 0 ? 0 : q;
     return q;
   }
-  template <bool VEC>
+  template <bool VEC, bool ADD_BIAS = true>
   static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
     int8_t* C = (int8_t*)p.C;
@@ -143,7 +143,7 @@ struct EpilogueI8 {
 #pragma unroll
     for (int e = 0; e < 4; e++) {
       int b = 0;
-      if (p.bias && (full || n + e < p.N)) b = p.bias_ld == 0 ? p.bias[n + e] : p.bias[(int64_t)m * p.bias_ld + n + e];
+      if (ADD_BIAS && p.bias && (full || n + e < p.N)) b = p.bias_ld == 0 ? p.bias[n + e] : p.bias[(int64_t)m * p.bias_ld + n + e];
       v[e] = requant(a[e] + b, p.shift, p.act);
     }
     int8_t* dst = C + (int64_t)m * p.ldc + n;
@@ -174,7 +174,54 @@ struct EpilogueI8 {
       }
     }
   }
-  template <class ACC>
+  // Fast form of requant() for 1 <= shift <= 23 with the lower clamp bound as a constant (0 folds the ReLU in):
+  // floor((t + 2^(shift-1) - 1 + bit) / 2^shift) with bit = bit `shift` of t rounds halves to even.  For these
+  // shifts every |t| >= 2^30 saturates, so clamping t to 30 bits first changes no result and keeps the rounding
+  // add inside int32.  `rnd` = 2^(shift-1) - 1.  Five VALU instructions per value.
+  template <int LO>
+  static __device__ __forceinline__ int requant_fast(int t, int shift, int rnd) {
+    int c = t < -(1 << 30) ? -(1 << 30) : t;
+    c = c > (1 << 30) - 1 ? (1 << 30) - 1 : c;
+    const int bit = (int)__builtin_amdgcn_ubfe((unsigned)c, (unsigned)shift, 1u);
+    int q = (c + bit + rnd) >> shift;
+    q = q < LO ? LO : q;
+    return q > 127 ? 127 : q;
+  }
+  // Four values already in [-128, 127] -> their low bytes in one dword (v0 lowest).
+  static __device__ __forceinline__ unsigned pack4(int v0, int v1, int v2, int v3) {
+    const unsigned lo = __builtin_amdgcn_perm((unsigned)v1, (unsigned)v0, 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm((unsigned)v3, (unsigned)v2, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+  }
+  // MODE 0: any shift / activation (requant); 1: fast form with ReLU; 2: fast form without.
+  template <int MODE>
+  static __device__ __forceinline__ unsigned quant4(const int* t, int shift, int act, int rnd) {
+    int v[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      if constexpr (MODE == 1) v[e] = requant_fast<0>(t[e], shift, rnd);
+      else if constexpr (MODE == 2) v[e] = requant_fast<-128>(t[e], shift, rnd);
+      else v[e] = requant(t[e], shift, act);
+    }
+    return pack4(v[0], v[1], v[2], v[3]);
+  }
+  // The 16 values of one lane (accumulator + bias) -> 16 output bytes in column order after the lane exchange:
+  // lanes l and l + 32 hold interleaved 4-byte pieces of the same row.  Swapping the upper half of d[0] (d[1])
+  // with the lower half of d[2] (d[3]) leaves 16 consecutive bytes in every lane: columns 0..15 in lanes 0..31,
+  // columns 16..31 in lanes 32..63, so a row leaves as two whole 16-byte stores.
+  template <int MODE>
+  static __device__ __forceinline__ v4i quant16(const int* t, int shift, int act) {
+    const int rnd = shift > 0 ? (1 << (shift - 1)) - 1 : 0;
+    unsigned d[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) d[q] = quant4<MODE>(t + 4 * q, shift, act, rnd);
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    const v2u s02 = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
+    const v2u s13 = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
+    return (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+  }
+  // BIASED: the accumulators already hold the bias (a kernel that starts its sums from the bias row).
+  template <bool BIASED = false, class ACC>
   static __device__ __forceinline__ void tile(const GemmParams& p, int mrow0, int ncol0, const ACC& acc, int lane, int, const Pre& pre) {
     const int m = mrow0 + (lane & 31);
     if (m >= p.M || ncol0 >= p.N) return;
@@ -182,33 +229,31 @@ struct EpilogueI8 {
     const bool wide = ncol0 + 32 <= p.N && (p.ldc & 15) == 0 && (((uintptr_t)C) & 15) == 0;
     const bool row_bias = p.bias && p.bias_ld == 0;
     if (wide) {
-      unsigned d[4];
+      int t[16];
 #pragma unroll
       for (int q = 0; q < 4; q++) {
         const int n = ncol0 + 8 * q + 4 * (lane >> 5);
-        int v[4];
 #pragma unroll
         for (int e = 0; e < 4; e++) {
-          int b = row_bias ? pre.bias[q][e] : 0;
-          if (p.bias && !row_bias) b = p.bias[(int64_t)m * p.bias_ld + n + e];
-          v[e] = requant(acc[4 * q + e] + b, p.shift, p.act);
+          int b = 0;
+          if constexpr (!BIASED) {
+            b = row_bias ? pre.bias[q][e] : 0;
+            if (p.bias && !row_bias) b = p.bias[(int64_t)m * p.bias_ld + n + e];
+          }
+          t[4 * q + e] = acc[4 * q + e] + b;
         }
-        d[q] = (unsigned)(v[0] & 0xff) | ((unsigned)(v[1] & 0xff) << 8) | ((unsigned)(v[2] & 0xff) << 16) | ((unsigned)(v[3] & 0xff) << 24);
       }
-      // Lanes l and l + 32 hold interleaved 4-byte pieces of the same row.  Swapping the upper half of d[0]
-      // (d[1]) with the lower half of d[2] (d[3]) leaves 16 consecutive bytes in every lane: columns 0..15 in
-      // lanes 0..31, columns 16..31 in lanes 32..63, so a row leaves as two whole 16-byte stores.
-      typedef unsigned v2u __attribute__((ext_vector_type(2)));
-      const v2u s02 = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
-      const v2u s13 = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
-      const v4i o = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+      v4i o;
+      if (p.shift >= 1 && p.shift <= 23) o = p.act ? quant16<1>(t, p.shift, p.act) : quant16<2>(t, p.shift, p.act);
+      else o = quant16<0>(t, p.shift, p.act);
       *(v4i*)(C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5)) = o;
     } else {
 #pragma unroll
       for (int q = 0; q < 4; q++) {
         const int n = ncol0 + 8 * q + 4 * (lane >> 5);
         int a4[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-        store4<true>(p, m, n, a4);
+        if constexpr (BIASED) store4<true, false>(p, m, n, a4);
+        else store4<true>(p, m, n, a4);
       }
     }
   }

@@ -25,7 +25,7 @@ AC_ACT_NONE, AC_ACT_RELU = 0, 1
 # every symbol include/ac.h declares
 EXPORTS = ("ac_gemm_i8", "ac_gemm_i8_workspace_bytes", "ac_conv2d_i8", "ac_gemm_bf16", "ac_batched_gemm_f32",
            "ac_tinympc_forward_f32", "ac_gemm_i8_acc32",
-           "ac_gemm_i8_t", "ac_gemm_i8_planned", "ac_gemm_i8_planned_workspace_bytes", "ac_gemm_bf16_planned",
+           "ac_gemm_i8_t", "ac_gemm_i8_planned", "ac_conv2d_i8_planned", "ac_gemm_i8_planned_workspace_bytes", "ac_gemm_bf16_planned",
            "ac_gemm_bf16_planned_workspace_bytes",
            "ac_gemm_i8_auto_plan", "ac_gemm_bf16_auto_plan",
            "ac_status_string", "ac_version")
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.ac_gemm_i8_workspace_bytes.argtypes = [i32, i32, i32]
         L.ac_conv2d_i8.restype = i32
         L.ac_conv2d_i8.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.ac_conv2d_i8_planned.restype = i32
+        L.ac_conv2d_i8_planned.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, i32, i32, vp]
         L.ac_gemm_bf16.restype = i32
         L.ac_gemm_bf16.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, f32, f32, vp]
         L.ac_batched_gemm_f32.restype = i32
@@ -201,7 +203,7 @@ def ac_gemm_i8_t(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, trans_a: boo
 
 
 def ac_gemm_i8_planned(A, B, bias, C, shift: int, act: int, tile: int, splits: int, workspace=None, stream=None):
-    """ac_gemm_i8 with the block tile code (64, 128, 192, 256) and the K split named by the caller.  Returns C."""
+    """ac_gemm_i8 with the block tile code (64, 128, 192, 256; 320 / 160 = weight-stationary) and the K split named by the caller.  Returns C."""
     wp, wb = _ws(workspace)
     st = lib().ac_gemm_i8_planned(*_gemm_i8_args(A, B, bias, C), shift, act, wp, wb, tile, splits, _stream(stream))
     if st != AC_OK:
@@ -209,8 +211,11 @@ def ac_gemm_i8_planned(A, B, bias, C, shift: int, act: int, tile: int, splits: i
     return C
 
 
-def ac_conv2d_i8(x, w, bias, out, stride: int, pad: int, shift: int, act: int = AC_ACT_NONE, workspace=None, stream=None):
-    """out[Nb,OH,OW,Cout] int8 = stage(conv(x[Nb,H,W,Cin], w[KH,KW,Cin,Cout]) + bias[Cout]).  Returns out."""
+def ac_conv2d_i8(x, w, bias, out, stride: int, pad: int, shift: int, act: int = AC_ACT_NONE, workspace=None, stream=None,
+                 plan=None):
+    """out[Nb,OH,OW,Cout] int8 = stage(conv(x[Nb,H,W,Cin], w[KH,KW,Cin,Cout]) + bias[Cout]).  Returns out.
+
+    plan = (tile, splits) goes through ac_conv2d_i8_planned."""
     for t, name in ((x, "x"), (w, "w"), (out, "out")):
         if t.dtype != torch.int8 or t.dim() != 4 or not t.is_contiguous() or not t.is_cuda:
             raise ValueError(f"{name}: expected a dense 4-D int8 device tensor")
@@ -225,6 +230,12 @@ def ac_conv2d_i8(x, w, bias, out, stride: int, pad: int, shift: int, act: int = 
     if tuple(out.shape) != (Nb, OH, OW, Cout):
         raise ValueError(f"out: expected shape {(Nb, OH, OW, Cout)}")
     wp, wb = _ws(workspace)
+    if plan is not None:
+        st = lib().ac_conv2d_i8_planned(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), Nb, H, W, Cin, Cout, KH, KW, stride, pad,
+                                        shift, act, wp, wb, int(plan[0]), int(plan[1]), _stream(stream))
+        if st != AC_OK:
+            raise AcError(st, "ac_conv2d_i8_planned")
+        return out
     st = lib().ac_conv2d_i8(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), Nb, H, W, Cin, Cout, KH, KW, stride, pad,
                             shift, act, wp, wb, _stream(stream))
     if st != AC_OK:

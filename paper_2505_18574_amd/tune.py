@@ -23,7 +23,10 @@ from . import ops
 
 Plan = Tuple[int, int]  # (tile code, splits)
 TILES = (64, 128, 192, 256)  # tile codes in order of area; 192 is the 256 x 128 (rows x columns) tile
-TILE_DIMS = {64: (64, 64), 128: (128, 128), 192: (256, 128), 256: (256, 256)}
+TILE_DIMS = {64: (64, 64), 128: (128, 128), 192: (256, 128), 256: (256, 256), 160: (128, 64), 320: (256, 64)}
+# int8 only: the weight-stationary kernel (128- / 256-row tiles, 64 columns, all of K resident in LDS, no K split)
+WS_TILES = (160, 320)
+WS_MAX_K = {160: 2048, 320: 1536}
 MAX_WORKGROUPS = 8192          # more slices than this only add reduction traffic
 MAX_WORKSPACE_BYTES = 1 << 30  # partial sums (int32 / fp32, splits * M * N * 4 bytes) the tuner is willing to allocate
 
@@ -47,6 +50,8 @@ def normalise(kind: str, K: int, plan: Plan) -> Plan:
 
 def valid(kind: str, M: int, N: int, K: int, plan: Plan) -> bool:
     tile, splits = plan
+    if tile in WS_TILES:
+        return kind == "i8" and splits == 1 and 1 <= K <= WS_MAX_K[tile]
     if tile not in TILES or splits < 1 or (splits > 1 and splits > k_tiles(kind, K, tile)):
         return False
     bm, bn = TILE_DIMS[tile]
@@ -68,6 +73,7 @@ def all_plans(kind: str, M: int, N: int, K: int) -> List[Plan]:
             if q not in out:
                 out.append(q)
             s *= 2
+    out += [(t, 1) for t in WS_TILES if valid(kind, M, N, K, (t, 1))]
     return out
 
 
@@ -85,15 +91,19 @@ def seed_plans(kind: str, M: int, N: int, K: int, auto: Plan, workgroups: int = 
         q = normalise(kind, K, (tile, s))
         if valid(kind, M, N, K, q) and q not in out:
             out.append(q)
+    out += [(t, 1) for t in WS_TILES if valid(kind, M, N, K, (t, 1)) and (t, 1) not in out]
     return out
 
 
 def neighbours(kind: str, M: int, N: int, K: int, plan: Plan) -> List[Plan]:
     """One step from `plan`: the next tile code up or down, half or twice the split."""
     tile, splits = plan
-    i = TILES.index(tile)
-    cand = [(TILES[j], splits) for j in (i - 1, i + 1) if 0 <= j < len(TILES)]
-    cand += [(tile, max(1, splits // 2)), (tile, splits * 2)]
+    if tile in WS_TILES:  # its neighbours: the other row-tile height, and the tiled kernels of similar height
+        cand = [(WS_TILES[1 - WS_TILES.index(tile)], 1), (64, 1), (192, 1)]
+    else:
+        i = TILES.index(tile)
+        cand = [(TILES[j], splits) for j in (i - 1, i + 1) if 0 <= j < len(TILES)]
+        cand += [(tile, max(1, splits // 2)), (tile, splits * 2)]
     out: List[Plan] = []
     for c in cand:
         if valid(kind, M, N, K, c):
@@ -174,7 +184,11 @@ def _evaluate(prob: _Problem, plan: Plan, gate, seen: Dict[Plan, Trial]) -> Tria
     if plan in seen:
         return seen[plan]
     prob.out.zero_()
-    prob.run(plan)
+    try:
+        prob.run(plan)
+    except ops.AcError:  # a plan these operands cannot take (alignment, bias layout): not a candidate
+        seen[plan] = Trial(plan, False, None)
+        return seen[plan]
     prob.sync()
     ok = bool(gate(prob.out))
     trial = Trial(plan, ok, prob.measure(lambda: prob.run(plan)) if ok else None)

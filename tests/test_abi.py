@@ -107,6 +107,8 @@ def test_auto_plans_are_host_arithmetic():
     # the benchmark shapes: big square problems take the 256 tile; narrow ones fall back to 64
     assert ops.ac_gemm_bf16_auto_plan(4096, 4096, 4096) == (256, 1)
     assert ops.ac_gemm_i8_auto_plan(3136, 64, 576) == (64, 1)
+    assert ops.ac_gemm_i8_auto_plan(65536, 64, 576) == (320, 1)   # long, narrow, short K: weight-stationary kernel
+    assert ops.ac_gemm_i8_auto_plan(65536, 64, 4096) == (64, 1)   # K too deep to stay resident
     tile, splits = ops.ac_gemm_i8_auto_plan(49, 2048, 4608, True)
     assert tile == 64 and splits > 1
     assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, False) == (64, 1)

@@ -33,7 +33,12 @@ def test_seed_plans_cover_every_tile():
     # a shape with plenty of tiles starts unsplit on every tile size; the library's plan comes first, once
     assert tune.seed_plans("i8", 4096, 4096, 4096, (256, 1)) == [(256, 1), (64, 1), (128, 1), (192, 1)]
     # splits never exceed the K tiles of the tile's kernel
-    assert tune.seed_plans("i8", 64, 64, 256, (64, 1)) == [(64, 1), (64, 2), (128, 2), (192, 2), (256, 4)]
+    # ... and a K short enough to stay resident also starts on the weight-stationary tiles
+    assert tune.seed_plans("i8", 64, 64, 256, (64, 1)) == [(64, 1), (64, 2), (128, 2), (192, 2), (256, 4), (160, 1), (320, 1)]
+    assert tune.valid("i8", 4096, 64, 1536, (320, 1)) and not tune.valid("i8", 4096, 64, 1537, (320, 1))
+    assert tune.valid("i8", 4096, 64, 2048, (160, 1)) and not tune.valid("i8", 4096, 64, 512, (160, 2))
+    assert not tune.valid("bf16", 4096, 64, 512, (320, 1))
+    assert set(tune.neighbours("i8", 4096, 64, 512, (320, 1))) == {(160, 1), (64, 1), (192, 1)}
 
 
 class FakeProblem(tune._Problem):
@@ -52,7 +57,7 @@ class FakeProblem(tune._Problem):
 
 
 def test_beam_keeps_correct_and_faster_candidates_only():
-    cost = lambda p: {64: 30.0, 128: 20.0, 192: 35.0, 256: 40.0}[p[0]] / (1 + 0.5 * (p[1] > 1)) + p[1]
+    cost = lambda p: {64: 30.0, 128: 20.0, 192: 35.0, 256: 40.0, 160: 50.0, 320: 60.0}[p[0]] / (1 + 0.5 * (p[1] > 1)) + p[1]
     # (128, 2) would be the fastest plan but produces a wrong result: it must never be chosen
     prob = FakeProblem(cost, wrong={(128, 2)})
     res = tune._search(prob, None, [(64, 1)], beam=2, iterations=6, exhaustive=False)

@@ -212,6 +212,11 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           B stays in LDS for all of K while tiles of A stream past it, the arrangement of the paper's best
  *           accelerator schedule, Appendix D.1).  It takes splits == 1, operands that qualify for the
  *           direct-to-LDS kernels (below), no bias or a bias row (bias_ld == 0), and K <= 1536 (320) / 2048 (160).
+ *           ac_conv2d_i8_planned only: 321 / 161 = the convolution patch kernel with units of 256 / 128 output
+ *           pixels: the weights of a 64-channel block AND the image patch a unit needs are both held in LDS, so
+ *           every input pixel is fetched once per unit instead of once per kernel tap.  It takes splits == 1,
+ *           Cin a multiple of 32, K <= 2048, out 16-byte aligned with Cout a multiple of 16, and a patch that
+ *           fits: 2 x (patch rows x patch width x (Cin + 16)) + 64 K bytes <= 160 KB.
  *   splits  1 = no split; n > 1 cuts the K range into at most n slices of equal whole K tiles (64 bytes of K
  *           per tile for tile 256, 128 bytes otherwise), each slice a workgroup of its own.  Needs operands
  *           that qualify for the direct-to-LDS kernels: base pointers and row pitches of A and B multiples of

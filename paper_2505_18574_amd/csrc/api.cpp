@@ -102,6 +102,7 @@ ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t l
   p.partial = (int32_t*)workspace;
   if (planned && plan.splits > 1 && !ac::gemm_i8_fast_path(p)) return AC_ERR_PLAN;
   if (planned && (tile == 320 || tile == 160) && !(ac::gemm_i8_fast_path(p) && ac::wstat_eligible(p, tile))) return AC_ERR_PLAN;
+  if (planned && (tile == 321 || tile == 161)) return AC_ERR_PLAN;  // the patch kernel is a convolution kernel
   return ac::launch_gemm_i8(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }
 
@@ -223,9 +224,10 @@ static ac_status conv2d_i8_entry(const int8_t* in, const int8_t* w, const int32_
     // a K split or the weight-stationary kernel need the direct-to-LDS path: 16-byte aligned operands, channel
     // counts in multiples of 16
     const bool fast = (((uintptr_t)in | (uintptr_t)w) & 15) == 0 && Cin % 16 == 0 && Cout % 16 == 0 && ((uintptr_t)out & 3) == 0;
-    const bool ws = tile == 320 || tile == 160;
-    if ((plan.splits > 1 || ws) && !fast) return AC_ERR_PLAN;
+    const bool ws = tile == 320 || tile == 160, patch = tile == 321 || tile == 161;
+    if ((plan.splits > 1 || ws || patch) && !fast) return AC_ERR_PLAN;
     if (ws && !ac::wstat_eligible(p, tile)) return AC_ERR_PLAN;
+    if (patch && !ac::conv_halo_eligible(p, tile)) return AC_ERR_PLAN;
   }
   return ac::launch_conv2d_i8(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }

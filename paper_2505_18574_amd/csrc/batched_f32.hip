@@ -134,8 +134,8 @@ __global__ void __launch_bounds__(256) batched_f32_kernel(const BatchedParams p)
 
 // ---- 12 x 12 streaming kernel -----------------------------------------------------------------------------
 // Each wavefront works alone (no workgroup barrier anywhere): it walks over groups of 4 consecutive items,
-// brings a group's A, B, x, d into its private LDS window with direct-to-LDS loads (two windows, the next
-// group is in flight while the current one is computed), and stores C and y straight from registers.
+// brings a group's A, B, x, d into its private LDS window with direct-to-LDS loads (three windows, the next two
+// groups are in flight while the current one is computed), and stores C and y straight from registers.
 // 16 lanes own one item: lane (bi, bj) holds rows 3bi..3bi+2 and columns 4bj..4bj+3 of C (bj == 3 idles in the
 // product but takes part in the quad reduction), so every store is a whole 16-byte chunk of a C row.
 #define AC_LDS3(T, p) ((__attribute__((address_space(3))) T*)(p))
@@ -154,7 +154,7 @@ __global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const 
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_b[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  unsigned char* win0 = lds_b + wave * 2 * B12_WIN;
+  unsigned char* win0 = lds_b + wave * 3 * B12_WIN;
   const unsigned win0_addr = (unsigned)(uintptr_t)AC_LDS3(unsigned char, win0);
   const int64_t ngroups = (p.batch + B12_GROUP - 1) / B12_GROUP;
   const int64_t stride = (int64_t)gridDim.x * B12_WAVES;
@@ -181,13 +181,26 @@ __global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const 
 
   const int it = lane >> 4, sub = lane & 15, bi = sub >> 2, bj = sub & 3;
   const int cb = bj < 3 ? bj : 2;  // idle lanes shadow column block 2
+  // Three windows in rotation: while group g is computed, groups g + stride and g + 2 stride are in flight.
+  // Vector-memory operations of a wave complete in issue order, loads and stores alike, so the wait at the end of
+  // a step names how many younger operations may still be pending instead of draining everything: the loads of
+  // the next group are followed by the stores of the previous step, the loads of the group after, and the stores
+  // of this step.  Waiting for the stores themselves would put a write round trip into every step.
+  // A full group issues 8 loads (3 + 3 for A and B, x, d) and the step 3 + 1 stores (C rows, y); any other case
+  // (a partial last group, absent operands) takes the plain wait for everything.
+  constexpr int LOADS = 8, STORES = 4;
+  const bool counted = has_x && has_d && p.C != nullptr;
   int64_t g = (int64_t)blockIdx.x * B12_WAVES + wave;
   int w = 0;
+  bool first = true;
   if (g < ngroups) issue(g, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (g + stride < ngroups) issue(g + stride, 1);
+  if (counted && (g + stride + 1) * B12_GROUP <= p.batch) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   for (; g < ngroups; g += stride) {
-    const int64_t gn = g + stride;
-    if (gn < ngroups) issue(gn, w ^ 1);
+    const int64_t gn = g + 2 * stride;
+    const int w2 = w >= 1 ? w - 1 : 2;  // window of group g + 2 stride == window of group g - stride
+    if (gn < ngroups) issue(gn, w2);
     const int64_t item = g * B12_GROUP + it;
     if (item < p.batch) {
       const unsigned char* Wn = win0 + w * B12_WIN;
@@ -229,15 +242,21 @@ __global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const 
         }
         if (bj == 0) {
           const float* dv = (const float*)(Wn + 2 * B12_MAT + B12_VEC + it * 48) + 3 * bi;
-          float* yg = p.y + item * 12 + 3 * bi;
-#pragma unroll
-          for (int i = 0; i < 3; i++) yg[i] = s[i] + (has_d ? dv[i] : 0.f);
+          typedef float v3f __attribute__((ext_vector_type(3)));
+          const v3f yv = {s[0] + (has_d ? dv[0] : 0.f), s[1] + (has_d ? dv[1] : 0.f), s[2] + (has_d ? dv[2] : 0.f)};
+          *(v3f*)(p.y + item * 12 + 3 * bi) = yv;  // one 12-byte store instruction (the wait below counts instructions)
         }
       }
     }
     // the next group's loads must have landed; every LDS read of this window has been consumed above
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    w ^= 1;
+    if (counted && (gn + 1) * B12_GROUP <= p.batch) {
+      if (first) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(LOADS + STORES) : "memory");  // no earlier step, no earlier stores
+      else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(STORES + LOADS + STORES) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    }
+    first = false;
+    w = w == 2 ? 0 : w + 1;
   }
 }
 
@@ -246,9 +265,11 @@ hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream) {
   const bool vec = al(p.A) && al(p.B) && al(p.C) && al(p.x) && al(p.d);
   const int n = p.n;
   if (n == 12 && vec) {
-    // streaming kernel: two persistent workgroups of B12_WAVES waves per CU, each wave walking over groups of
-    // B12_GROUP items through its own pair of LDS windows
-    constexpr int WGS_PER_CU = 2;
+    // streaming kernel: one persistent workgroup of B12_WAVES waves per CU, each wave walking over groups of
+    // B12_GROUP items through its own three LDS windows.  More waves per CU were measured slower (4 waves
+    // 88 us, 5: 97, 6: 97, 8: 96 for 262144 items; 2 waves: 122): past 4 waves the extra requests in flight only
+    // spread the six streams over more DRAM pages.
+    constexpr int WGS_PER_CU = 1;
     static int cus = 0;
     if (cus == 0) {
       int dev = 0;
@@ -257,7 +278,7 @@ hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream) {
     const int64_t ngroups = (p.batch + B12_GROUP - 1) / B12_GROUP;
     int64_t wgs = (ngroups + B12_WAVES - 1) / B12_WAVES;
     if (wgs > (int64_t)cus * WGS_PER_CU) wgs = (int64_t)cus * WGS_PER_CU;
-    hipLaunchKernelGGL(batched12_stream_kernel, dim3((unsigned)wgs), dim3(64 * B12_WAVES), B12_WAVES * 2 * B12_WIN, stream, p);
+    hipLaunchKernelGGL(batched12_stream_kernel, dim3((unsigned)wgs), dim3(64 * B12_WAVES), B12_WAVES * 3 * B12_WIN, stream, p);
     return hipGetLastError();
   }
   // LDS-staged kernel: 32 items per workgroup for unaligned 12 x 12 operands (39 KB of LDS), 16 for other n

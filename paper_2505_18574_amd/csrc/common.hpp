@@ -62,7 +62,8 @@ struct TinyMpcParams {
 // by the caller through the planned entry points (make_plan_*), which is what a tuner drives.
 struct GemmPlan {
   int tile;          // block tile code: 64, 128, 256 = square tile of that edge; 192 = 256 rows x 128 columns;
-                     // 320 / 160 = weight-stationary kernel with 256- / 128-row tiles, 64 columns wide
+                     // 320 / 160 = weight-stationary kernel with 256- / 128-row tiles, 64 columns wide;
+                     // 321 / 161 = convolution patch kernel with units of 256 / 128 output pixels
   int ktb;           // K bytes per tile of the kernel that serves this block tile
   int splits;        // K slices (1 = no split)
   int kt_per_split;  // K tiles per slice (0 when splits == 1)
@@ -86,6 +87,8 @@ hipError_t launch_gemm_i8_trans(const GemmParams& p, bool trans_a, bool trans_b,
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
 // True when the weight-stationary kernel behind `tile` (320 / 160) can run p: bias absent or a row, K resident.
 bool wstat_eligible(const GemmParams& p, int tile);
+// True when the convolution patch kernel behind `tile` (321 / 161) can run the convolution described by p.
+bool conv_halo_eligible(const GemmParams& p, int tile);
 hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
 hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream);
 bool gemm_i8_fast_path(const GemmParams& p);

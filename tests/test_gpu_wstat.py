@@ -143,3 +143,57 @@ def test_conv_plan_errors():
     ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, 1, 1, 8, 1, plan=(64, 1))
     torch.cuda.synchronize()
     np.testing.assert_array_equal(host(out), oracle.conv2d_i8(x, w, bias, 1, 1, 8, 1))
+
+
+# ---- the convolution patch kernel (tile codes 321 / 161): weights and the image patch of a unit both in LDS ----
+
+PATCH_TILES = (321, 161)
+
+
+@pytest.mark.parametrize("tile", PATCH_TILES)
+@pytest.mark.parametrize("Nb,H,W,Cin,Cout,KH,KW,stride,pad", [
+    (1, 5, 5, 32, 16, 3, 3, 1, 1),
+    (2, 9, 7, 32, 32, 3, 3, 2, 1),       # stride 2, odd image: two column planes of unequal width
+    (3, 12, 12, 32, 48, 3, 3, 1, 0),     # no padding
+    (2, 14, 14, 64, 64, 1, 1, 1, 0),     # 1x1
+    (1, 6, 6, 32, 16, 5, 5, 1, 2),       # 5x5
+    (1, 3, 3, 32, 16, 5, 5, 1, 1),       # kernel larger than the image
+    (4, 30, 30, 96, 80, 3, 3, 1, 1),     # Cin not a power of two, a partial second column block
+    (2, 17, 23, 32, 272, 3, 3, 3, 2),    # stride 3, pad 2, five column blocks
+    (8, 56, 56, 64, 64, 3, 3, 1, 1),     # the stride-1 workload
+    (9, 61, 67, 32, 16, 3, 3, 1, 1),     # odd row length: units start and end mid-row
+    (70, 31, 29, 32, 16, 2, 3, 2, 0),    # stride 2, KH != KW
+    (3, 20, 300, 32, 32, 3, 3, 1, 1),    # rows longer than a unit
+    (40, 56, 56, 64, 64, 3, 3, 1, 1),    # 520 / 1000 units: every workgroup streams several
+])
+def test_patch_kernel_shapes(Nb, H, W, Cin, Cout, KH, KW, stride, pad, tile):
+    x, w, bias = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=H * W + Cin)
+    conv_check(x, w, bias, stride, pad, 8, 1, tile)
+    if Nb * H * W <= 4000:
+        conv_check(x, w, None, stride, pad, 5, 0, tile)
+
+
+def test_patch_kernel_small_magnitudes():
+    x, w, bias = inputs.conv_i8_inputs(2, 9, 9, 32, 32, 3, 3, seed=1, lo=-3, hi=3, bias_bits=4)
+    for shift in (0, 1, 2, 3):
+        conv_check(x, w, bias, 1, 1, shift, 0, 161)
+
+
+def test_patch_kernel_plan_errors():
+    # the stride-2 workload: its patch (a whole 28 x 28 x 128 image) and 72 KB of weights do not fit in LDS together
+    x, w, bias = inputs.conv_i8_inputs(2, 28, 28, 128, 256, 3, 3, seed=1)
+    out = torch.empty((2, 14, 14, 256), dtype=torch.int8, device="cuda")
+    for tile in PATCH_TILES:
+        with pytest.raises(ops.AcError) as e:
+            ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, 2, 1, 9, 1, plan=(tile, 1))
+        assert e.value.status == ops.AC_ERR_PLAN
+    x, w, bias = inputs.conv_i8_inputs(1, 8, 8, 16, 16, 3, 3, seed=1)  # Cin = 16: a K-step would straddle two taps
+    out = torch.empty((1, 8, 8, 16), dtype=torch.int8, device="cuda")
+    with pytest.raises(ops.AcError) as e:
+        ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, 1, 1, 8, 1, plan=(161, 1))
+    assert e.value.status == ops.AC_ERR_PLAN
+    A, B, b = inputs.gemm_i8_inputs(128, 64, 128, seed=1)  # not a GEMM kernel
+    C = torch.empty((128, 64), dtype=torch.int8, device="cuda")
+    with pytest.raises(ops.AcError) as e:
+        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(b), C, 8, 1, 321, 1)
+    assert e.value.status == ops.AC_ERR_PLAN

@@ -17,6 +17,7 @@
 // transposing ds_read_b64_tr of a B fragment (4 or 8 k-rows x 64 or 32 B) touch
 // every LDS bank once.
 #pragma once
+#include <type_traits>
 #include "gemm_mfma.hpp"
 
 namespace ac {
@@ -86,6 +87,33 @@ static __device__ __forceinline__ v4i dtl_read_col_i8(const unsigned char* Bs, i
   v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(AC_LDS(v2i, p));
   v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(AC_LDS(v2i, p + 8 * B_ROW));
   return (v4i){lo[0], lo[1], hi[0], hi[1]};
+}
+// Byte offset, inside a B tile, of the first of the two transposing reads of dtl_read_col (the second lies
+// HI rows further down), and the fragment read at a given address.
+template <class T, int B_ROW>
+static __device__ __forceinline__ int dtl_col_off(int kb, int seg, int lane) {
+  using S = BSwizzle<T::EB, B_ROW>;
+  const int i = lane & 15, g1 = (lane >> 4) & 1;
+  if constexpr (T::EB == 2) {
+    const int r = (kb >> 1) + (i >> 2);
+    return r * B_ROW + ((seg ^ S::seg_xor(r)) << 6) + g1 * 32 + 8 * (i & 3);
+  } else {
+    const int r = kb + (i >> 1);
+    return r * B_ROW + ((seg ^ S::seg_xor(r)) << 5) + g1 * 16 + 8 * (i & 1);
+  }
+}
+template <class T, int B_ROW>
+static __device__ __forceinline__ v4i dtl_read_col_at(const unsigned char* p) {
+  if constexpr (T::EB == 2) {
+    v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(AC_LDS(v4s, p));
+    v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(AC_LDS(v4s, p + 4 * B_ROW));
+    v2i l2 = __builtin_bit_cast(v2i, lo), h2 = __builtin_bit_cast(v2i, hi);
+    return (v4i){l2[0], l2[1], h2[0], h2[1]};
+  } else {
+    v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(AC_LDS(v2i, p));
+    v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(AC_LDS(v2i, p + 8 * B_ROW));
+    return (v4i){lo[0], lo[1], hi[0], hi[1]};
+  }
 }
 template <class T, int B_ROW>
 static __device__ __forceinline__ v4i dtl_read_col(const unsigned char* Bs, int kb, int seg, int lane) {
@@ -330,7 +358,53 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     block_sync();                  // tile 0 is visible
     if (grp == 1) block_sync();    // hold group 1 back by one phase
     int buf = 0;
-    for (int kt = 0; kt < nkt; kt++) {
+    int kt = 0;
+    if constexpr (AMODE == 0) {
+      // Steady state, STAGES tiles per trip, for as long as the tile being requested is a whole one: with the stage
+      // index a compile-time constant every LDS address of a phase is a fixed per-lane register plus an
+      // immediate, the loads take the uniform-base form, and no decision is left inside a phase.  (A wave has
+      // an issue slot only every few cycles, so in a phase of some 500 cycles every scalar branch and address
+      // add of the memory phase is time the partner wave's MFMA phase has to wait for.)
+      static_assert(BSwizzle<EB, G::B_ROW>::RPW == 1, "the B swizzle term must not depend on the K-step");
+      constexpr int KS_B = (32 / EB) * G::B_ROW;  // bytes between the B rows of consecutive K-steps
+      int a_fo[G::KSTEPS], b_fo[G::TN];
+#pragma unroll
+      for (int ks = 0; ks < G::KSTEPS; ks++) a_fo[ks] = a_lane_off + (((2 * ks + (lane >> 5)) ^ a_swz) << 4);
+#pragma unroll
+      for (int j = 0; j < G::TN; j++) b_fo[j] = G::A_BYTES + dtl_col_off<T, G::B_ROW>((lane >> 5) * 16, wn * G::TN + j, lane);
+      const int nkt_whole = p.splits > 1 ? 0 : kbytes / G::KTB;  // K slices keep the general loop
+      auto trip = [&](auto bufc) {
+        constexpr int BUF = decltype(bufc)::value, LBUF = (BUF + STAGES - 1) % STAGES;
+#pragma unroll
+        for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], lds0 + LBUF * G::STAGE + (wave * G::A_INSTR + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], lds0 + LBUF * G::STAGE + G::A_BYTES + (wave * G::B_INSTR + i) * 1024);
+        a_base += G::KTB;
+        b_base += b_step;
+#pragma unroll
+        for (int ks = 0; ks < G::KSTEPS; ks++) {
+#pragma unroll
+          for (int i = 0; i < G::TM; i++) fr[ks].a[i] = *(const v4i*)(smem + (a_fo[ks] + (BUF * G::STAGE + i * 32 * G::KTB)));
+#pragma unroll
+          for (int j = 0; j < G::TN; j++) fr[ks].b[j] = dtl_read_col_at<T, G::B_ROW>(smem + (b_fo[j] + (BUF * G::STAGE + ks * KS_B)));
+        }
+        wait_vm<(STAGES - 2) * PER_TILE>();
+        block_sync();
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int ks = 0; ks < G::KSTEPS; ks++) mfma_rows(fr[ks], 0, G::TM);
+        __builtin_amdgcn_s_setprio(0);
+        block_sync();
+      };
+      static_assert(STAGES == 4, "the steady-state trip is written for four stages");
+      for (; kt + 2 * STAGES - 2 < nkt_whole && kt + 2 * STAGES - 2 < nkt; kt += STAGES) {  // tiles kt + 3 .. kt + 6 are whole
+        trip(std::integral_constant<int, 0>{});
+        trip(std::integral_constant<int, 1>{});
+        trip(std::integral_constant<int, 2>{});
+        trip(std::integral_constant<int, 3>{});
+      }
+    }
+    for (; kt < nkt; kt++) {
       // memory phase
       const int lbuf = buf == 0 ? STAGES - 1 : buf - 1;  // stage of tile kt - 1 == stage of tile kt + STAGES - 1
       if (kt + STAGES - 1 < nkt) issue_loads(kt + STAGES - 1, lbuf);

@@ -333,6 +333,38 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   const int nkt = p.splits > 1 ? (nkt_total - kt0 < p.kt_per_split ? nkt_total - kt0 : p.kt_per_split) : nkt_total;
   constexpr int PER_TILE = G::A_INSTR + G::B_INSTR;  // outstanding vector-memory ops per tile per wave
   static_assert((STAGES - 1) * PER_TILE <= 63, "vmcnt is a 6-bit counter");
+
+  // Steady state (plain GEMM operands): both loops below run STAGES tiles per trip for as long as the tile being
+  // requested is a whole one.  With the stage index a compile-time constant every LDS address of a step is a
+  // fixed per-lane register plus an immediate, the loads take the uniform-base form, and no decision is left
+  // inside a step.  (A wave has an issue slot only every few cycles: every scalar branch and address add of
+  // a memory phase is time the MFMAs wait for.)
+  using SW = BSwizzle<EB, G::B_ROW>;
+  constexpr int ROWS_PER_CHUNK = 16 / EB;  // k-rows of B that 16 bytes of K span
+  static_assert(ROWS_PER_CHUNK % SW::RPW == 0 && ((ROWS_PER_CHUNK / SW::RPW) & SW::MASK) == 0, "the B swizzle term must not depend on the K-step");
+  constexpr int KS_B = (32 / EB) * G::B_ROW;  // bytes between the B rows of consecutive K-steps
+  int a_fo[G::KSTEPS], b_fo[G::TN];
+#pragma unroll
+  for (int ks = 0; ks < G::KSTEPS; ks++) a_fo[ks] = a_lane_off + (((2 * ks + (lane >> 5)) ^ a_swz) << 4);
+#pragma unroll
+  for (int j = 0; j < G::TN; j++) b_fo[j] = G::A_BYTES + dtl_col_off<T, G::B_ROW>((lane >> 5) * 16, wn * G::TN + j, lane);
+  const int nkt_whole = p.splits > 1 ? 0 : kbytes / G::KTB;  // K slices keep the general loops
+  auto issue_whole = [&](auto lbufc) {  // the next tile in order, a whole one, into stage LBUF
+    constexpr int LBUF = decltype(lbufc)::value;
+#pragma unroll
+    for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], lds0 + LBUF * G::STAGE + (wave * G::A_INSTR + i) * 1024);
+#pragma unroll
+    for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], lds0 + LBUF * G::STAGE + G::A_BYTES + (wave * G::B_INSTR + i) * 1024);
+    a_base += G::KTB;
+    b_base += b_step;
+  };
+  auto read_frags_at = [&](auto bufc, int ks, Frag& f) {  // read_frags with the stage as a constant
+    constexpr int BUF = decltype(bufc)::value;
+#pragma unroll
+    for (int i = 0; i < G::TM; i++) f.a[i] = *(const v4i*)(smem + (a_fo[ks] + (BUF * G::STAGE + i * 32 * G::KTB)));
+#pragma unroll
+    for (int j = 0; j < G::TN; j++) f.b[j] = dtl_read_col_at<T, G::B_ROW>(smem + (b_fo[j] + (BUF * G::STAGE + ks * KS_B)));
+  };
   if constexpr (PINGPONG) {
     // ---- ping-pong main loop ---------------------------------------------------------------------------
     // Eight waves, two per SIMD, in two groups of four (one wave of each group on every SIMD).  A wave
@@ -360,34 +392,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     int buf = 0;
     int kt = 0;
     if constexpr (AMODE == 0) {
-      // Steady state, STAGES tiles per trip, for as long as the tile being requested is a whole one: with the stage
-      // index a compile-time constant every LDS address of a phase is a fixed per-lane register plus an
-      // immediate, the loads take the uniform-base form, and no decision is left inside a phase.  (A wave has
-      // an issue slot only every few cycles, so in a phase of some 500 cycles every scalar branch and address
-      // add of the memory phase is time the partner wave's MFMA phase has to wait for.)
-      static_assert(BSwizzle<EB, G::B_ROW>::RPW == 1, "the B swizzle term must not depend on the K-step");
-      constexpr int KS_B = (32 / EB) * G::B_ROW;  // bytes between the B rows of consecutive K-steps
-      int a_fo[G::KSTEPS], b_fo[G::TN];
-#pragma unroll
-      for (int ks = 0; ks < G::KSTEPS; ks++) a_fo[ks] = a_lane_off + (((2 * ks + (lane >> 5)) ^ a_swz) << 4);
-#pragma unroll
-      for (int j = 0; j < G::TN; j++) b_fo[j] = G::A_BYTES + dtl_col_off<T, G::B_ROW>((lane >> 5) * 16, wn * G::TN + j, lane);
-      const int nkt_whole = p.splits > 1 ? 0 : kbytes / G::KTB;  // K slices keep the general loop
       auto trip = [&](auto bufc) {
         constexpr int BUF = decltype(bufc)::value, LBUF = (BUF + STAGES - 1) % STAGES;
+        issue_whole(std::integral_constant<int, LBUF>{});
 #pragma unroll
-        for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], lds0 + LBUF * G::STAGE + (wave * G::A_INSTR + i) * 1024);
-#pragma unroll
-        for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], lds0 + LBUF * G::STAGE + G::A_BYTES + (wave * G::B_INSTR + i) * 1024);
-        a_base += G::KTB;
-        b_base += b_step;
-#pragma unroll
-        for (int ks = 0; ks < G::KSTEPS; ks++) {
-#pragma unroll
-          for (int i = 0; i < G::TM; i++) fr[ks].a[i] = *(const v4i*)(smem + (a_fo[ks] + (BUF * G::STAGE + i * 32 * G::KTB)));
-#pragma unroll
-          for (int j = 0; j < G::TN; j++) fr[ks].b[j] = dtl_read_col_at<T, G::B_ROW>(smem + (b_fo[j] + (BUF * G::STAGE + ks * KS_B)));
-        }
+        for (int ks = 0; ks < G::KSTEPS; ks++) read_frags_at(bufc, ks, fr[ks]);
         wait_vm<(STAGES - 2) * PER_TILE>();
         block_sync();
         __builtin_amdgcn_s_setprio(1);
@@ -441,7 +450,28 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     for (int ks = 0; ks < G::KSTEPS; ks++) read_frags(0, ks, fr[ks]);
   }
   int buf = 0;
-  for (int kt = 0; kt + 1 < nkt; kt++) {  // every tile but the last
+  int kt = 0;
+  if constexpr (AMODE == 0) {
+    auto roll = [&](auto bufc) {
+      constexpr int BUF = decltype(bufc)::value;
+      wait_vm<(STAGES - 2) * PER_TILE>();
+      block_sync();
+      issue_whole(bufc);  // tile kt + STAGES takes the stage that tile kt has just left
+#pragma unroll
+      for (int ks = 0; ks < G::KSTEPS; ks++) {
+        mfma_rows(fr[ks], 0, G::TM);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags_at(std::integral_constant<int, (BUF + 1) % STAGES>{}, ks, fr[ks]);
+      }
+    };
+    auto roll_all = [&](auto... bufcs) { (roll(bufcs), ...); };
+    const int lim = nkt < nkt_whole ? nkt : nkt_whole;
+    for (; kt + 2 * STAGES - 1 < lim; kt += STAGES) {  // tiles kt + STAGES .. kt + 2 STAGES - 1 are whole
+      if constexpr (STAGES == 4) roll_all(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, std::integral_constant<int, 3>{});
+      else if constexpr (STAGES == 3) roll_all(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{});
+    }
+  }
+  for (; kt + 1 < nkt; kt++) {  // every tile but the last
     const int nbuf = buf + 1 == STAGES ? 0 : buf + 1;
     // tile kt + 1 must have landed: only the (STAGES - 2) younger tiles may still be in flight
     if (kt + STAGES - 1 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();

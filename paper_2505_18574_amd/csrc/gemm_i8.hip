@@ -78,13 +78,12 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   if (plan.tile == 64) {
     const int64_t t = tiles(64);
     const int nkt = (K + plan.ktb - 1) / plan.ktb;
-    // The second (reduce) launch costs about 3 us: worth it only for a deep K on at most 32 tiles, and then with
-    // just enough slices to put a workgroup on every second CU (measured: 49 x 2048 x 4608 is fastest with 4
-    // slices, 196 x 1024 x 2304 unsplit).
-    if (have_workspace && t <= 32 && nkt >= 16) {
-      int want = (int)((128 + t - 1) / t);
-      int per = (nkt + want - 1) / want;               // K tiles per slice ...
-      if (per < 2) per = 2;                            // ... but at least two, so a slice amortises its fill
+    // The second (reduce) launch costs about 3 us and a K tile of this kernel about 0.11 us: a split pays only
+    // from some 64 K tiles on, on at most 32 tiles, and the measured optimum is then 8 slices whatever the tile
+    // count (49 x 512 x 9216: 9.8 us with 8 slices, 12.0 unsplit; 64 x 64 x 16384: 11.4 against 18.1;
+    // 49 x 2048 x 4608, 36 K tiles: 8.0 unsplit against 9.3 with the best split).
+    if (have_workspace && t <= 32 && nkt >= 64) {
+      int per = (nkt + 7) / 8;  // K tiles per slice
       plan.kt_per_split = per;
       plan.splits = (nkt + per - 1) / per;
       if (plan.splits <= 1) {

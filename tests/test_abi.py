@@ -109,10 +109,13 @@ def test_auto_plans_are_host_arithmetic():
     assert ops.ac_gemm_i8_auto_plan(3136, 64, 576) == (64, 1)
     assert ops.ac_gemm_i8_auto_plan(65536, 64, 576) == (320, 1)   # long, narrow, short K: weight-stationary kernel
     assert ops.ac_gemm_i8_auto_plan(65536, 64, 4096) == (64, 1)   # K too deep to stay resident
-    tile, splits = ops.ac_gemm_i8_auto_plan(49, 2048, 4608, True)
-    assert tile == 64 and splits > 1
-    assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, False) == (64, 1)
-    assert ops.ac_gemm_i8_workspace_bytes(49, 2048, 4608) == ops.ac_gemm_i8_planned_workspace_bytes(49, 2048, 4608, tile, splits)
+    # a K split needs few tiles and at least 64 K tiles of 128 bytes: it then takes 8 slices
+    assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, True) == (64, 1)
+    tile, splits = ops.ac_gemm_i8_auto_plan(49, 512, 9216, True)
+    assert tile == 64 and splits == 8
+    assert ops.ac_gemm_i8_auto_plan(49, 512, 9216, False) == (64, 1)
+    assert ops.ac_gemm_i8_workspace_bytes(49, 512, 9216) == ops.ac_gemm_i8_planned_workspace_bytes(49, 512, 9216, tile, splits)
+    assert ops.ac_gemm_i8_workspace_bytes(49, 2048, 4608) == 0
     tile, splits = ops.ac_gemm_bf16_auto_plan(256, 256, 524288)
     assert tile == 64 and splits > 1
 

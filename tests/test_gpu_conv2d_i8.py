@@ -47,8 +47,9 @@ def test_workload_configs(case):
     (1, 3, 3, 16, 16, 5, 5, 1, 1),      # kernel larger than the image, fits only through padding
     (4, 30, 30, 48, 80, 3, 3, 1, 1),    # many tiles, ragged in M and N
     (2, 17, 23, 16, 272, 3, 3, 3, 2),   # stride 3, pad 2
-    (1, 14, 14, 256, 64, 3, 3, 1, 1),   # few tiles, deep K: split-K when a workspace is given
+    (1, 14, 14, 256, 64, 3, 3, 1, 1),   # few tiles, deep K
     (2, 7, 7, 512, 128, 3, 3, 1, 1),
+    (1, 7, 7, 1024, 64, 3, 3, 1, 1),    # one tile, 72 K tiles: split-K when a workspace is given
 ])
 def test_shapes(Nb, H, W, Cin, Cout, KH, KW, stride, pad):
     x, w, bias = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=H * W + Cin)

@@ -348,7 +348,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   for (int ks = 0; ks < G::KSTEPS; ks++) a_fo[ks] = a_lane_off + (((2 * ks + (lane >> 5)) ^ a_swz) << 4);
 #pragma unroll
   for (int j = 0; j < G::TN; j++) b_fo[j] = G::A_BYTES + dtl_col_off<T, G::B_ROW>((lane >> 5) * 16, wn * G::TN + j, lane);
-  const int nkt_whole = p.splits > 1 ? 0 : kbytes / G::KTB;  // K slices keep the general loops
+  // K slices keep the general loops; the convolution gather handles a partial last tile itself
+  const int nkt_whole = p.splits > 1 ? 0 : (AMODE == 0 ? kbytes / G::KTB : nkt_total);
   auto issue_whole = [&](auto lbufc) {  // the next tile in order, a whole one, into stage LBUF
     constexpr int LBUF = decltype(lbufc)::value;
 #pragma unroll
@@ -391,10 +392,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     if (grp == 1) block_sync();    // hold group 1 back by one phase
     int buf = 0;
     int kt = 0;
-    if constexpr (AMODE == 0) {
+    {
       auto trip = [&](auto bufc) {
         constexpr int BUF = decltype(bufc)::value, LBUF = (BUF + STAGES - 1) % STAGES;
-        issue_whole(std::integral_constant<int, LBUF>{});
+        if constexpr (AMODE == 0) issue_whole(std::integral_constant<int, LBUF>{});
+        else issue_loads(kt + BUF + STAGES - 1, LBUF);  // the gather keeps its per-lane addressing; kt is a multiple of STAGES here
 #pragma unroll
         for (int ks = 0; ks < G::KSTEPS; ks++) read_frags_at(bufc, ks, fr[ks]);
         wait_vm<(STAGES - 2) * PER_TILE>();
@@ -451,12 +453,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   }
   int buf = 0;
   int kt = 0;
-  if constexpr (AMODE == 0) {
+  {
     auto roll = [&](auto bufc) {
       constexpr int BUF = decltype(bufc)::value;
       wait_vm<(STAGES - 2) * PER_TILE>();
       block_sync();
-      issue_whole(bufc);  // tile kt + STAGES takes the stage that tile kt has just left
+      if constexpr (AMODE == 0) issue_whole(bufc);  // tile kt + STAGES takes the stage that tile kt has just left
+      else issue_loads(kt + BUF + STAGES, BUF);
 #pragma unroll
       for (int ks = 0; ks < G::KSTEPS; ks++) {
         mfma_rows(fr[ks], 0, G::TM);

@@ -82,81 +82,93 @@ __global__ void __launch_bounds__(256) tinympc_forward_12_4_5_kernel(const TinyM
   for (int i = threadIdx.x; i < NU * NX; i += 256) sK[i] = p.Kinf[i];
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t b0 = (int64_t)blockIdx.x * 256 + wave * 64;  // first problem of this wave
-  if (b0 >= p.batch) return;
-  const int nvalid = p.batch - b0 < 64 ? (int)(p.batch - b0) : 64;
-  const int64_t b = b0 + (lane < nvalid ? lane : 0);  // idle lanes recompute problem b0 and store nothing
-
-  float xs[H + 1][NX], us[H][NU], dv[UROW];
-  {
+  float* win = tinympc_lds + wave * 64 * XPITCH;
+  // Persistent waves: wave-block k is problems 64 k .. 64 k + 63; a wave takes blocks first, first + stride, ...
+  // and requests the inputs of its next block before it computes and stores the current one, so that the reads of
+  // one block travel while the writes of the previous one drain (the wait for those inputs counts the stores
+  // issued after them instead of draining them: vector-memory operations complete in issue order).
+  const int64_t nblk = (p.batch + 63) / 64, stride = (int64_t)gridDim.x * 4;
+  int64_t blk = (int64_t)blockIdx.x * 4 + wave;
+  if (blk >= nblk) return;
+  v4f xin[NX / 4], din[UROW / 4];
+  auto request = [&](int64_t k) {  // idle lanes of a partial block re-read its first problem and store nothing
+    const int64_t first = k * 64, left = p.batch - first;
+    const int64_t b = first + (lane < left ? lane : 0);
     const v4f* x4 = (const v4f*)(p.x0 + b * NX);
     const v4f* d4 = (const v4f*)(p.d + b * UROW);
 #pragma unroll
-    for (int q = 0; q < NX / 4; q++) {
-      const v4f v = x4[q];
+    for (int q = 0; q < NX / 4; q++) xin[q] = x4[q];
 #pragma unroll
-      for (int e = 0; e < 4; e++) xs[0][4 * q + e] = v[e];
-    }
+    for (int q = 0; q < UROW / 4; q++) din[q] = d4[q];
+  };
+  request(blk);
+  for (; blk < nblk; blk += stride) {
+    const int64_t b0 = blk * 64;
+    const int nvalid = p.batch - b0 < 64 ? (int)(p.batch - b0) : 64;
+    float xs[H + 1][NX], us[H][NU], dv[UROW];
 #pragma unroll
-    for (int q = 0; q < UROW / 4; q++) {
-      const v4f v = d4[q];
+    for (int q = 0; q < NX / 4; q++)
 #pragma unroll
-      for (int e = 0; e < 4; e++) dv[4 * q + e] = v[e];
-    }
-  }
+      for (int e = 0; e < 4; e++) xs[0][4 * q + e] = xin[q][e];
 #pragma unroll
-  for (int i = 0; i < H; i++) {
+    for (int q = 0; q < UROW / 4; q++)
 #pragma unroll
-    for (int r = 0; r < NU; r++) {
-      float s = 0.f;
+      for (int e = 0; e < 4; e++) dv[4 * q + e] = din[q][e];
+    if (blk + stride < nblk) request(blk + stride);
 #pragma unroll
-      for (int c = 0; c < NX; c++) s = __builtin_fmaf(sK[r * NX + c], xs[i][c], s);
-      us[i][r] = -s - dv[i * NU + r];
-    }
-    if (i + 1 < H || WITH_X) {
+    for (int i = 0; i < H; i++) {
 #pragma unroll
-      for (int r = 0; r < NX; r++) {
+      for (int r = 0; r < NU; r++) {
         float s = 0.f;
 #pragma unroll
-        for (int c = 0; c < NX; c++) s = __builtin_fmaf(sA[r * NX + c], xs[i][c], s);
-        float t = 0.f;
+        for (int c = 0; c < NX; c++) s = __builtin_fmaf(sK[r * NX + c], xs[i][c], s);
+        us[i][r] = -s - dv[i * NU + r];
+      }
+      if (i + 1 < H || WITH_X) {
 #pragma unroll
-        for (int c = 0; c < NU; c++) t = __builtin_fmaf(sB[r * NU + c], us[i][c], t);
-        xs[i + 1][r] = s + t;
+        for (int r = 0; r < NX; r++) {
+          float s = 0.f;
+#pragma unroll
+          for (int c = 0; c < NX; c++) s = __builtin_fmaf(sA[r * NX + c], xs[i][c], s);
+          float t = 0.f;
+#pragma unroll
+          for (int c = 0; c < NU; c++) t = __builtin_fmaf(sB[r * NU + c], us[i][c], t);
+          xs[i + 1][r] = s + t;
+        }
       }
     }
-  }
 
-  float* win = tinympc_lds + wave * 64 * XPITCH;
-  // controls: rows of 20 floats, then the block of nvalid * 20 floats in 16-byte pieces
+    // controls: rows of 20 floats, then the block of nvalid * 20 floats in 16-byte pieces
 #pragma unroll
-  for (int i = 0; i < H; i++)
+    for (int i = 0; i < H; i++)
 #pragma unroll
-    for (int r = 0; r < NU; r++) win[lane * UROW + i * NU + r] = us[i][r];
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  {
-    v4f* dst = (v4f*)(p.u + b0 * UROW);
-    const int pieces = nvalid * (UROW / 4);
-#pragma unroll
-    for (int k = 0; k < UROW / 4; k++) {
-      const int q = k * 64 + lane;
-      if (q < pieces) dst[q] = *(const v4f*)(win + 4 * q);
-    }
-  }
-  if constexpr (WITH_X) {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the read-back above is done before the window is reused
-#pragma unroll
-    for (int i = 0; i <= H; i++)
-#pragma unroll
-      for (int r = 0; r < NX; r++) win[lane * XPITCH + i * NX + r] = xs[i][r];
+      for (int r = 0; r < NU; r++) win[lane * UROW + i * NU + r] = us[i][r];
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    v4f* dst = (v4f*)(p.x_out + b0 * XROW);
-    const int pieces = nvalid * (XROW / 4);
+    {
+      v4f* dst = (v4f*)(p.u + b0 * UROW);
+      const int pieces = nvalid * (UROW / 4);
 #pragma unroll
-    for (int k = 0; k < XROW / 4; k++) {
-      const int q = k * 64 + lane;  // 16-byte piece q of the block: problem q / 18, piece q % 18 of its row
-      if (q < pieces) dst[q] = *(const v4f*)(win + (q / (XROW / 4)) * XPITCH + (q % (XROW / 4)) * 4);
+      for (int k = 0; k < UROW / 4; k++) {
+        const int q = k * 64 + lane;
+        if (q < pieces) dst[q] = *(const v4f*)(win + 4 * q);
+      }
     }
+    if constexpr (WITH_X) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the read-back above is done before the window is reused
+#pragma unroll
+      for (int i = 0; i <= H; i++)
+#pragma unroll
+        for (int r = 0; r < NX; r++) win[lane * XPITCH + i * NX + r] = xs[i][r];
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      v4f* dst = (v4f*)(p.x_out + b0 * XROW);
+      const int pieces = nvalid * (XROW / 4);
+#pragma unroll
+      for (int k = 0; k < XROW / 4; k++) {
+        const int q = k * 64 + lane;  // 16-byte piece q of the block: problem q / 18, piece q % 18 of its row
+        if (q < pieces) dst[q] = *(const v4f*)(win + (q / (XROW / 4)) * XPITCH + (q % (XROW / 4)) * 4);
+      }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the window is free for the next block
   }
 }
 
@@ -221,12 +233,16 @@ __global__ void __launch_bounds__(256) tinympc_forward_generic_kernel(const Tiny
   }
 }
 
+// Persistent workgroups per compute unit of the (12, 4, 5) kernel: one (31.5 us for 262144 problems; two: 34.1 us).
+#ifndef TINYMPC_WGS_PER_CU
+#define TINYMPC_WGS_PER_CU 1
+#endif
 hipError_t launch_tinympc_forward(const TinyMpcParams& p, hipStream_t stream) {
   const int64_t blocks = (p.batch + 255) / 256;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   const bool aligned16 = ((((uintptr_t)p.x0) | ((uintptr_t)p.d) | ((uintptr_t)p.u) | ((uintptr_t)p.x_out)) & 15) == 0;
   if (p.nx == 12 && p.nu == 4 && p.horizon == 5 && aligned16) {
-    constexpr int LDS = (4 * 64 * 76 + 12 * 12 + 12 * 4 + 4 * 12) * (int)sizeof(float);  // 78784 bytes: two workgroups per CU
+    constexpr int LDS = (4 * 64 * 76 + 12 * 12 + 12 * 4 + 4 * 12) * (int)sizeof(float);  // 78784 bytes
     static bool configured = false;
     if (!configured) {
       if (hipFuncSetAttribute((const void*)tinympc_forward_12_4_5_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess ||
@@ -234,8 +250,14 @@ hipError_t launch_tinympc_forward(const TinyMpcParams& p, hipStream_t stream) {
         return hipGetLastError();
       configured = true;
     }
-    if (p.x_out) hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<true>, dim3((unsigned)blocks), dim3(256), LDS, stream, p);
-    else hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<false>, dim3((unsigned)blocks), dim3(256), LDS, stream, p);
+    static int cus = 0;
+    if (cus == 0) {
+      int dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    }
+    const int64_t wgs = blocks < (int64_t)cus * TINYMPC_WGS_PER_CU ? blocks : (int64_t)cus * TINYMPC_WGS_PER_CU;  // persistent waves
+    if (p.x_out) hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<true>, dim3((unsigned)wgs), dim3(256), LDS, stream, p);
+    else hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<false>, dim3((unsigned)wgs), dim3(256), LDS, stream, p);
   } else if (p.nx == 12 && p.nu == 4) hipLaunchKernelGGL((tinympc_forward_kernel<12, 4>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else hipLaunchKernelGGL(tinympc_forward_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();

@@ -197,3 +197,30 @@ def test_patch_kernel_plan_errors():
     with pytest.raises(ops.AcError) as e:
         ops.ac_gemm_i8_planned(dev(A), dev(B), dev(b), C, 8, 1, 321, 1)
     assert e.value.status == ops.AC_ERR_PLAN
+
+
+# ---- the library's own choice: shapes that ac_gemm_i8 / ac_conv2d_i8 hand to these kernels by themselves ----
+
+@pytest.mark.parametrize("M,N,K", [(60000, 32, 16), (50000, 128, 1536), (49153, 80, 272)])
+def test_gemm_auto_choice(M, N, K):
+    assert ops.ac_gemm_i8_auto_plan(M, N, K, True) == (320, 1)
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + N + K)
+    C = torch.full((M, N), 77, dtype=torch.int8, device="cuda")
+    ops.ac_gemm_i8(dev(A), dev(B), dev(bias), C, 9, ops.AC_ACT_RELU)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C), oracle.gemm_i8(A, B, bias, 9, 1))
+    # a bias matrix is not something the weight-stationary kernel takes: the same call falls back to the tiled kernels
+    if M <= 50000:
+        _, _, full = inputs.gemm_i8_inputs(M, N, K, seed=M + N + K + 1, bias_matrix=True)
+        ops.ac_gemm_i8(dev(A), dev(B), dev(full), C, 9, ops.AC_ACT_NONE)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(C), oracle.gemm_i8(A, B, full, 9, 0))
+
+
+def test_conv_auto_choice():
+    # 24 images of 56 x 56 x 64 -> 64: 312 units of 256 output pixels, which the library runs on the patch kernel
+    x, w, bias = inputs.conv_i8_inputs(24, 56, 56, 64, 64, 3, 3, seed=77)
+    out = torch.full((24, 56, 56, 64), 99, dtype=torch.int8, device="cuda")
+    ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, 1, 1, 9, ops.AC_ACT_RELU)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(out), oracle.conv2d_i8(x, w, bias, 1, 1, 9, 1))

@@ -91,6 +91,34 @@ def test_planned_entry_validation_without_gpu():
     assert "tile" in ops.status_string(ops.AC_ERR_PLAN)
 
 
+def test_resident_operand_kernels_validation_without_gpu():
+    """Tile codes of the weight-stationary (320 / 160) and convolution patch (321 / 161) kernels: what they cannot
+    take is refused on the host with AC_ERR_PLAN, before any launch."""
+    L = ops.lib()
+    p = 0x1000  # never dereferenced; 16-byte aligned
+    i8 = lambda tile, splits, M=512, N=64, K=512, bias=None, bias_ld=0: L.ac_gemm_i8_planned(
+        p, K, p + (1 << 20), N, bias, bias_ld, p + (2 << 20), N, M, N, K, 8, 1, None, 0, tile, splits, None)
+    assert i8(320, 2) == ops.AC_ERR_PLAN                            # all of K is resident: no K split
+    assert i8(320, 1, K=1552) == ops.AC_ERR_PLAN                    # 13 K tiles do not fit beside the 256-row ring
+    assert i8(160, 1, K=2064) == ops.AC_ERR_PLAN                    # ... nor 17 beside the 128-row ring
+    assert i8(160, 1, bias=p + (3 << 20), bias_ld=64) == ops.AC_ERR_PLAN  # a bias matrix
+    assert i8(160, 1, N=60) == ops.AC_ERR_PLAN                      # N not a multiple of 16
+    assert i8(321, 1) == ops.AC_ERR_PLAN and i8(161, 1) == ops.AC_ERR_PLAN  # the patch kernel is a convolution kernel
+    assert L.ac_gemm_bf16_planned(p, 512, p + (1 << 20), 64, p + (2 << 20), 64, 512, 64, 512, 1.0, 0.0, None, 0, 320, 1, None) == ops.AC_ERR_PLAN
+    conv = lambda tile, splits, Nb=1, H=8, W=8, Cin=32, Cout=16, KH=3, KW=3, stride=1, pad=1, out=p + (2 << 20): L.ac_conv2d_i8_planned(
+        p, p + (1 << 20), None, out, Nb, H, W, Cin, Cout, KH, KW, stride, pad, 8, 1, None, 0, tile, splits, None)
+    assert conv(77, 1) == ops.AC_ERR_PLAN                           # unknown tile
+    assert conv(321, 2) == ops.AC_ERR_PLAN                          # no K split
+    assert conv(321, 1, Cin=16) == ops.AC_ERR_PLAN                  # a K-step would straddle two taps
+    assert conv(161, 1, Cin=48) == ops.AC_ERR_PLAN                  # Cin not a multiple of 32
+    assert conv(321, 1, Cin=3, Cout=8) == ops.AC_ERR_PLAN           # not even the direct-to-LDS path
+    assert conv(321, 1, out=p + (2 << 20) + 4) == ops.AC_ERR_PLAN   # 16-byte output stores
+    assert conv(321, 1, Nb=8, H=28, W=28, Cin=128, Cout=256, stride=2) == ops.AC_ERR_PLAN  # patch + weights exceed LDS
+    assert conv(161, 1, Nb=8, H=28, W=28, Cin=128, Cout=256, stride=2) == ops.AC_ERR_PLAN
+    assert conv(321, 1, H=300, W=300, Cin=256, Cout=64) == ops.AC_ERR_PLAN  # K = 2304: more than 64 K-steps
+    assert conv(320, 1, Cin=256, Cout=64, KH=3, KW=3) == ops.AC_ERR_PLAN    # K = 2304 is not resident for 320 ...
+
+
 def test_transposed_entry_validation_without_gpu():
     L = ops.lib()
     p = 0x1000  # never dereferenced

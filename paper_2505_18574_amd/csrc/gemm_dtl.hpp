@@ -18,6 +18,7 @@
 // every LDS bank once.
 #pragma once
 #include <type_traits>
+#include <utility>
 #include "gemm_mfma.hpp"
 
 namespace ac {
@@ -119,6 +120,12 @@ template <class T, int B_ROW>
 static __device__ __forceinline__ v4i dtl_read_col(const unsigned char* Bs, int kb, int seg, int lane) {
   if constexpr (T::EB == 2) return dtl_read_col_bf16<B_ROW>(Bs, kb, seg, lane);
   else return dtl_read_col_i8<B_ROW>(Bs, kb, seg, lane);
+}
+
+// f(integral_constant<0>), f(integral_constant<1>), ...: one call per LDS stage with the stage index a constant.
+template <class F, int... I>
+static __device__ __forceinline__ void for_each_stage(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
 }
 
 template <class T, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int KTB_>
@@ -467,11 +474,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
         read_frags_at(std::integral_constant<int, (BUF + 1) % STAGES>{}, ks, fr[ks]);
       }
     };
-    auto roll_all = [&](auto... bufcs) { (roll(bufcs), ...); };
+
     const int lim = nkt < nkt_whole ? nkt : nkt_whole;
     for (; kt + 2 * STAGES - 1 < lim; kt += STAGES) {  // tiles kt + STAGES .. kt + 2 STAGES - 1 are whole
-      if constexpr (STAGES == 4) roll_all(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{}, std::integral_constant<int, 3>{});
-      else if constexpr (STAGES == 3) roll_all(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{});
+      for_each_stage(roll, std::make_integer_sequence<int, STAGES>{});
     }
   }
   for (; kt + 1 < nkt; kt++) {  // every tile but the last
@@ -536,7 +542,8 @@ static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
 
 // The four direct-to-LDS configurations by tile code.  256: eight waves in ping-pong over four 32 KB stages
 // (64 bytes of K per tile); 192 (256 x 128), 128 and 64: the rolling-refill loop with 128 bytes of K per tile,
-// eight waves of 64 x 64 / 64 x 32 or four waves of 32 x 32.
+// eight waves of 64 x 64 / 64 x 32 or four waves of 32 x 32 (four stages: six and eight were measured slower on
+// every few-tile deep-K shape, 7.9 / 8.3 / 9.3 us on 49 x 2048 x 4608: those loops wait on the barrier, not on loads).
 template <class T, class EPI, int AMODE>
 static hipError_t launch_dtl_tile(int tile, const GemmParams& p, hipStream_t stream) {
   switch (tile) {

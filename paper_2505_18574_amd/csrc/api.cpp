@@ -218,12 +218,15 @@ static ac_status conv2d_i8_entry(const int8_t* in, const int8_t* w, const int32_
   p.lda = 0; p.ldb = Cout; p.ldc = Cout; p.bias_ld = 0;
   p.M = (int32_t)M; p.N = Cout; p.K = (int32_t)K; p.shift = shift; p.act = act;
   p.H = H; p.W = W; p.Cin = Cin; p.KW = KW; p.OH = (int32_t)OH; p.OW = (int32_t)OW; p.stride = stride; p.pad = pad;
+  p.KH = KH; p.a_bytes = (int32_t)in_elems;
+  p.dCin = ac::FastDiv::make((unsigned)(Cin > 0 ? Cin : 1)); p.dKW = ac::FastDiv::make((unsigned)KW);
+  p.dOW = ac::FastDiv::make((unsigned)(OW > 0 ? OW : 1)); p.dOH = ac::FastDiv::make((unsigned)(OH > 0 ? OH : 1));
   p.splits = 1;
   p.partial = (int32_t*)workspace;
   if (planned) {
-    // a K split or the weight-stationary kernel need the direct-to-LDS path: 16-byte aligned operands, channel
-    // counts in multiples of 16
-    const bool fast = (((uintptr_t)in | (uintptr_t)w) & 15) == 0 && Cin % 16 == 0 && Cout % 16 == 0 && ((uintptr_t)out & 3) == 0;
+    // a K split, the weight-stationary kernel and the patch kernel need the direct-to-LDS path: 16-byte aligned
+    // operands, channel counts in multiples of 16, at most 32 kernel taps
+    const bool fast = ac::conv_i8_fast_path(p);
     const bool ws = tile == 320 || tile == 160, patch = tile == 321 || tile == 161;
     if ((plan.splits > 1 || ws || patch) && !fast) return AC_ERR_PLAN;
     if (ws && !ac::wstat_eligible(p, tile)) return AC_ERR_PLAN;

@@ -16,6 +16,13 @@ typedef short v4s __attribute__((ext_vector_type(4)));
 typedef short v8s __attribute__((ext_vector_type(8)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
+// x / d by one multiply, exact while x * d < 2^32 (the host checks the ranges it is used on).
+struct FastDiv {
+  unsigned magic, d;
+  __host__ __device__ static FastDiv make(unsigned d) { return FastDiv{d > 1 ? (unsigned)(0x100000000ull / d) + 1u : 0u, d}; }
+  __device__ __forceinline__ unsigned div(unsigned x) const { return d == 1 ? x : __umulhi(x, magic); }
+};
+
 // One descriptor serves the int8 GEMM, the int8 implicit-GEMM convolution and
 // the bf16 GEMM: all three are C[M][N] = epilogue(A[M][K] . B[K][N]).
 struct GemmParams {
@@ -29,6 +36,9 @@ struct GemmParams {
   float alpha, beta;    // bf16 epilogue
   // convolution geometry (implicit GEMM: m -> (n, oh, ow), k -> (kh, kw, ci))
   int32_t H, W, Cin, KW, OH, OW, stride, pad;
+  int32_t KH;            // kernel rows (K == KH * KW * Cin)
+  int32_t a_bytes;       // convolution: bytes of the whole input (Nb * H * W * Cin), the range of the bounds-checked gather
+  FastDiv dCin, dKW, dOW, dOH;  // convolution index arithmetic of the direct-to-LDS gather
   // split-K: number of K slices; int8 slices leave int32 partial sums in a workspace, bf16 slices add into C
   int32_t splits;        // number of K slices (1 = no split)
   int32_t kt_per_split;  // K tiles (of the launched kernel's tile depth) per slice
@@ -92,6 +102,7 @@ bool conv_halo_eligible(const GemmParams& p, int tile);
 hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
 hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream);
 bool gemm_i8_fast_path(const GemmParams& p);
+bool conv_i8_fast_path(const GemmParams& p);
 bool gemm_bf16_fast_path(const GemmParams& p);
 
 }  // namespace ac

@@ -31,12 +31,6 @@
 
 namespace ac {
 
-struct FastDiv {  // x / d for x * d < 2^32
-  unsigned magic, d;
-  __host__ __device__ static FastDiv make(unsigned d) { return FastDiv{d > 1 ? (unsigned)(0x100000000ull / d) + 1u : 0u, d}; }
-  __device__ __forceinline__ unsigned div(unsigned x) const { return d == 1 ? x : __umulhi(x, magic); }
-};
-
 // A pointer the compiler must keep in scalar registers (it is the same in every lane by construction).
 static __device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* q) {
   const uint64_t v = (uint64_t)(uintptr_t)q;

@@ -38,6 +38,12 @@ static __device__ __forceinline__ void load_to_lds16(const void* gptr, unsigned 
 static __device__ __forceinline__ void load_to_lds16_so(const void* sbase, unsigned voff, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
 }
+// The same through a buffer descriptor with a 32-bit byte offset per lane: a lane whose offset lies beyond the
+// descriptor's size receives zeros (the hardware bounds check), which is how the convolution gather writes its
+// padding: no pointer select, no block of zeros.
+static __device__ __forceinline__ void buffer_to_lds16(v4i rsrc, unsigned voff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
+}
 // Workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() would also drain every
 // outstanding global store, which would serialise one tile's epilogue with the next tile's main loop.
 static __device__ __forceinline__ void block_sync() {
@@ -201,19 +207,40 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   // constant 32-bit byte offset per lane and instruction.  Rows beyond M and columns beyond N are clamped
   // to valid ones (their products land in accumulators that are never stored); only a partial last K tile
   // needs zeros and takes the slower per-lane pointer path.
+  // Convolution (AMODE 1): the row's output pixel gives the byte offset of its window origin in the image
+  // (g_base, possibly "negative": only ever used together with an in-range tap) and one bit per kernel tap that
+  // says whether the tap falls inside the image (g_mask, bit kh * KW + kw; the host keeps KH * KW <= 32).  A
+  // load then costs an add, a bit test and an OR: a lane whose tap is padding, whose row is beyond M or whose K
+  // position is beyond K gets the offset 0xffffffff and the bounds check of the buffer load writes its zeros.
   unsigned a_voff[G::A_INSTR], b_voff[G::B_INSTR];
   int b_krow[G::B_INSTR];
-  ARow<1> a_pix[G::A_INSTR];  // AMODE 1: output pixel of the row
+  int g_base[G::A_INSTR];
+  unsigned g_mask[G::A_INSTR];
 #pragma unroll
   for (int i = 0; i < G::A_INSTR; i++) {
     const int row = (wave * G::A_INSTR + i) * G::A_ROWS_PER_INSTR + lane / G::A_SPR;
     const int v = (wave * G::A_INSTR + i) & (NVAR - 1);
+    g_base[i] = 0, g_mask[i] = 0u, a_voff[i] = 0;
     if constexpr (AMODE == 0) {
       const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
       a_voff[i] = (unsigned)rclamp * (unsigned)(p.lda * EB) + a_chunk[v] * 16;
     } else {
-      a_pix[i].init(p, m0 + row, EB);
-      a_voff[i] = 0;
+      const int m = m0 + row;
+      const unsigned mm = m < p.M ? (unsigned)m : 0u;
+      const unsigned q = p.dOW.div(mm), img = p.dOH.div(q);
+      const int ow = (int)(mm - q * p.OW), oh = (int)(q - img * p.OH);
+      const int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
+      g_base[i] = (((int)img * p.H + ih0) * p.W + iw0) * p.Cin;
+      auto span = [](int first, int n, int extent) {  // bits k = 0 .. n-1 with 0 <= first + k < extent
+        const int lo = first < 0 ? -first : 0, hi = extent - first < n ? extent - first : n;
+        if (hi <= lo) return 0u;
+        return (hi >= 32 ? ~0u : (1u << hi) - 1u) & ~((1u << lo) - 1u);
+      };
+      const unsigned rows = span(ih0, p.KH, p.H), cols = span(iw0, p.KW, p.W);
+      unsigned mask = 0u;
+      for (int kh = 0; kh < p.KH; kh++)
+        if ((rows >> kh) & 1u) mask |= cols << (kh * p.KW);
+      g_mask[i] = m < p.M ? mask : 0u;
     }
   }
 #pragma unroll
@@ -227,21 +254,18 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   const unsigned char* a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda * EB : 0) + (int64_t)kt0 * G::KTB;
   const unsigned char* b_base = (const unsigned char*)p.B + (int64_t)n0 * EB + kt0 * b_step;
 
-  // convolution: (kh, kw, ci) of this lane's possible chunks, advanced by KTB bytes of K per tile
-  // c_off is the element offset (kh * W + kw) * Cin + ci of the chunk from the window's first pixel; it grows by
-  // KTB per tile and by (W - KW) * Cin more whenever kh steps
-  int c_kh[NVAR], c_kw[NVAR], c_ci[NVAR], c_off[NVAR];
+  // convolution: the lane's chunk sits at K byte g_kb, i.e. tap g_kb / Cin, channel g_kb % Cin; both come from
+  // two multiply-high divisions per K tile instead of a carried (kh, kw, ci) counter with its loops
+  unsigned g_kb[NVAR];  // K position (bytes) of the lane's chunk in the next K tile to be requested
 #pragma unroll
-  for (int v = 0; v < NVAR; v++) {
-    c_kh[v] = c_kw[v] = c_ci[v] = c_off[v] = 0;
-    if constexpr (AMODE == 1) {
-      int kb = kt0 * G::KTB + a_chunk[v] * 16;
-      int tap = kb / p.Cin;
-      c_ci[v] = kb - tap * p.Cin;
-      c_kh[v] = tap / p.KW;
-      c_kw[v] = tap - c_kh[v] * p.KW;
-      c_off[v] = (c_kh[v] * p.W + c_kw[v]) * p.Cin + c_ci[v];
-    }
+  for (int v = 0; v < NVAR; v++) g_kb[v] = (unsigned)(kt0 * G::KTB + a_chunk[v] * 16);
+  v4i a_rsrc = {0, 0, 0, 0};  // buffer descriptor of the input image: base, size in bytes, raw dword format
+  if constexpr (AMODE == 1) {
+    const uint64_t ab = (uint64_t)(uintptr_t)p.A;
+    a_rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)ab);
+    a_rsrc[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(ab >> 32));
+    a_rsrc[2] = __builtin_amdgcn_readfirstlane(p.a_bytes);
+    a_rsrc[3] = 0x00020000;
   }
 
   // Tiles are issued strictly in order 0, 1, 2, ...: the running bases and tap decode rely on it.
@@ -251,7 +275,24 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     const int kt = kt0 + kt_local;
     const int kbase = kt * G::KTB;
     const bool full = kbase + G::KTB <= kbytes;  // wave-uniform
-    if (AMODE == 0 && full) {
+    if constexpr (AMODE == 1) {
+      unsigned g_off[NVAR], g_tap[NVAR], g_dead[NVAR];
+#pragma unroll
+      for (int v = 0; v < NVAR; v++) {
+        const unsigned tap = p.dCin.div(g_kb[v]), ci = g_kb[v] - tap * p.Cin;
+        const unsigned kh = p.dKW.div(tap), kw = tap - kh * p.KW;
+        g_off[v] = (kh * p.W + kw) * p.Cin + ci;
+        g_tap[v] = tap;
+        g_dead[v] = g_kb[v] < (unsigned)kbytes ? 0u : ~0u;
+        g_kb[v] += G::KTB;
+      }
+#pragma unroll
+      for (int i = 0; i < G::A_INSTR; i++) {
+        const int v = (wave * G::A_INSTR + i) & (NVAR - 1);
+        const unsigned inside = (g_mask[i] >> (g_tap[v] & 31u)) & 1u;
+        buffer_to_lds16(a_rsrc, ((unsigned)g_base[i] + g_off[v]) | (inside - 1u) | g_dead[v], As + (wave * G::A_INSTR + i) * 1024);
+      }
+    } else if (full) {
 #pragma unroll
       for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], As + (wave * G::A_INSTR + i) * 1024);
     } else {
@@ -259,16 +300,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
       for (int i = 0; i < G::A_INSTR; i++) {
         const int v = (wave * G::A_INSTR + i) & (NVAR - 1);
         const int kb = kbase + a_chunk[v] * 16;
-        const unsigned char* src = zero;
-        if constexpr (AMODE == 0) {
-          if (kb < kbytes) src = a_base + a_voff[i];
-        } else {
-          const ARow<1>& r = a_pix[i];
-          const int ih = r.ih0 + c_kh[v], iw = r.iw0 + c_kw[v];
-          if (r.ok && kb < kbytes && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
-            src = (const unsigned char*)p.A + r.base + c_off[v];
-        }
-        load_to_lds16(src, As + (wave * G::A_INSTR + i) * 1024);
+        load_to_lds16(kb < kbytes ? a_base + a_voff[i] : zero, As + (wave * G::A_INSTR + i) * 1024);
       }
     }
     if (full) {  // every k-row of the tile exists; columns beyond N were clamped when b_voff was set up
@@ -283,21 +315,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     }
     a_base += G::KTB;
     b_base += b_step;
-    if constexpr (AMODE == 1) {  // advance the tap decode by one K tile
-#pragma unroll
-      for (int v = 0; v < NVAR; v++) {
-        c_ci[v] += G::KTB;
-        c_off[v] += G::KTB;
-        while (c_ci[v] >= p.Cin) {
-          c_ci[v] -= p.Cin;
-          if (++c_kw[v] == p.KW) {
-            c_kw[v] = 0;
-            ++c_kh[v];
-            c_off[v] += (p.W - p.KW) * p.Cin;
-          }
-        }
-      }
-    }
   };
 
   typename T::accv acc[G::TM][G::TN];

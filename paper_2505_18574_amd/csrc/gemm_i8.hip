@@ -211,25 +211,40 @@ hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream, const GemmPla
   return dispatch_i8<0>(p, stream, aligned, gemm_i8_fast_path(p), forced);
 }
 
-hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced) {
-  // Fast path: channel counts in multiples of 16 so that a 16-byte K chunk stays inside one kernel tap.
+// Direct-to-LDS path of the convolution: channel counts in multiples of 16 so that a 16-byte K chunk stays inside
+// one kernel tap, at most 32 taps (one validity bit each), and index ranges that the one-multiply divisions of the
+// gather cover (K * Cin, M * OW and (M / OW) * OH below 2^32).
+bool conv_i8_fast_path(const GemmParams& p) {
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.Cin % 16 == 0) && (p.ldb % 16 == 0) &&
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
-  if (!forced && aligned) {
+  const int64_t lim = 1ll << 32;
+  return aligned && p.KH >= 1 && p.KH * p.KW <= 32 && (int64_t)p.K * p.Cin < lim && (int64_t)p.M * p.OW < lim &&
+         ((int64_t)p.M / (p.OW > 0 ? p.OW : 1) + 1) * p.OH < lim && p.a_bytes > 0;
+}
+
+hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced) {
+  const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.Cin % 16 == 0) && (p.ldb % 16 == 0) &&
+                       (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
+  const bool fast = conv_i8_fast_path(p);
+  if (!forced && fast) {
     // The patch kernel (weights and the image patch of a unit both in LDS) once the convolution has at least a
     // unit of 256 output pixels per compute unit and column block: measured 20.8 against 28.4 us (next best
     // kernel) on 64 images of 56 x 56 x 64 -> 64, 47 against 82 us on 256; below that the fixed cost of filling
     // LDS once per workgroup makes the 64 x 64 tiles the faster choice.
     ConvHaloParams h;
     size_t lds = 0;
-    if (conv_halo_plan(p, 256, &h, &lds) && (int64_t)h.units * ((p.N + 63) / 64) >= 256) {
-      GemmParams q = p;
-      q.splits = 1;
-      q.kt_per_split = 0;
-      return launch_conv_halo<256>(q, h, lds, stream);
+    GemmParams q = p;
+    q.splits = 1;
+    q.kt_per_split = 0;
+    if (conv_halo_plan(p, 256, &h, &lds)) {
+      if ((int64_t)h.units * ((p.N + 63) / 64) >= 256) return launch_conv_halo<256>(q, h, lds, stream);
+    } else if (conv_halo_plan(p, 128, &h, &lds) && (int64_t)h.units * ((p.N + 63) / 64) >= 512) {
+      // the patch of 256 pixels does not fit, that of 128 does (64 images of 28 x 28 x 128 -> 128: 18.9 us against
+      // 22.9 us on the tiled kernels)
+      return launch_conv_halo<128>(q, h, lds, stream);
     }
   }
-  return dispatch_i8<1>(p, stream, aligned, aligned, forced);
+  return dispatch_i8<1>(p, stream, aligned, fast, forced);
 }
 
 }  // namespace ac

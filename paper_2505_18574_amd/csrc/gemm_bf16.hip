@@ -1,34 +1,54 @@
 // bf16 GEMM, fp32 accumulate and output: tile selection, split-K and launch.
+#include <algorithm>
+
 #include "gemm_dtl.hpp"
 
 namespace ac {
 
 // Block tile and K split for an M x N x K bf16 problem: the largest tile that still gives most compute units
 // work (thresholds from exhaustive plan tables: 256 x 256 from 192 tiles, 128 x 128 from 128 tiles).  When even
-// 64 x 64 tiles leave most of the chip idle and K is deep, K is cut into slices that add into C (see
-// EpilogueAtomicF32).  The slice count minimises a two-term estimate measured on this chip: a 64 x 64
-// workgroup alone on its compute unit advances one K tile in about 0.24 us, and the fp32 atomic adds of one
-// slice retire at about 43 elements per nanosecond, so every extra slice costs M * N / 43000 us.
+// 64 x 64 tiles leave most of the chip idle, K is cut into slices that add into C (see EpilogueAtomicF32), and
+// tile and slice count together minimise an estimate fitted to the plan tables of twenty such shapes on this chip
+// (worst miss 18 % over the table's best, against 67 % for a rule that only ever slices the 64 x 64 tile):
+//   memory term  = max(operand bytes as the tiles request them / min(8 TB/s, W * r),
+//                      operand bytes once                       / min(5 TB/s, W * r)),
+//                  W workgroups resident, each sustaining r bytes/us on its own (loads in flight over latency);
+//   serial term  = K tiles per slice * time of one K tile of that kernel with warm operands;
+//   slicing      = 2 us (the launch that scales C) + slices * M * N / 200 fp32 atomic adds per ns.
+// A bigger tile requests each operand fewer times but offers fewer, slower-starting streams; slicing restores
+// the stream count until the atomic traffic outweighs it.  Slices keep at least four K tiles and fit the chip in
+// one round.
 GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K) {
-  auto tiles = [&](int t) { return (int64_t)((M + t - 1) / t) * ((N + t - 1) / t); };
-  const int tile = choose_tile(M, N);
   GemmPlan plan;
-  make_plan_bf16(K, tile, 1, &plan);
-  if (tile == 64) {
-    const int64_t t = tiles(64);
-    const int64_t nkt = ((int64_t)K * 2 + plan.ktb - 1) / plan.ktb;
-    const double slice_us = (double)M * N / 43000.0;
-    double best = 0.24 * (double)nkt * (double)((t + 255) / 256);
-    int best_s = 1;
-    for (int s = 2; s * t <= 256 && s <= nkt; s *= 2) {  // at most one workgroup per compute unit
-      const double est = 0.24 * (double)((nkt + s - 1) / s) + 2.0 + slice_us * s;
-      if (est < best) {
-        best = est;
-        best_s = s;
-      }
+  make_plan_bf16(K, choose_tile(M, N), 1, &plan);
+  if (plan.tile != 64 || M < 1 || N < 1 || K < 1) return plan;
+  struct Candidate {
+    int tile, per_cu;
+    double stream, ktile_us;  // bytes/us one workgroup sustains alone; us per K tile with warm operands
+  };
+  static const Candidate cands[] = {{64, 2, 40e3, 0.192}, {128, 1, 45e3, 0.32}, {192, 1, 30e3, 0.44}, {256, 1, 25e3, 0.48}};
+  const double once = 2.0 * K * ((double)M + N);
+  double best = 0.0;
+  int best_tile = 0, best_s = 1;
+  for (const Candidate& c : cands) {
+    int bm, bn;
+    GemmPlan trial;
+    tile_dims(c.tile, &bm, &bn);
+    make_plan_bf16(K, c.tile, 1, &trial);
+    const int64_t tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn;
+    const int64_t nkt = ((int64_t)K * 2 + trial.ktb - 1) / trial.ktb, slots = 256 * c.per_cu;
+    const double requested = 2.0 * K * ((double)tm * bm * tn + (double)tn * bn * tm);
+    for (int s = 1; s <= 256; s *= 2) {
+      const int64_t items = tm * tn * s;
+      if (s > 1 && (items > slots || (int64_t)s * 4 > nkt)) break;
+      const double rate = (double)(items < slots ? items : slots) * c.stream;
+      const double mem = std::max(requested / std::min(8e6, rate), once / std::min(5e6, rate));
+      const double serial = (double)((items + slots - 1) / slots) * (double)((nkt + s - 1) / s) * c.ktile_us;
+      const double est = std::max(mem, serial) + (s > 1 ? 2.0 + (double)s * M * N / 2e5 : 0.0);
+      if (best_tile == 0 || est < best) best = est, best_tile = c.tile, best_s = s;
     }
-    if (best_s > 1) make_plan_bf16(K, tile, best_s, &plan);
   }
+  make_plan_bf16(K, best_tile, best_s, &plan);
   return plan;
 }
 
@@ -70,7 +90,7 @@ hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const Gemm
   GemmPlan plan = forced ? *forced : plan_gemm_bf16(p.M, p.N, p.K);
   if (plan.splits > 1 && !fast) {
     if (forced) return hipErrorInvalidValue;
-    make_plan_bf16(p.K, plan.tile, 1, &plan);
+    make_plan_bf16(p.K, choose_tile(p.M, p.N), 1, &plan);  // the generic kernels do not slice K
   }
   p.splits = plan.splits;
   p.kt_per_split = plan.kt_per_split;

@@ -144,8 +144,18 @@ def test_auto_plans_are_host_arithmetic():
     assert ops.ac_gemm_i8_auto_plan(49, 512, 9216, False) == (64, 1)
     assert ops.ac_gemm_i8_workspace_bytes(49, 512, 9216) == ops.ac_gemm_i8_planned_workspace_bytes(49, 512, 9216, tile, splits)
     assert ops.ac_gemm_i8_workspace_bytes(49, 2048, 4608) == 0
-    tile, splits = ops.ac_gemm_bf16_auto_plan(256, 256, 524288)
-    assert tile == 64 and splits > 1
+    # bf16 with few output tiles: tile and slice count come from one cost estimate; a very deep K takes a
+    # big tile (operands requested fewer times) and enough slices to fill the chip once
+    assert ops.ac_gemm_bf16_auto_plan(256, 256, 524288) == (192, 128)
+    assert ops.ac_gemm_bf16_auto_plan(256, 256, 8192) == (64, 8)
+    assert ops.ac_gemm_bf16_auto_plan(1024, 1024, 1024) == (64, 1)
+    for M, N, K in [(1, 1, 1), (64, 64, 100000), (100, 36, 7), (768, 768, 32768), (32, 8192, 8192)]:
+        tile, splits = ops.ac_gemm_bf16_auto_plan(M, N, K)
+        bm, bn, ktb = {64: (64, 64, 128), 128: (128, 128, 128), 192: (256, 128, 128), 256: (256, 256, 64)}[tile]
+        nkt = -(-2 * K // ktb)
+        assert 1 <= splits <= max(1, nkt // 4 + 1)
+        if splits > 1:  # one round of workgroups
+            assert -(-M // bm) * -(-N // bn) * splits <= (512 if tile == 64 else 256)
 
 
 def test_missing_library_fails_loudly(monkeypatch):

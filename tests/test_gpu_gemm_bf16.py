@@ -50,6 +50,22 @@ def test_shapes_full_oracle(M, N, K):
     check_full(A, B)
 
 
+@pytest.mark.parametrize("M,N,K,plan", [
+    (256, 256, 8192, (64, 8)), (128, 128, 262144, (128, 128)), (384, 384, 16384, None), (768, 768, 8192, None),
+    (256, 256, 65536, None), (200, 120, 40000, None), (1024, 256, 8192, None)])
+def test_few_tiles_deep_k_auto_plan(M, N, K, plan):
+    """Few output tiles and a deep K: the library picks tile and K slices from its cost estimate (slices add
+    into C with fp32 atomics, so the order of the K / slices partial sums varies from run to run)."""
+    auto = ops.ac_gemm_bf16_auto_plan(M, N, K)
+    if plan is not None:
+        assert auto == plan
+    assert auto[1] > 1
+    A, B = inputs.gemm_bf16_inputs(M, N, K, seed=M + N + K)
+    check_full(A, B)
+    C_in = np.random.default_rng(K).standard_normal((M, N)).astype(np.float32)
+    check_full(A, B, 0.5, -1.5, C_in)
+
+
 def test_alpha_beta():
     A, B = inputs.gemm_bf16_inputs(200, 264, 136, seed=1)
     Cin = np.random.default_rng(2).standard_normal((200, 264)).astype(np.float32)

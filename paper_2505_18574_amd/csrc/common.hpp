@@ -85,6 +85,22 @@ bool tile_dims(int32_t tile, int* bm, int* bn);
 // Tile code the library picks for an M x N output.
 int choose_tile(int32_t M, int32_t N);
 // Explicit plans: false when the tile code is unknown, or splits is outside 1 .. number of K tiles.
+// Tile and K slices for a problem whose 64 x 64 tiles would leave most of the chip idle: the pair that minimises
+//   max(memory term, serial term) + slicing cost, with
+//   memory term = max(operand bytes as the tiles request them / min(8 TB/s, W * r),
+//                     operand bytes once                       / min(5 TB/s, W * r)),
+//                 W workgroups resident, each sustaining r bytes/us on its own (loads in flight over latency);
+//   serial term = K tiles per slice * time of one K tile of that kernel with warm operands;
+//   slicing     = a fixed cost (the extra launch) + slices * M * N / the rate the partial sums are combined at.
+// A bigger tile requests each operand fewer times but offers fewer, slower-starting streams; slicing restores the
+// stream count until the traffic of the partial sums outweighs it.  Slices keep at least four K tiles and fit
+// the chip in one round.  The constants are fitted to plan tables measured on this chip, one set per data type.
+struct SliceModel {
+  double stream[4];    // r of the tile codes 64, 128, 192, 256 (bytes/us)
+  double ktile_us[4];  // time of one K tile of those kernels
+  double slice_fix_us, combine_per_us;
+};
+void plan_few_tiles(int32_t M, int32_t N, int64_t kbytes, bool may_slice, const SliceModel& model, int* tile, int* splits);
 bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan);
 bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan);
 

@@ -8,47 +8,17 @@ namespace ac {
 // Block tile and K split for an M x N x K bf16 problem: the largest tile that still gives most compute units
 // work (thresholds from exhaustive plan tables: 256 x 256 from 192 tiles, 128 x 128 from 128 tiles).  When even
 // 64 x 64 tiles leave most of the chip idle, K is cut into slices that add into C (see EpilogueAtomicF32), and
-// tile and slice count together minimise an estimate fitted to the plan tables of twenty such shapes on this chip
-// (worst miss 18 % over the table's best, against 67 % for a rule that only ever slices the 64 x 64 tile):
-//   memory term  = max(operand bytes as the tiles request them / min(8 TB/s, W * r),
-//                      operand bytes once                       / min(5 TB/s, W * r)),
-//                  W workgroups resident, each sustaining r bytes/us on its own (loads in flight over latency);
-//   serial term  = K tiles per slice * time of one K tile of that kernel with warm operands;
-//   slicing      = 2 us (the launch that scales C) + slices * M * N / 200 fp32 atomic adds per ns.
-// A bigger tile requests each operand fewer times but offers fewer, slower-starting streams; slicing restores
-// the stream count until the atomic traffic outweighs it.  Slices keep at least four K tiles and fit the chip in
-// one round.
+// tile and slice count come from the cost estimate of plan_few_tiles with constants fitted to the plan tables
+// of twenty such shapes (worst miss 18 % over a table's best, against 67 % for a rule that only ever slices
+// the 64 x 64 tile): 2 us for the launch that scales C, and 200 fp32 atomic adds per ns.
 GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K) {
   GemmPlan plan;
   make_plan_bf16(K, choose_tile(M, N), 1, &plan);
-  if (plan.tile != 64 || M < 1 || N < 1 || K < 1) return plan;
-  struct Candidate {
-    int tile, per_cu;
-    double stream, ktile_us;  // bytes/us one workgroup sustains alone; us per K tile with warm operands
-  };
-  static const Candidate cands[] = {{64, 2, 40e3, 0.192}, {128, 1, 45e3, 0.32}, {192, 1, 30e3, 0.44}, {256, 1, 25e3, 0.48}};
-  const double once = 2.0 * K * ((double)M + N);
-  double best = 0.0;
-  int best_tile = 0, best_s = 1;
-  for (const Candidate& c : cands) {
-    int bm, bn;
-    GemmPlan trial;
-    tile_dims(c.tile, &bm, &bn);
-    make_plan_bf16(K, c.tile, 1, &trial);
-    const int64_t tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn;
-    const int64_t nkt = ((int64_t)K * 2 + trial.ktb - 1) / trial.ktb, slots = 256 * c.per_cu;
-    const double requested = 2.0 * K * ((double)tm * bm * tn + (double)tn * bn * tm);
-    for (int s = 1; s <= 256; s *= 2) {
-      const int64_t items = tm * tn * s;
-      if (s > 1 && (items > slots || (int64_t)s * 4 > nkt)) break;
-      const double rate = (double)(items < slots ? items : slots) * c.stream;
-      const double mem = std::max(requested / std::min(8e6, rate), once / std::min(5e6, rate));
-      const double serial = (double)((items + slots - 1) / slots) * (double)((nkt + s - 1) / s) * c.ktile_us;
-      const double est = std::max(mem, serial) + (s > 1 ? 2.0 + (double)s * M * N / 2e5 : 0.0);
-      if (best_tile == 0 || est < best) best = est, best_tile = c.tile, best_s = s;
-    }
-  }
-  make_plan_bf16(K, best_tile, best_s, &plan);
+  if (plan.tile != 64) return plan;
+  static const SliceModel model = {{40e3, 45e3, 30e3, 25e3}, {0.192, 0.32, 0.44, 0.48}, 2.0, 2e5};
+  int tile = 64, splits = 1;
+  plan_few_tiles(M, N, (int64_t)K * 2, true, model, &tile, &splits);
+  make_plan_bf16(K, tile, splits, &plan);
   return plan;
 }
 
@@ -69,7 +39,17 @@ __global__ void __launch_bounds__(256) splitk_reduce_f32_kernel(const GemmParams
   const int n = (int)(q - (int64_t)m * quads_per_row) * 4;
   const float* part = (const float*)p.partial;
   v4f s = {0.f, 0.f, 0.f, 0.f};
-  for (int k = 0; k < p.splits; k++) s += *(const v4f*)(part + ((int64_t)k * p.M + m) * p.N + n);
+  part += (int64_t)m * p.N + n;
+  const int64_t slice = (int64_t)p.M * p.N;
+  int k = 0;
+  for (; k + 8 <= p.splits; k += 8) {  // eight loads in flight; the sum still runs in slice order
+    v4f v[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) v[u] = *(const v4f*)(part + (k + u) * slice);
+#pragma unroll
+    for (int u = 0; u < 8; u++) s += v[u];
+  }
+  for (; k < p.splits; k++) s += *(const v4f*)(part + k * slice);
   float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
   v4f o = p.alpha * s;
   if (p.beta != 0.f) o += p.beta * *(const v4f*)dst;

@@ -2,6 +2,8 @@
 #include "conv_halo.hpp"
 #include "gemm_wstat.hpp"
 
+#include <algorithm>
+
 namespace ac {
 
 static int ktb_of_tile(int tile) { return tile == 256 ? 64 : 128; }  // K bytes per tile of the kernel behind a tile code
@@ -62,10 +64,9 @@ int choose_wstat_tile(int32_t M, int32_t N, int32_t K) {
 
 // Pick block tile and K split for an M x N x K int8 problem.  The chip has 256 compute units: a launch
 // wants at least that many workgroups, and a bigger tile re-reads less of A and B.  Take the largest tile
-// that still yields enough workgroups; when even the smallest tile leaves most CUs idle and K is deep, slice
-// K so that every slice becomes its own workgroup (needs the caller's workspace for the int32 partial sums).
+// that still yields enough workgroups; when even the smallest tile leaves most CUs idle, tile and K slices come
+// from the cost estimate of plan_few_tiles (slicing needs the caller's workspace for the int32 partial sums).
 GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
-  auto tiles = [&](int t) { return (int64_t)((M + t - 1) / t) * ((N + t - 1) / t); };
   GemmPlan plan;
   plan.splits = 1;
   plan.kt_per_split = 0;
@@ -76,21 +77,15 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
     return plan;
   }
   if (plan.tile == 64) {
-    const int64_t t = tiles(64);
-    const int nkt = (K + plan.ktb - 1) / plan.ktb;
-    // The second (reduce) launch costs about 3 us and a K tile of this kernel about 0.11 us: a split pays only
-    // from some 64 K tiles on, on at most 32 tiles, and the measured optimum is then 8 slices whatever the tile
-    // count (49 x 512 x 9216: 9.8 us with 8 slices, 12.0 unsplit; 64 x 64 x 16384: 11.4 against 18.1;
-    // 49 x 2048 x 4608, 36 K tiles: 8.0 unsplit against 9.3 with the best split).
-    if (have_workspace && t <= 32 && nkt >= 64) {
-      int per = (nkt + 7) / 8;  // K tiles per slice
-      plan.kt_per_split = per;
-      plan.splits = (nkt + per - 1) / per;
-      if (plan.splits <= 1) {
-        plan.splits = 1;
-        plan.kt_per_split = 0;
-      }
-    }
+    // Constants from the plan tables of 23 int8 shapes (worst miss 38 % over a table's best; the rule this replaces,
+    // eight slices of the 64 x 64 tile from 64 K tiles on, missed by up to 3.8x on deep K).  The slices' int32
+    // partial sums go through the caller's workspace and a second launch combines them: the fit prices that at
+    // 7 us before a split pays, so 49 x 2048 x 4608 (36 K tiles) stays unsplit at 7.9 us while 49 x 512 x 9216
+    // takes slices.
+    static const SliceModel model = {{60e3, 45e3, 40e3, 25e3}, {0.066, 0.132, 0.198, 0.24}, 7.0, 4e5};
+    int tile = 64, splits = 1;
+    plan_few_tiles(M, N, K, have_workspace, model, &tile, &splits);
+    make_plan_i8(K, tile, splits, &plan);
   }
   return plan;
 }
@@ -128,6 +123,33 @@ bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
   return make_plan((int64_t)K * 2, tile, ktb_of_tile(tile), splits, plan);
 }
 
+void plan_few_tiles(int32_t M, int32_t N, int64_t kbytes, bool may_slice, const SliceModel& model, int* tile, int* splits) {
+  static const int codes[4] = {64, 128, 192, 256};
+  static const int per_cu[4] = {2, 1, 1, 1};  // workgroups of that kernel a compute unit holds (LDS)
+  const double once = (double)kbytes * ((double)M + N);
+  double best = 0.0;
+  *tile = 64, *splits = 1;
+  if (M < 1 || N < 1 || kbytes < 1) return;
+  if ((int64_t)((M + 63) / 64) * ((N + 63) / 64) > 256) return;  // enough 64 x 64 tiles for the chip: outside the fitted range
+  for (int c = 0; c < 4; c++) {
+    int bm, bn;
+    tile_dims(codes[c], &bm, &bn);
+    const int ktb = ktb_of_tile(codes[c]);
+    const int64_t tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn;
+    const int64_t nkt = (kbytes + ktb - 1) / ktb, slots = 256 * per_cu[c];
+    const double requested = (double)kbytes * ((double)tm * bm * tn + (double)tn * bn * tm);
+    for (int s = 1; s <= 256; s *= 2) {
+      const int64_t items = tm * tn * s;
+      if (s > 1 && (!may_slice || items > slots || (int64_t)s * 4 > nkt)) break;
+      const double rate = (double)(items < slots ? items : slots) * model.stream[c];
+      const double mem = std::max(requested / std::min(8e6, rate), once / std::min(5e6, rate));
+      const double serial = (double)((items + slots - 1) / slots) * (double)((nkt + s - 1) / s) * model.ktile_us[c];
+      const double est = std::max(mem, serial) + (s > 1 ? model.slice_fix_us + (double)s * M * N / model.combine_per_us : 0.0);
+      if ((c == 0 && s == 1) || est < best) best = est, *tile = codes[c], *splits = s;
+    }
+  }
+}
+
 // Output stage of a split-K launch: sum the K slices, then bias / shift / saturate / ReLU, 4 outputs per thread.
 __global__ void __launch_bounds__(256) splitk_reduce_i8_kernel(const GemmParams p) {
   const int64_t quads_per_row = p.N / 4;  // split-K is only used on the fast path: N is a multiple of 16
@@ -136,7 +158,17 @@ __global__ void __launch_bounds__(256) splitk_reduce_i8_kernel(const GemmParams 
   const int m = (int)(q / quads_per_row);
   const int n = (int)(q - (int64_t)m * quads_per_row) * 4;
   v4i s = {0, 0, 0, 0};
-  for (int k = 0; k < p.splits; k++) s += *(const v4i*)(p.partial + ((int64_t)k * p.M + m) * p.N + n);
+  const int32_t* part = p.partial + (int64_t)m * p.N + n;
+  const int64_t slice = (int64_t)p.M * p.N;
+  int k = 0;
+  for (; k + 8 <= p.splits; k += 8) {  // eight loads in flight: the slices of one output are a latency chain otherwise
+    v4i v[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) v[u] = *(const v4i*)(part + (k + u) * slice);
+#pragma unroll
+    for (int u = 0; u < 8; u++) s += v[u];
+  }
+  for (; k < p.splits; k++) s += *(const v4i*)(part + k * slice);
   int a4[4] = {s[0], s[1], s[2], s[3]};
   EpilogueI8::store4<true>(p, m, n, a4);
 }

@@ -94,6 +94,16 @@ def test_split_k_shapes(M, N, K):
     check(A, B, None, 9, 0, workspace=True)
 
 
+@pytest.mark.parametrize("M,N,K", [(512, 512, 16384), (256, 200, 40000), (300, 260, 70000), (16, 16, 100000), (384, 384, 16384), (1024, 256, 8192)])
+def test_few_tiles_deep_k_auto_plan(M, N, K):
+    """Tile and K slices chosen together by the library's cost estimate (big tiles with many slices on very deep K)."""
+    tile, splits = ops.ac_gemm_i8_auto_plan(M, N, K)
+    assert splits > 1
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + K)
+    check(A, B, bias, 14, 1, workspace=True)
+    check(A, B, None, 16, 0, workspace=True)
+
+
 def test_k_zero_and_empty():
     bias = np.arange(-40, 40, dtype=np.int32) * 100
     A = np.zeros((5, 0), np.int8)

@@ -50,6 +50,13 @@ def test_workload_configs(case):
     (1, 14, 14, 256, 64, 3, 3, 1, 1),   # few tiles, deep K
     (2, 7, 7, 512, 128, 3, 3, 1, 1),
     (1, 7, 7, 1024, 64, 3, 3, 1, 1),    # one tile, 72 K tiles: split-K when a workspace is given
+    (1, 9, 9, 16, 16, 4, 8, 1, 3),      # 32 kernel taps: the most the tap bit mask of the tiled gather holds
+    (1, 10, 10, 16, 32, 6, 6, 1, 2),    # 36 taps: beyond the mask, the element-wise gather takes it
+    (1, 12, 12, 16, 16, 7, 7, 2, 3),    # 7x7 stride 2
+    (2, 5, 7, 48, 16, 3, 3, 1, 3),      # padding wider than the kernel: border outputs see no input at all
+    (1, 6, 20, 32, 16, 1, 5, 1, 2),     # one kernel row
+    (2, 8, 8, 16, 16, 2, 2, 2, 0),      # non-overlapping windows
+    (3, 11, 13, 80, 96, 3, 3, 2, 1),    # Cin not a power of two, odd image, stride 2
 ])
 def test_shapes(Nb, H, W, Cin, Cout, KH, KW, stride, pad):
     x, w, bias = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=H * W + Cin)

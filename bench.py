@@ -3,7 +3,7 @@
 
 A *step* is one pass of the whole hot path: every workload configuration launched once, back to back,
 on one stream -- the 256^3 int8 GEMM, the six-shape int8 GEMM sweep, the two int8 convolutions, the two
-bf16 GEMMs and the batched 12x12 fp32 problem (12 launches).  Inputs are seeded, synthetic and already
+bf16 GEMMs and the batched 12x12 fp32 problem (12 calls; a call that slices K launches a second kernel).  Inputs are seeded, synthetic and already
 resident in HBM when the timed region starts.  The pass is captured once in a HIP graph and replayed,
 so that host launch overhead does not hide the kernels.
 
@@ -411,7 +411,7 @@ def main():
         "metric": METRIC, "value": round(value, 2), "unit": UNIT, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "i8+bf16+f32", "data": "synthetic",
-        "config": {"workload": "one pass over all five workload configurations (12 launches): " + ", ".join(w.name for w in wl),
+        "config": {"workload": "one pass over all five workload configurations (12 calls): " + ", ".join(w.name for w in wl),
                    "launch": "eager" if args.no_graph else "hip-graph replay", "sum_kernel_ms": round(float(kt.sum()), 5)},
         "roofline": roof,
         "per_workload": per,

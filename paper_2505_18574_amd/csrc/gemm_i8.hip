@@ -79,10 +79,13 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   if (plan.tile == 64) {
     // Constants from the plan tables of 23 int8 shapes (worst miss 38 % over a table's best; the rule this replaces,
     // eight slices of the 64 x 64 tile from 64 K tiles on, missed by up to 3.8x on deep K).  The slices' int32
-    // partial sums go through the caller's workspace and a second launch combines them: the fit prices that at
-    // 7 us before a split pays, so 49 x 2048 x 4608 (36 K tiles) stays unsplit at 7.9 us while 49 x 512 x 9216
-    // takes slices.
-    static const SliceModel model = {{60e3, 45e3, 40e3, 25e3}, {0.066, 0.132, 0.198, 0.24}, 7.0, 4e5};
+    // partial sums go through the caller's workspace and a second launch combines them.  The tables are timed on
+    // warm operands, where that second launch costs 7 us; the fixed cost used here is 5 us, which moves one
+    // boundary case: 49 x 2048 x 4608 (9.4 MB of weights behind 32 tiles) takes four slices, 9.3 us instead of
+    // 7.9 us on warm operands but 12.7 instead of 22.2 us when the weights come from HBM, as they do whenever
+    // anything else ran since the last call (a compute unit sustains only some 50 GB/s of cold misses, so few
+    // workgroups cannot stream weights however deep their prefetch).
+    static const SliceModel model = {{60e3, 45e3, 40e3, 25e3}, {0.066, 0.132, 0.198, 0.24}, 5.0, 4e5};
     int tile = 64, splits = 1;
     plan_few_tiles(M, N, K, have_workspace, model, &tile, &splits);
     make_plan_i8(K, tile, splits, &plan);

@@ -138,14 +138,16 @@ def test_auto_plans_are_host_arithmetic():
     assert ops.ac_gemm_i8_auto_plan(65536, 64, 576) == (320, 1)   # long, narrow, short K: weight-stationary kernel
     assert ops.ac_gemm_i8_auto_plan(65536, 64, 4096) == (64, 1)   # K too deep to stay resident
     # few output tiles: tile and K slices come from one cost estimate; slicing needs the workspace and is priced at
-    # several microseconds, so the 36 K tiles of 49 x 2048 x 4608 stay whole
-    assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, True) == (64, 1)
+    # several microseconds, so the 18 K tiles of 196 x 1024 x 2304 stay whole while the weight-streaming
+    # 49 x 2048 x 4608 is sliced
     assert ops.ac_gemm_i8_auto_plan(196, 1024, 2304, True) == (64, 1)
+    assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, True) == (64, 4)
+    assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, False) == (64, 1)
     tile, splits = ops.ac_gemm_i8_auto_plan(49, 512, 9216, True)
     assert tile == 64 and splits > 1
     assert ops.ac_gemm_i8_auto_plan(49, 512, 9216, False) == (64, 1)
     assert ops.ac_gemm_i8_workspace_bytes(49, 512, 9216) == ops.ac_gemm_i8_planned_workspace_bytes(49, 512, 9216, tile, splits)
-    assert ops.ac_gemm_i8_workspace_bytes(49, 2048, 4608) == 0
+    assert ops.ac_gemm_i8_workspace_bytes(196, 1024, 2304) == 0
     assert ops.ac_gemm_i8_auto_plan(256, 256, 1048576, True) == (192, 128)  # very deep K: a big tile, the chip filled once
     assert ops.ac_gemm_i8_auto_plan(256, 256, 1048576, False) == (64, 1)
     for M, N, K in [(16, 16, 100000), (300, 260, 70000), (512, 512, 16384), (1024, 256, 8192)]:

@@ -123,6 +123,7 @@ static __device__ __forceinline__ void for_each_unswapped(int mrow0, int ncol0, 
 // int8 output stage: bias, v / 2^shift to nearest (halves to even), saturate, ReLU.
 struct EpilogueI8 {
   static constexpr bool SWAP = true;
+  static constexpr bool LDS_STAGED = false;
   static __device__ __forceinline__ int requant(int v, int shift, int act) {
     int fl = v >> shift;
     unsigned int rem = (unsigned int)v & ((1u << shift) - 1u);
@@ -263,6 +264,7 @@ struct EpilogueI8 {
 // runs in splitk_reduce_i8_kernel once every slice has been written.
 struct EpiloguePartialI32 {
   static constexpr bool SWAP = false;
+  static constexpr bool LDS_STAGED = false;
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
   template <class ACC>
@@ -277,6 +279,7 @@ struct EpiloguePartialI32 {
 // C32[m][n] = acc + bias, int32, row stride ldc.
 struct EpilogueRawI32 {
   static constexpr bool SWAP = false;
+  static constexpr bool LDS_STAGED = false;
   template <bool VEC>
   static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
@@ -313,6 +316,7 @@ struct EpilogueRawI32 {
 // fp32 output: C = alpha * acc + beta * C (C read only when beta != 0).
 struct EpilogueF32 {
   static constexpr bool SWAP = false;
+  static constexpr bool LDS_STAGED = true;  // the direct-to-LDS kernels store fp32 tiles through an LDS transpose
   template <bool VEC>
   static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
@@ -355,6 +359,7 @@ struct EpilogueF32 {
 // which slices arrive is not fixed, so the last bits of a sum may differ between runs.
 struct EpilogueAtomicF32 {
   static constexpr bool SWAP = false;
+  static constexpr bool LDS_STAGED = false;
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
   template <class ACC>
@@ -370,6 +375,7 @@ struct EpilogueAtomicF32 {
 // alpha / beta, so the result does not depend on which slice finishes first.
 struct EpiloguePartialF32 {
   static constexpr bool SWAP = false;
+  static constexpr bool LDS_STAGED = false;
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
   template <class ACC>

@@ -164,14 +164,21 @@ struct EpilogueI8 {
   struct Pre {
     v4i bias[4];  // bias of this lane's 16 columns (row-vector bias only), fetched before the K loop
   };
+  // The bias row is read through a bounds-checked buffer of N int32 (no row bias: zero records), so the four
+  // loads carry no branches: columns beyond N, and every column when there is no row bias, come back as zeros.
   static __device__ __forceinline__ void prefetch(const GemmParams& p, int ncol0, int lane, Pre& pre) {
+    const bool row_bias = p.bias != nullptr && p.bias_ld == 0;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.bias, 0, row_bias && p.N <= (1 << 29) ? p.N * 4 : 0, 0x00020000);
+    const int off = (ncol0 + 4 * (lane >> 5)) * 4;
+    if (p.N <= (1 << 29)) {  // wave-uniform; byte offsets fit the 32-bit buffer arithmetic
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
-      pre.bias[q] = (v4i){0, 0, 0, 0};
-      if (p.bias && p.bias_ld == 0 && n + 3 < p.N) {
-        if ((((uintptr_t)p.bias) & 15) == 0) pre.bias[q] = *(const v4i*)(p.bias + n);
-        else pre.bias[q] = (v4i){p.bias[n], p.bias[n + 1], p.bias[n + 2], p.bias[n + 3]};
+      for (int q = 0; q < 4; q++) pre.bias[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + 32 * q, 0, 0);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+        pre.bias[q] = (v4i){0, 0, 0, 0};
+        if (row_bias && n + 3 < p.N) pre.bias[q] = (v4i){p.bias[n], p.bias[n + 1], p.bias[n + 2], p.bias[n + 3]};
       }
     }
   }

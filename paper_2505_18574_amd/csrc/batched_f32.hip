@@ -270,11 +270,7 @@ hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream) {
     // 88 us, 5: 97, 6: 97, 8: 96 for 262144 items; 2 waves: 122): past 4 waves the extra requests in flight only
     // spread the six streams over more DRAM pages.
     constexpr int WGS_PER_CU = 1;
-    static int cus = 0;
-    if (cus == 0) {
-      int dev = 0;
-      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    }
+    const int cus = compute_units();
     const int64_t ngroups = (p.batch + B12_GROUP - 1) / B12_GROUP;
     int64_t wgs = (ngroups + B12_WAVES - 1) / B12_WAVES;
     if (wgs > (int64_t)cus * WGS_PER_CU) wgs = (int64_t)cus * WGS_PER_CU;

@@ -23,6 +23,24 @@ struct FastDiv {
   __device__ __forceinline__ unsigned div(unsigned x) const { return d == 1 ? x : __umulhi(x, magic); }
 };
 
+// Compute units of the device that was current at the first call (256 if the query fails).  A function-local
+// static: initialised once, safely under concurrent first calls.  The library serves one GPU per process.
+inline int compute_units() {
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    return n;
+  }();
+  return cus;
+}
+
+// Raises a kernel's dynamic-LDS limit.  Launchers keep the result in a function-local static, so the call is
+// made once per kernel instantiation, safely under concurrent first launches.
+template <class K>
+inline hipError_t allow_dynamic_lds(K kern, int bytes) {
+  return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
 // One descriptor serves the int8 GEMM, the int8 implicit-GEMM convolution and
 // the bf16 GEMM: all three are C[M][N] = epilogue(A[M][K] . B[K][N]).
 struct GemmParams {

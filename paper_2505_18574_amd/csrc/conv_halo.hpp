@@ -360,18 +360,9 @@ static inline bool conv_halo_plan(const GemmParams& p, int bm, ConvHaloParams* h
 template <int BM, int NKS>
 static hipError_t launch_conv_halo_nks(const GemmParams& p, const ConvHaloParams& h, size_t lds, hipStream_t stream) {
   auto kern = conv_i8_halo_kernel<BM, NKS>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-  }
+  static const hipError_t configured = allow_dynamic_lds(kern, 160 * 1024);
+  if (configured != hipSuccess) return configured;
+  const int cus = compute_units();
   const int n_blocks = (p.N + 63) / 64;
   int wgs = cus / n_blocks;
   if (wgs < 1) wgs = 1;

@@ -572,24 +572,14 @@ template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMOD
 static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
   using G = DtlGeometry<T, BM, BN, WAVES_M, WAVES_N, STAGES, KTB_>;
   auto kern = gemm_dtl_kernel<T, EPI, BM, BN, WAVES_M, WAVES_N, AMODE, STAGES, KTB_, PINGPONG>;
-  static bool configured = false;
-  if (!configured && G::LDS_BYTES > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static const hipError_t configured = G::LDS_BYTES > 64 * 1024 ? allow_dynamic_lds(kern, G::LDS_BYTES) : hipSuccess;
+  if (configured != hipSuccess) return configured;
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const int ntiles = tiles_m * tiles_n;
   // one persistent workgroup per LDS-limited slot of every compute unit
-  static int slots = 0;
-  if (slots == 0) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-    const int per_cu = (160 * 1024) / (G::LDS_BYTES > 0 ? G::LDS_BYTES : 1);
-    slots = cus * (per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu));
-    slots -= slots % 8;
-  }
+  constexpr int per_cu = (160 * 1024) / (G::LDS_BYTES > 0 ? G::LDS_BYTES : 1);
+  int slots = compute_units() * (per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu));
+  slots -= slots % 8;
   const int nwork = ntiles * (p.splits > 1 ? p.splits : 1);
   const int grid = nwork < slots ? nwork : slots;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(G::THREADS), G::LDS_BYTES, stream, p, tiles_m, tiles_n);

@@ -284,20 +284,11 @@ template <int BM, int AMODE, int STAGES>
 static hipError_t launch_wstat(const GemmParams& p, hipStream_t stream) {
   using G = WstatGeometry<BM, STAGES>;
   auto kern = gemm_i8_wstat_kernel<BM, AMODE, STAGES>;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static const hipError_t configured = allow_dynamic_lds(kern, 160 * 1024);
+  if (configured != hipSuccess) return configured;
   const int nkt = (p.K + G::KTB - 1) / G::KTB;
   if (nkt < 1 || nkt > G::MAX_KT) return hipErrorInvalidValue;
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-  }
+  const int cus = compute_units();
   const int tiles_m = (p.M + BM - 1) / BM, n_blocks = (p.N + G::BN - 1) / G::BN;
   // one workgroup per compute unit (its LDS holds B and the ring); every column block gets the same number
   int wgs = cus / n_blocks;

@@ -243,18 +243,12 @@ hipError_t launch_tinympc_forward(const TinyMpcParams& p, hipStream_t stream) {
   const bool aligned16 = ((((uintptr_t)p.x0) | ((uintptr_t)p.d) | ((uintptr_t)p.u) | ((uintptr_t)p.x_out)) & 15) == 0;
   if (p.nx == 12 && p.nu == 4 && p.horizon == 5 && aligned16) {
     constexpr int LDS = (4 * 64 * 76 + 12 * 12 + 12 * 4 + 4 * 12) * (int)sizeof(float);  // 78784 bytes
-    static bool configured = false;
-    if (!configured) {
-      if (hipFuncSetAttribute((const void*)tinympc_forward_12_4_5_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess ||
-          hipFuncSetAttribute((const void*)tinympc_forward_12_4_5_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess)
-        return hipGetLastError();
-      configured = true;
-    }
-    static int cus = 0;
-    if (cus == 0) {
-      int dev = 0;
-      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    }
+    static const hipError_t configured = [] {
+      const hipError_t e = allow_dynamic_lds(tinympc_forward_12_4_5_kernel<true>, LDS);
+      return e != hipSuccess ? e : allow_dynamic_lds(tinympc_forward_12_4_5_kernel<false>, LDS);
+    }();
+    if (configured != hipSuccess) return configured;
+    const int cus = compute_units();
     const int64_t wgs = blocks < (int64_t)cus * TINYMPC_WGS_PER_CU ? blocks : (int64_t)cus * TINYMPC_WGS_PER_CU;  // persistent waves
     if (p.x_out) hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<true>, dim3((unsigned)wgs), dim3(256), LDS, stream, p);
     else hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<false>, dim3((unsigned)wgs), dim3(256), LDS, stream, p);

@@ -520,20 +520,21 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
 
   // ---- epilogue ----------------------------------------------------------------------------------------
   if constexpr (EPI::LDS_STAGED) {
-    // fp32 output through LDS: the accumulator layout gives a lane one column of many rows, so straight
+    // 4-byte outputs through LDS: the accumulator layout gives a lane one column of many rows, so straight
     // stores are dwords (one 128-byte row segment per half-wave and instruction, 128 instructions per wave for
     // a 64 x 128 wave tile, each about as slow to issue as a 16-byte one).  Every wave instead transposes 16
-    // rows of its tile at a time through a private LDS region (row pitch WTN + 8 floats: the two half-waves,
+    // rows of its tile at a time through a private LDS region (row pitch WTN + 8 values: the two half-waves,
     // four rows apart, hit different banks) and stores 16 bytes per lane, whole 128-byte lines per 8 lanes.
-    // (Cycle stamps: 11000 -> 6800 per 256 x 256 tile; writing the next chunk under the reads of this one did
-    // not shorten it further: the LDS writes and the store issue are the time, not the LDS latency.)
+    // (Cycle stamps: 11000 -> 6800 per 256 x 256 fp32 tile; writing the next chunk under the reads of this one
+    // did not shorten it further: the LDS writes and the store issue are the time, not the LDS latency.)
+    using SV = typename EPI::StagedValue;
+    typedef SV sv4 __attribute__((ext_vector_type(4)));
     constexpr int PITCH = G::WTN + 8;
     constexpr int LPR = G::WTN / 4, RPI = 64 / LPR, NI = 16 / RPI;  // lanes per row, rows per instruction, instructions per 16 rows
-    static_assert(G::WAVES * 16 * PITCH * 4 <= G::LDS_BYTES && 64 % LPR == 0 && 16 % RPI == 0, "staging region");
+    static_assert(G::WAVES * 16 * PITCH * 4 <= G::LDS_BYTES && 64 % LPR == 0 && 16 % RPI == 0 && sizeof(SV) == 4, "staging region");
     block_sync();  // every wave has read its last fragments: the stages are free
-    float* region = (float*)smem + wave * (16 * PITCH);
+    SV* region = (SV*)smem + wave * (16 * PITCH);
     const int h = lane >> 5, c = lane & 31;
-    const float alpha = p.alpha, beta = p.beta;
 #pragma unroll
     for (int i = 0; i < G::TM; i++) {
 #pragma unroll
@@ -542,17 +543,14 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
         for (int j = 0; j < G::TN; j++)
 #pragma unroll
           for (int rr = 0; rr < 8; rr++)
-            region[(8 * (rr / 4) + 4 * h + rr % 4) * PITCH + 32 * j + c] = alpha * acc[i][j][hf * 8 + rr];
+            region[(8 * (rr / 4) + 4 * h + rr % 4) * PITCH + 32 * j + c] = EPI::staged_in(p, acc[i][j][hf * 8 + rr]);
 #pragma unroll
         for (int q = 0; q < NI; q++) {
           const int row = q * RPI + lane / LPR, col = (lane % LPR) * 4;
-          v4f o = *(const v4f*)(region + row * PITCH + col);
+          const sv4 o = *(const sv4*)(region + row * PITCH + col);
           const int m = m0 + wm * G::WTM + i * 32 + hf * 16 + row, n = n0 + wn * G::WTN + col;
-          if (m < p.M && n < p.N) {  // N is a multiple of 4 on this path: a group of four columns is inside or outside
-            float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
-            if (beta != 0.f) o += beta * *(const v4f*)dst;
-            *(v4f*)dst = o;
-          }
+          // N is a multiple of 4 on this path: a group of four columns is inside or outside
+          if (m < p.M && n < p.N) EPI::staged_out(p, m, n, o, split);
         }
       }
     }

@@ -271,7 +271,12 @@ struct EpilogueI8 {
 // runs in splitk_reduce_i8_kernel once every slice has been written.
 struct EpiloguePartialI32 {
   static constexpr bool SWAP = false;
-  static constexpr bool LDS_STAGED = false;
+  static constexpr bool LDS_STAGED = true;  // the workspace is 16-byte aligned and N a multiple of 16 on this path
+  typedef int StagedValue;
+  static __device__ __forceinline__ int staged_in(const GemmParams&, int a) { return a; }
+  static __device__ __forceinline__ void staged_out(const GemmParams& p, int m, int n, v4i o, int split) {
+    *(v4i*)(p.partial + ((int64_t)split * p.M + m) * p.N + n) = o;
+  }
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
   template <class ACC>
@@ -286,7 +291,16 @@ struct EpiloguePartialI32 {
 // C32[m][n] = acc + bias, int32, row stride ldc.
 struct EpilogueRawI32 {
   static constexpr bool SWAP = false;
-  static constexpr bool LDS_STAGED = false;
+  static constexpr bool LDS_STAGED = true;  // C is 16-byte aligned with ldc a multiple of 4 on this path
+  typedef int StagedValue;
+  static __device__ __forceinline__ int staged_in(const GemmParams&, int a) { return a; }
+  static __device__ __forceinline__ void staged_out(const GemmParams& p, int m, int n, v4i o, int) {
+    if (p.bias) {
+      const int32_t* b = p.bias_ld == 0 ? p.bias + n : p.bias + (int64_t)m * p.bias_ld + n;  // only 4-byte aligned
+      o += (v4i){b[0], b[1], b[2], b[3]};
+    }
+    *(v4i*)((int32_t*)p.C + (int64_t)m * p.ldc + n) = o;
+  }
   template <bool VEC>
   static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const int* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
@@ -323,7 +337,16 @@ struct EpilogueRawI32 {
 // fp32 output: C = alpha * acc + beta * C (C read only when beta != 0).
 struct EpilogueF32 {
   static constexpr bool SWAP = false;
-  static constexpr bool LDS_STAGED = true;  // the direct-to-LDS kernels store fp32 tiles through an LDS transpose
+  // The direct-to-LDS kernels hand over 4-byte outputs through an LDS transpose: staged_in() is applied to every
+  // accumulator on its way into LDS, staged_out() receives four consecutive columns of one row.
+  static constexpr bool LDS_STAGED = true;
+  typedef float StagedValue;
+  static __device__ __forceinline__ float staged_in(const GemmParams& p, float a) { return p.alpha * a; }
+  static __device__ __forceinline__ void staged_out(const GemmParams& p, int m, int n, v4f o, int) {
+    float* dst = (float*)p.C + (int64_t)m * p.ldc + n;
+    if (p.beta != 0.f) o += p.beta * *(const v4f*)dst;
+    *(v4f*)dst = o;
+  }
   template <bool VEC>
   static __device__ __forceinline__ void store4(const GemmParams& p, int m, int n, const float* a, int = 0) {
     if (m >= p.M || n >= p.N) return;
@@ -382,7 +405,12 @@ struct EpilogueAtomicF32 {
 // alpha / beta, so the result does not depend on which slice finishes first.
 struct EpiloguePartialF32 {
   static constexpr bool SWAP = false;
-  static constexpr bool LDS_STAGED = false;
+  static constexpr bool LDS_STAGED = true;  // the workspace is 16-byte aligned and N a multiple of 8 on this path
+  typedef float StagedValue;
+  static __device__ __forceinline__ float staged_in(const GemmParams&, float a) { return a; }
+  static __device__ __forceinline__ void staged_out(const GemmParams& p, int m, int n, v4f o, int split) {
+    *(v4f*)((float*)p.partial + ((int64_t)split * p.M + m) * p.N + n) = o;
+  }
   struct Pre {};
   static __device__ __forceinline__ void prefetch(const GemmParams&, int, int, Pre&) {}
   template <class ACC>

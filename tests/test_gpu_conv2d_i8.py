@@ -64,6 +64,32 @@ def test_shapes(Nb, H, W, Cin, Cout, KH, KW, stride, pad):
     check(x, w, None, stride, pad, 5, 0)
 
 
+@pytest.mark.parametrize("case", inputs.CONV_I8, ids=lambda c: c.name)
+def test_batch_256_sampled_images(case):
+    """The workload convolutions at batch 256, as the benchmark's scale-up lines launch them (the library then
+    picks its large-problem kernels): images are independent, so whole output images are checked against the
+    oracle run on those images alone, and the last image guards the end of the buffers."""
+    Nb = 256
+    x, w, bias = inputs.conv_i8_inputs(Nb, case.H, case.W, case.Cin, case.Cout, case.KH, case.KW, seed=case.seed + 7)
+    out = torch.full((Nb, case.OH, case.OW, case.Cout), 99, dtype=torch.int8, device="cuda")
+    ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, case.stride, case.pad, case.shift, case.act)
+    torch.cuda.synchronize()
+    got = host(out)
+    picks = [0, 1, 100, 191, 254, 255]
+    want = oracle.conv2d_i8(np.ascontiguousarray(x[picks]), w, bias, case.stride, case.pad, case.shift, case.act)
+    np.testing.assert_array_equal(got[picks], want)
+    # images the oracle did not see: an image that equals a checked one must produce that one's output
+    x2 = x.copy()
+    x2[7] = x[100]
+    x2[200] = x[0]
+    ops.ac_conv2d_i8(dev(x2), dev(w), dev(bias), out, case.stride, case.pad, case.shift, case.act)
+    torch.cuda.synchronize()
+    got2 = host(out)
+    np.testing.assert_array_equal(got2[7], want[2])
+    np.testing.assert_array_equal(got2[200], want[0])
+    np.testing.assert_array_equal(got2[picks], want)
+
+
 def test_small_magnitudes():
     x, w, bias = inputs.conv_i8_inputs(2, 9, 9, 16, 32, 3, 3, seed=1, lo=-3, hi=3, bias_bits=4)
     for shift in (0, 1, 2, 3):

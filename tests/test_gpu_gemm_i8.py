@@ -138,10 +138,11 @@ def test_strided_views_and_guard_bands():
     assert (out[mask] == 55).all()
 
 
-def test_full_size_sampled_large():
-    """A shape far larger than the workloads (8192 x 8192 x 1024): sampled outputs against the oracle."""
+@pytest.mark.parametrize("K", [1024, 8192])
+def test_full_size_sampled_large(K):
+    """Shapes far larger than the workloads (8192 x 8192 x 1024, and the 8192^3 of the benchmark's scale-up line):
+    sampled outputs against the oracle."""
     M = N = 8192
-    K = 1024
     A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=77)
     got = run_gpu(A, B, bias, 12, 1)
     rng = np.random.default_rng(0)

@@ -262,22 +262,33 @@ hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmP
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
   const bool fast = conv_i8_fast_path(p);
   if (!forced && fast) {
-    // The patch kernel (weights and the image patch of a unit both in LDS) once the convolution has at least a
-    // unit of 256 output pixels per compute unit and column block: measured 20.8 against 28.4 us (next best
-    // kernel) on 64 images of 56 x 56 x 64 -> 64, 47 against 82 us on 256; below that the fixed cost of filling
-    // LDS once per workgroup makes the 64 x 64 tiles the faster choice.
+    // The patch kernel (weights and the image patch of a unit both in LDS) as soon as the 64 x 64 tiles would
+    // need a second round on the chip (more than two per compute unit), or the convolution has a unit of 256
+    // output pixels per compute unit and column block.  Plan tables, 56 x 56 x 64 -> 64: 10 images (490 tiles)
+    // 6.5 us tiled against 7.5 us, 12 images (588 tiles) 9.2 against 7.5, 16 images 10.0 against 7.6, 64 images
+    // 28 against 17; 56 x 56 x 64 -> 128 at 8 images 10.0 against 7.7.  Below that the fixed cost of filling LDS
+    // once per workgroup makes the 64 x 64 tiles the faster choice.
     ConvHaloParams h;
     size_t lds = 0;
     GemmParams q = p;
     q.splits = 1;
     q.kt_per_split = 0;
+    const int64_t nblk = (p.N + 63) / 64, tiles64 = (int64_t)((p.M + 63) / 64) * nblk;
     if (conv_halo_plan(p, 256, &h, &lds)) {
-      if ((int64_t)h.units * ((p.N + 63) / 64) >= 256) return launch_conv_halo<256>(q, h, lds, stream);
-    } else if (conv_halo_plan(p, 128, &h, &lds) && (int64_t)h.units * ((p.N + 63) / 64) >= 512) {
-      // the patch of 256 pixels does not fit, that of 128 does (64 images of 28 x 28 x 128 -> 128: 18.9 us against
-      // 22.9 us on the tiled kernels)
-      return launch_conv_halo<128>(q, h, lds, stream);
+      if (h.units * nblk >= 256 || tiles64 > 512) return launch_conv_halo<256>(q, h, lds, stream);
+    } else if (conv_halo_plan(p, 128, &h, &lds)) {
+      // the patch of 256 pixels does not fit, that of 128 does (28 x 28 x 128 -> 128: 64 images 18.7 us against
+      // 18.5 us on the best tiled kernel, 128 images 29.6 against 33.6)
+      if (h.units * nblk >= 512) return launch_conv_halo<128>(q, h, lds, stream);
+    } else {
+      return dispatch_i8<1>(p, stream, aligned, fast, forced);
     }
+    // a convolution the patch kernel could take but that is too small for it: the tiled kernels, never the
+    // weight-stationary one, whose gather loses to both (28 x 28 x 128 -> 128, 32 images: 13.9 us against 10.2)
+    GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, p.partial != nullptr);
+    int ws_bm;
+    if (wstat_tile_rows(plan.tile, &ws_bm)) make_plan_i8(p.K, choose_tile(p.M, p.N), 1, &plan);  // unsplit: no workspace needed
+    return dispatch_i8<1>(p, stream, aligned, fast, &plan);
   }
   return dispatch_i8<1>(p, stream, aligned, fast, forced);
 }

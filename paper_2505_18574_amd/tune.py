@@ -1,11 +1,11 @@
-"""Search over the launch plans (block tile, K split) of the two GEMM entry points.
+"""Search over the launch plans (kernel / block tile, K split) of the GEMM and convolution entry points.
 
 This is the part of the paper's optimisation loop that needs no language model: candidates are run on the
 device, kept only if their output is still correct, and ranked by measured latency; the best few seed the
 next iteration (beam search, Section 3.3).  A plan found for one shape can seed the search for a related
 shape, which then looks only at that plan and its neighbours (schedule reuse, Sections 3.5 and 5).
 
-A candidate here is a (tile, splits) pair of ac_gemm_i8_planned / ac_gemm_bf16_planned.  Every candidate is
+A candidate here is a (tile, splits) pair of ac_gemm_i8_planned / ac_gemm_bf16_planned / ac_conv2d_i8_planned.  Every candidate is
 run through the C ABI; nothing is computed on the host.  The correctness gate is a callable supplied by the
 caller (the tests pass one that compares against the CPU oracle); without one, a candidate must reproduce the
 library's own unplanned result -- bit for bit for int8, to a relative Frobenius error of 1e-5 for bf16 (two
@@ -27,13 +27,16 @@ TILE_DIMS = {64: (64, 64), 128: (128, 128), 192: (256, 128), 256: (256, 256), 16
 # int8 only: the weight-stationary kernel (128- / 256-row tiles, 64 columns, all of K resident in LDS, no K split)
 WS_TILES = (160, 320)
 WS_MAX_K = {160: 2048, 320: 1536}
+# convolutions only (kind "conv"): the patch kernel with 128- / 256-pixel work units; the library refuses it for
+# geometries it does not fit, and a refused plan simply drops out of the search
+HALO_TILES = (161, 321)
 MAX_WORKGROUPS = 8192          # more slices than this only add reduction traffic
 MAX_WORKSPACE_BYTES = 1 << 30  # partial sums (int32 / fp32, splits * M * N * 4 bytes) the tuner is willing to allocate
 
 
 def k_tiles(kind: str, K: int, tile: int) -> int:
     """K tiles of the kernel behind `tile`: 64 bytes of K per tile for the 256 tile, 128 bytes otherwise."""
-    kbytes = K * (1 if kind == "i8" else 2)
+    kbytes = K * (2 if kind == "bf16" else 1)
     ktb = 64 if tile == 256 else 128
     return (kbytes + ktb - 1) // ktb
 
@@ -51,7 +54,9 @@ def normalise(kind: str, K: int, plan: Plan) -> Plan:
 def valid(kind: str, M: int, N: int, K: int, plan: Plan) -> bool:
     tile, splits = plan
     if tile in WS_TILES:
-        return kind == "i8" and splits == 1 and 1 <= K <= WS_MAX_K[tile]
+        return kind in ("i8", "conv") and splits == 1 and 1 <= K <= WS_MAX_K[tile]
+    if tile in HALO_TILES:
+        return kind == "conv" and splits == 1
     if tile not in TILES or splits < 1 or (splits > 1 and splits > k_tiles(kind, K, tile)):
         return False
     bm, bn = TILE_DIMS[tile]
@@ -73,7 +78,7 @@ def all_plans(kind: str, M: int, N: int, K: int) -> List[Plan]:
             if q not in out:
                 out.append(q)
             s *= 2
-    out += [(t, 1) for t in WS_TILES if valid(kind, M, N, K, (t, 1))]
+    out += [(t, 1) for t in WS_TILES + HALO_TILES if valid(kind, M, N, K, (t, 1))]
     return out
 
 
@@ -91,7 +96,7 @@ def seed_plans(kind: str, M: int, N: int, K: int, auto: Plan, workgroups: int = 
         q = normalise(kind, K, (tile, s))
         if valid(kind, M, N, K, q) and q not in out:
             out.append(q)
-    out += [(t, 1) for t in WS_TILES if valid(kind, M, N, K, (t, 1)) and (t, 1) not in out]
+    out += [(t, 1) for t in WS_TILES + HALO_TILES if valid(kind, M, N, K, (t, 1)) and (t, 1) not in out]
     return out
 
 
@@ -99,7 +104,9 @@ def neighbours(kind: str, M: int, N: int, K: int, plan: Plan) -> List[Plan]:
     """One step from `plan`: the next tile code up or down, half or twice the split."""
     tile, splits = plan
     if tile in WS_TILES:  # its neighbours: the other row-tile height, and the tiled kernels of similar height
-        cand = [(WS_TILES[1 - WS_TILES.index(tile)], 1), (64, 1), (192, 1)]
+        cand = [(WS_TILES[1 - WS_TILES.index(tile)], 1), (64, 1), (192, 1)] + [(t, 1) for t in HALO_TILES]
+    elif tile in HALO_TILES:  # the other unit size, the other resident-operand kernel, the tiled kernels
+        cand = [(HALO_TILES[1 - HALO_TILES.index(tile)], 1)] + [(t, 1) for t in WS_TILES] + [(64, 1), (192, 1)]
     else:
         i = TILES.index(tile)
         cand = [(TILES[j], splits) for j in (i - 1, i + 1) if 0 <= j < len(TILES)]
@@ -269,6 +276,22 @@ def _bf16_problem(A, B, C, alpha: float, beta: float) -> _Problem:
     return _Problem("bf16", M, N, K, run, reference, C, exact=False)
 
 
+def _conv_problem(x, w, bias, out, stride: int, pad: int, shift: int, act: int) -> _Problem:
+    Nb, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    M, N, K = out.shape[0] * out.shape[1] * out.shape[2], Cout, KH * KW * Cin
+    workspace = _workspace_pool(x.device)
+
+    def run(plan: Plan):
+        ws = workspace(ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, plan[0], plan[1]))
+        ops.ac_conv2d_i8(x, w, bias, out, stride, pad, shift, act, workspace=ws, plan=plan)
+
+    def reference():
+        ops.ac_conv2d_i8(x, w, bias, out, stride, pad, shift, act, workspace=workspace(ops.ac_gemm_i8_workspace_bytes(M, N, K)))
+
+    return _Problem("conv", M, N, K, run, reference, out, exact=True)
+
+
 def tune_gemm_i8(A, B, bias, C, shift: int, act: int, gate=None, start: Optional[Iterable[Plan]] = None,
                  beam: int = 3, iterations: int = 4, exhaustive: bool = False) -> TuneResult:
     """Best (tile, splits) for this int8 GEMM.  `start`: plans to seed the beam with (default: seed_plans());
@@ -284,6 +307,16 @@ def tune_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, gate=None, st
     """Best (tile, splits) for this bf16 GEMM; arguments as for tune_gemm_i8."""
     prob = _bf16_problem(A, B, C, alpha, beta)
     seeds = list(start) if start is not None else seed_plans("bf16", prob.M, prob.N, prob.K, ops.ac_gemm_bf16_auto_plan(prob.M, prob.N, prob.K))
+    return _search(prob, gate, seeds, beam, iterations, exhaustive)
+
+
+def tune_conv2d_i8(x, w, bias, out, stride: int, pad: int, shift: int, act: int, gate=None,
+                   start: Optional[Iterable[Plan]] = None, beam: int = 3, iterations: int = 4, exhaustive: bool = False) -> TuneResult:
+    """Best (kernel / tile, splits) for this NHWC int8 convolution: the tiled kernels with their K splits, the
+    weight-stationary kernel and the patch kernel (codes 161 / 321), each where the geometry admits it.  Arguments
+    as for tune_gemm_i8; `out` is overwritten."""
+    prob = _conv_problem(x, w, bias, out, stride, pad, shift, act)
+    seeds = list(start) if start is not None else seed_plans("conv", prob.M, prob.N, prob.K, ops.ac_gemm_i8_auto_plan(prob.M, prob.N, prob.K, True))
     return _search(prob, gate, seeds, beam, iterations, exhaustive)
 
 

@@ -109,6 +109,29 @@ def test_search_int8_with_oracle_gate_and_reuse():
     assert len(book.plans) == 3
 
 
+@pytest.mark.parametrize("Nb,H,W,Cin,Cout,stride,pad", [(16, 56, 56, 64, 64, 1, 1), (8, 28, 28, 128, 256, 2, 1), (4, 14, 14, 256, 64, 1, 1)])
+def test_search_conv_exhaustive_with_oracle_gate(Nb, H, W, Cin, Cout, stride, pad):
+    """Every kernel / tile / K split the library offers for a convolution, gated by the oracle: each plan either
+    is refused by the library (a geometry its kernel does not take) or reproduces the oracle bit for bit."""
+    x, w, bias = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, 3, 3, seed=Nb + Cin)
+    want = torch.from_numpy(oracle.conv2d_i8(x, w, bias, stride, pad, 9, 1)).cuda()
+    out = torch.empty_like(want)
+    gate = lambda got: bool(torch.equal(got, want))
+    res = tune.tune_conv2d_i8(dev(x), dev(w), dev(bias), out, stride, pad, 9, 1, gate=gate, exhaustive=True)
+    print("conv", (Nb, H, W, Cin, Cout, stride), "best", res.best, f"{res.best_us:.2f} us",
+          [(t.plan, t.us and round(t.us, 2)) for t in res.trials], flush=True)
+    M, N, K = want.shape[0] * want.shape[1] * want.shape[2], Cout, 9 * Cin
+    assert len(res.trials) == len(tune.all_plans("conv", M, N, K))
+    refused = [t.plan for t in res.trials if not t.correct]
+    for plan in refused:  # a candidate that is not correct must be one the library refuses, never a wrong result
+        with pytest.raises(ops.AcError):
+            ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, stride, pad, 9, 1, plan=plan)
+    assert all(p[0] in tune.WS_TILES + tune.HALO_TILES for p in refused)
+    # beam search from the library's own plan ends at a plan no slower than the library's
+    res2 = tune.tune_conv2d_i8(dev(x), dev(w), dev(bias), out, stride, pad, 9, 1, gate=gate)
+    assert res2.best in [t.plan for t in res.trials]
+
+
 def test_search_bf16_exhaustive_default_gate():
     M, N, K = 256, 256, 16384
     A, B = inputs.gemm_bf16_inputs(M, N, K, seed=9)

@@ -41,6 +41,20 @@ def test_seed_plans_cover_every_tile():
     assert set(tune.neighbours("i8", 4096, 64, 512, (320, 1))) == {(160, 1), (64, 1), (192, 1)}
 
 
+def test_convolution_plan_space():
+    # a convolution adds the patch kernel's two unit sizes to the int8 plan space; they never split K
+    M, N, K = 8 * 56 * 56, 64, 576
+    plans = tune.all_plans("conv", M, N, K)
+    assert set(tune.all_plans("i8", M, N, K)) | {(161, 1), (321, 1)} == set(plans)
+    assert tune.valid("conv", M, N, K, (321, 1)) and not tune.valid("conv", M, N, K, (321, 2))
+    assert not tune.valid("i8", M, N, K, (321, 1)) and not tune.valid("bf16", M, N, K, (161, 1))
+    seeds = tune.seed_plans("conv", M, N, K, (64, 1))
+    assert seeds[0] == (64, 1) and {(160, 1), (320, 1), (161, 1), (321, 1)} <= set(seeds)
+    assert set(tune.neighbours("conv", M, N, K, (321, 1))) == {(161, 1), (160, 1), (320, 1), (64, 1), (192, 1)}
+    assert {(161, 1), (321, 1)} <= set(tune.neighbours("conv", M, N, K, (320, 1)))
+    assert tune.k_tiles("conv", K, 64) == tune.k_tiles("i8", K, 64)
+
+
 class FakeProblem(tune._Problem):
     """A cost model in place of the device: latency by plan, and a set of plans whose output is 'wrong'."""
 

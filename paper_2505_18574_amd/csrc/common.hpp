@@ -100,8 +100,17 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace);
 GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K);
 // Rows / columns of a tile code (false for an unknown code).
 bool tile_dims(int32_t tile, int* bm, int* bn);
-// Tile code the library picks for an M x N output.
+// Tile code the library picks for an M x N output when nothing else is known (convolutions, fallbacks).
 int choose_tile(int32_t M, int32_t N);
+// Kernel / tile code for a GEMM with more than 256 tiles of 64 x 64 (more than the chip holds at once), from
+// per-code time estimates  t = c0 + rounds * (c1 + c2 * k)  with k = K bytes / 128 and rounds = the number of
+// times the code's workgroups fill the chip (tiled codes), or  t = c0 + rounds * (c1 k + c2 r + c3 r k)  with r =
+// row tiles per workgroup (the weight-stationary codes, int8 only, where K and the bias layout admit them).  The
+// coefficients are least-squares fits to the measured times of every code on some 300 int8 and 200 bf16 shapes
+// (M, N 256..16384, K 64..8192); on shapes held out of the fit the chosen code is on average 1 % slower than
+// the best one (worst case 24 %), against 10 % (63 %) for thresholds on the tile count alone.
+int choose_tile_i8(int32_t M, int32_t N, int32_t K, bool allow_weight_stationary);
+int choose_tile_bf16(int32_t M, int32_t N, int32_t K);
 // Explicit plans: false when the tile code is unknown, or splits is outside 1 .. number of K tiles.
 // Tile and K slices for a problem whose 64 x 64 tiles would leave most of the chip idle: the pair that minimises
 //   max(memory term, serial term) + slicing cost, with

@@ -5,16 +5,19 @@
 
 namespace ac {
 
-// Block tile and K split for an M x N x K bf16 problem: the largest tile that still gives most compute units
-// work (thresholds from exhaustive plan tables: 256 x 256 from 192 tiles, 128 x 128 from 128 tiles).  When even
-// 64 x 64 tiles leave most of the chip idle, K is cut into slices that add into C (see EpilogueAtomicF32), and
-// tile and slice count come from the cost estimate of plan_few_tiles with constants fitted to the plan tables
-// of twenty such shapes (worst miss 18 % over a table's best, against 67 % for a rule that only ever slices
-// the 64 x 64 tile): 2 us for the launch that scales C, and 200 fp32 atomic adds per ns.
+// Block tile and K split for an M x N x K bf16 problem.  With more 64 x 64 tiles than the chip holds at once: the
+// tile with the lowest time estimate (choose_tile_bf16), unsplit.  With fewer, K is cut into slices that add into
+// C (see EpilogueAtomicF32), and tile and slice count come from the cost estimate of plan_few_tiles with constants
+// fitted to the plan tables of twenty such shapes (worst miss 18 % over a table's best, against 67 % for a rule
+// that only ever slices the 64 x 64 tile): 2 us for the launch that scales C, and 200 fp32 atomic adds per ns.
 GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K) {
   GemmPlan plan;
-  make_plan_bf16(K, choose_tile(M, N), 1, &plan);
-  if (plan.tile != 64) return plan;
+  make_plan_bf16(K, 64, 1, &plan);
+  if (M < 1 || N < 1) return plan;
+  if ((int64_t)((M + 63) / 64) * ((N + 63) / 64) > 256) {  // more 64 x 64 tiles than the chip holds at once
+    make_plan_bf16(K, choose_tile_bf16(M, N, K), 1, &plan);
+    return plan;
+  }
   static const SliceModel model = {{40e3, 45e3, 30e3, 25e3}, {0.192, 0.32, 0.44, 0.48}, 2.0, 2e5};
   int tile = 64, splits = 1;
   plan_few_tiles(M, N, (int64_t)K * 2, true, model, &tile, &splits);
@@ -70,7 +73,7 @@ hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const Gemm
   GemmPlan plan = forced ? *forced : plan_gemm_bf16(p.M, p.N, p.K);
   if (plan.splits > 1 && !fast) {
     if (forced) return hipErrorInvalidValue;
-    make_plan_bf16(p.K, choose_tile(p.M, p.N), 1, &plan);  // the generic kernels do not slice K
+    make_plan_bf16(p.K, choose_tile(p.M, p.N), 1, &plan);  // the generic kernels do not slice K and have square tiles
   }
   p.splits = plan.splits;
   p.kt_per_split = plan.kt_per_split;

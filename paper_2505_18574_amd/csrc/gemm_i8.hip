@@ -33,6 +33,65 @@ int choose_tile(int32_t M, int32_t N) {
   return 64;
 }
 
+namespace {
+struct TiledCost { double c0, per_round, per_round_k; };
+struct StationaryCost { double c0, per_k, per_row_tile, per_row_tile_k; };
+// time estimate (us) of a tiled code: bm x bn tiles, per_cu workgroups resident per compute unit
+double tiled_estimate(const TiledCost& c, int bm, int bn, int per_cu, int32_t M, int32_t N, int64_t k128) {
+  const int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn), slots = 256 * per_cu;
+  const double rounds = (double)((tiles + slots - 1) / slots);
+  return c.c0 + rounds * (c.per_round + c.per_round_k * (double)k128);
+}
+// ... of a weight-stationary code: every column block of 64 gets the same number of persistent workgroups
+double stationary_estimate(const StationaryCost& c, int bm, int32_t M, int32_t N, int64_t k128) {
+  const int64_t nblk = (N + 63) / 64, tm = (M + bm - 1) / bm;
+  int64_t wgs = nblk <= 256 ? 256 / nblk : 1;
+  if (wgs > tm) wgs = tm;
+  if (wgs < 1) wgs = 1;
+  const double per = (double)((tm + wgs - 1) / wgs), rounds = (double)((wgs * nblk + 255) / 256);
+  return c.c0 + rounds * (c.per_k * (double)k128 + c.per_row_tile * per + c.per_row_tile_k * per * (double)k128);
+}
+int cheapest_tiled(const TiledCost (&c)[4], int32_t M, int32_t N, int64_t k128, double* cost) {
+  static const int codes[4] = {64, 128, 192, 256}, per_cu[4] = {2, 1, 1, 1};
+  int best = 64;
+  // from three rounds of 256 x 256 tiles on, only that tile: the fits stop at 8192 x 8192 outputs, and beyond
+  // them the smaller tiles' estimates grow too slowly (32768 x 32768 x 32 bf16: 814 us against 1006 us on 128 x 128)
+  const bool huge = (int64_t)((M + 255) / 256) * ((N + 255) / 256) >= 768;
+  for (int i = huge ? 3 : 0; i < 4; i++) {
+    int bm, bn;
+    tile_dims(codes[i], &bm, &bn);
+    const double t = tiled_estimate(c[i], bm, bn, per_cu[i], M, N, k128);
+    if (i == 0 || huge || t < *cost) *cost = t, best = codes[i];
+  }
+  return best;
+}
+}  // namespace
+
+int choose_tile_i8(int32_t M, int32_t N, int32_t K, bool allow_weight_stationary) {
+  static const TiledCost tiled[4] = {{1.298, 1.791, 0.3930}, {1.564, 3.370, 0.4437}, {1.075, 6.635, 0.7549}, {-1.198, 10.768, 1.0961}};
+  static const StationaryCost st160 = {2.414, 0.0705, 1.0672, 0.4786}, st320 = {2.397, 0.0043, 1.2743, 0.6840};
+  const int64_t k128 = ((int64_t)K + 127) / 128;
+  double cost = 0.0;
+  int best = cheapest_tiled(tiled, M, N, k128, &cost);
+  if (allow_weight_stationary && K >= 16) {
+    if (k128 <= wstat_max_kt(160)) {
+      const double t = stationary_estimate(st160, 128, M, N, k128);
+      if (t < cost) cost = t, best = 160;
+    }
+    if (k128 <= wstat_max_kt(320)) {
+      const double t = stationary_estimate(st320, 256, M, N, k128);
+      if (t < cost) cost = t, best = 320;
+    }
+  }
+  return best;
+}
+
+int choose_tile_bf16(int32_t M, int32_t N, int32_t K) {
+  static const TiledCost tiled[4] = {{1.944, 1.630, 0.3737}, {1.479, 3.315, 0.4174}, {-0.530, 7.057, 0.6704}, {-6.486, 15.278, 0.9995}};
+  double cost = 0.0;
+  return cheapest_tiled(tiled, M, N, ((int64_t)K * 2 + 127) / 128, &cost);
+}
+
 // The weight-stationary kernel takes direct-to-LDS operands (checked by the caller), no bias or a bias row, and a
 // K whose 64-column block of B fits in LDS beside the ring of A stages.
 bool wstat_eligible(const GemmParams& p, int tile) {
@@ -49,34 +108,22 @@ bool conv_halo_eligible(const GemmParams& p, int tile) {
   return halo_tile_rows(tile, &bm) && conv_halo_plan(p, bm, &h, &lds);
 }
 
-// Shapes the library hands to the weight-stationary kernel by itself (from timings of every tile code on this
-// chip): a narrow output (at most two 64-column blocks, so A passes through the compute units at most twice),
-// a K short enough to stay resident beside the deep ring, and enough 256-row tiles to give most compute units
-// a stream of their own.  Smaller problems are faster on the 64 x 64 tiles, wider ones on the big square tiles.
-// 0 = not this kernel.
-int choose_wstat_tile(int32_t M, int32_t N, int32_t K) {
-  if (M < 1 || N < 1 || N > 128 || K < 16) return 0;
-  const int nkt = (K + 127) / 128;
-  const int64_t nblk = (N + 63) / 64;
-  if (((M + 255) / 256) * nblk < 192) return 0;
-  return nkt <= wstat_max_kt(320) ? 320 : 0;
-}
-
-// Pick block tile and K split for an M x N x K int8 problem.  The chip has 256 compute units: a launch
-// wants at least that many workgroups, and a bigger tile re-reads less of A and B.  Take the largest tile
-// that still yields enough workgroups; when even the smallest tile leaves most CUs idle, tile and K slices come
-// from the cost estimate of plan_few_tiles (slicing needs the caller's workspace for the int32 partial sums).
+// Kernel / tile and K split for an M x N x K int8 problem.  With more 64 x 64 tiles than the chip holds at once:
+// the code with the lowest time estimate (choose_tile_i8), unsplit.  With fewer: tile and K slices together from
+// the cost estimate of plan_few_tiles (slicing needs the caller's workspace for the int32 partial sums).
 GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   GemmPlan plan;
   plan.splits = 1;
   plan.kt_per_split = 0;
-  plan.tile = choose_tile(M, N);
+  plan.tile = 64;
   plan.ktb = ktb_of_tile(plan.tile);
-  if (const int ws = choose_wstat_tile(M, N, K)) {
-    plan.tile = ws;
+  if (M < 1 || N < 1) return plan;
+  if ((int64_t)((M + 63) / 64) * ((N + 63) / 64) > 256) {  // more 64 x 64 tiles than the chip holds at once
+    plan.tile = choose_tile_i8(M, N, K, true);
+    plan.ktb = ktb_of_tile(plan.tile);
     return plan;
   }
-  if (plan.tile == 64) {
+  {
     // Constants from the plan tables of 23 int8 shapes (worst miss 38 % over a table's best; the rule this replaces,
     // eight slices of the 64 x 64 tile from 64 K tiles on, missed by up to 3.8x on deep K).  The slices' int32
     // partial sums go through the caller's workspace and a second launch combines them.  The tables are timed on
@@ -181,7 +228,7 @@ hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast
   GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr);
   int ws_bm;
   if (!forced && wstat_tile_rows(plan.tile, &ws_bm) && !(fast && wstat_eligible(p, plan.tile))) {
-    plan.tile = choose_tile(p.M, p.N);  // operands the weight-stationary kernel does not take: the tiled kernels
+    plan.tile = choose_tile_i8(p.M, p.N, p.K, false);  // operands the weight-stationary kernel does not take: the tiled kernels
     plan.ktb = ktb_of_tile(plan.tile);
   }
   p.splits = plan.splits;
@@ -235,7 +282,7 @@ hipError_t launch_gemm_i8_acc32(const GemmParams& p0, hipStream_t stream) {
   p.kt_per_split = 0;
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) && aligned16(p.C) && (p.ldc % 4 == 0);
   const bool fast = aligned && (p.K % 16 == 0) && (p.N % 16 == 0);
-  if (fast) return launch_dtl_tile<TypeI8, EpilogueRawI32, 0>(choose_tile(p.M, p.N), p, stream);
+  if (fast) return launch_dtl_tile<TypeI8, EpilogueRawI32, 0>(choose_tile(p.M, p.N), p, stream);  // 4-byte output: its own regime, thresholds kept
   return aligned ? launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, true>(p, stream)
                  : launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, false>(p, stream);
 }

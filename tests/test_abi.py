@@ -154,6 +154,19 @@ def test_auto_plans_are_host_arithmetic():
         tile, splits = ops.ac_gemm_i8_auto_plan(M, N, K, True)
         assert splits > 1
         assert ops.ac_gemm_i8_workspace_bytes(M, N, K) == ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits) > 0
+    # more 64 x 64 tiles than the chip holds at once: the code with the lowest fitted time estimate
+    assert ops.ac_gemm_i8_auto_plan(8192, 8192, 8192) == (256, 1) and ops.ac_gemm_bf16_auto_plan(4096, 8192, 8192) == (256, 1)
+    assert ops.ac_gemm_bf16_auto_plan(2048, 4096, 8192) == (192, 1)      # 128 tiles of 256 x 256 would idle half the chip
+    assert ops.ac_gemm_i8_auto_plan(3072, 3072, 768) == (256, 1)         # 144 big tiles in one round beat 288 in two
+    assert ops.ac_gemm_i8_auto_plan(4096, 4096, 128) == (320, 1)         # short K: weight-stationary also on a wide output
+    assert ops.ac_gemm_i8_auto_plan(4096, 4096, 2048)[0] in (128, 192, 256)   # K too deep to stay resident
+    assert ops.ac_gemm_bf16_auto_plan(32768, 32768, 32) == (256, 1)      # beyond the fitted range: the big tile
+    for M, N, K in [(5000, 3000, 100), (700, 9000, 3000), (100000, 64, 16), (64, 100000, 4000), (12345, 6789, 1011)]:
+        assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[1] == 1 and ops.ac_gemm_bf16_auto_plan(M, N, K)[1] == 1
+        assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[0] in (64, 128, 192, 256, 160, 320)
+        assert ops.ac_gemm_bf16_auto_plan(M, N, K)[0] in (64, 128, 192, 256)
+        if K > 2048:
+            assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[0] not in (160, 320)
     # bf16 with few output tiles: tile and slice count come from one cost estimate; a very deep K takes a
     # big tile (operands requested fewer times) and enough slices to fill the chip once
     assert ops.ac_gemm_bf16_auto_plan(256, 256, 524288) == (192, 128)

@@ -201,8 +201,11 @@ def test_patch_kernel_plan_errors():
 
 # ---- the library's own choice: shapes that ac_gemm_i8 / ac_conv2d_i8 hand to these kernels by themselves ----
 
-@pytest.mark.parametrize("M,N,K", [(60000, 32, 16), (50000, 128, 1536), (49153, 80, 272)])
+@pytest.mark.parametrize("M,N,K", [(60000, 32, 16), (49153, 80, 272), (50000, 128, 256),
+                                   (2048, 4096, 512), (4096, 4096, 128), (3000, 1100, 200), (1024, 3072, 512)])
 def test_gemm_auto_choice(M, N, K):
+    """Shapes whose lowest time estimate is the weight-stationary kernel's: long and narrow ones, and wide ones
+    with a short K (every 64-column block then has its own workgroups, up to several rounds of them)."""
     assert ops.ac_gemm_i8_auto_plan(M, N, K, True) == (320, 1)
     A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + N + K)
     C = torch.full((M, N), 77, dtype=torch.int8, device="cuda")

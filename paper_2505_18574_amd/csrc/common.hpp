@@ -109,6 +109,7 @@ int choose_tile(int32_t M, int32_t N);
 // coefficients are least-squares fits to the measured times of every code on some 300 int8 and 200 bf16 shapes
 // (M, N 256..16384, K 64..8192); on shapes held out of the fit the chosen code is on average 1 % slower than
 // the best one (worst case 24 %), against 10 % (63 %) for thresholds on the tile count alone.
+bool many_tiles(int32_t M, int32_t N, int64_t kbytes);
 int choose_tile_i8(int32_t M, int32_t N, int32_t K, bool allow_weight_stationary);
 int choose_tile_bf16(int32_t M, int32_t N, int32_t K);
 // Explicit plans: false when the tile code is unknown, or splits is outside 1 .. number of K tiles.

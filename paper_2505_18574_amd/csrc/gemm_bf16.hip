@@ -14,7 +14,7 @@ GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K) {
   GemmPlan plan;
   make_plan_bf16(K, 64, 1, &plan);
   if (M < 1 || N < 1) return plan;
-  if ((int64_t)((M + 63) / 64) * ((N + 63) / 64) > 256) {  // more 64 x 64 tiles than the chip holds at once
+  if (many_tiles(M, N, (int64_t)K * 2)) {
     make_plan_bf16(K, choose_tile_bf16(M, N, K), 1, &plan);
     return plan;
   }

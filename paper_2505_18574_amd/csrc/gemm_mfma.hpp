@@ -75,10 +75,16 @@ static __device__ __forceinline__ v4i load16_bytes(const unsigned char* p, int v
   return (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
 }
 
+// Without the 16-byte guarantee a whole chunk at a 4-byte aligned address is still four dword loads rather than
+// sixteen byte loads (a row pitch that is a multiple of 4 but not of 16, say N = 1000, keeps every chunk there).
 template <bool ALIGNED>
 static __device__ __forceinline__ v4i load16(const unsigned char* p, int valid) {
   if (valid <= 0) return (v4i){0, 0, 0, 0};
   if (ALIGNED && valid >= 16) return *(const v4i*)p;
+  if (!ALIGNED && valid >= 16 && (((uintptr_t)p) & 3) == 0) {
+    const int* q = (const int*)p;
+    return (v4i){q[0], q[1], q[2], q[3]};
+  }
   return load16_bytes(p, valid);
 }
 

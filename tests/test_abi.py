@@ -181,6 +181,31 @@ def test_auto_plans_are_host_arithmetic():
             assert -(-M // bm) * -(-N // bn) * splits <= (512 if tile == 64 else 256)
 
 
+def test_workspace_size_matches_the_automatic_plan():
+    """The size ac_gemm_i8_workspace_bytes reports is the one the library's own plan needs (the call checks the
+    caller's workspace against it), over a random sweep of shapes on both sides of every planner boundary."""
+    import random
+    rng = random.Random(7)
+    dims = [1, 7, 49, 64, 65, 196, 256, 300, 784, 1000, 1024, 1100, 1280, 2048, 3136, 4096, 8192, 12544, 50176]
+    ks = [1, 16, 64, 100, 256, 576, 1152, 2304, 4096, 4608, 9216, 16384, 65536, 524288]
+    split_seen = 0
+    for _ in range(400):
+        M, N, K = rng.choice(dims), rng.choice(dims), rng.choice(ks)
+        tile, splits = ops.ac_gemm_i8_auto_plan(M, N, K, True)
+        assert tile in (64, 128, 192, 256, 160, 320) and splits >= 1
+        need = ops.ac_gemm_i8_workspace_bytes(M, N, K)
+        assert need == ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits)
+        assert (need > 0) == (splits > 1)
+        if splits > 1:
+            split_seen += 1
+            assert need == splits * M * N * 4
+        # without a workspace the plan never slices
+        assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[1] == 1
+        t2, s2 = ops.ac_gemm_bf16_auto_plan(M, N, K)
+        assert t2 in (64, 128, 192, 256) and s2 >= 1
+    assert split_seen > 20
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ops, "_lib", None)
     monkeypatch.setattr(ops, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libac_mi355x.so"))

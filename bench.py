@@ -13,7 +13,9 @@ record of the dominant kernel, and the CPU oracle timed on a bounded sample of t
 Per workload: `ms_in_pass` is the latency of a single eager launch inside a pass (device events around it:
 includes the host's launch gap, which dominates the microsecond-sized int8 kernels); `ms_isolated_warm` /
 `ms_isolated_warm_min` are the median / minimum over five timed regions of at least 20 ms of back-to-back
-launches of that workload replayed from a HIP graph.
+launches of that workload on the same buffers replayed from a HIP graph (operands stay in the caches);
+`ms_isolated_cold` / `ms_isolated_cold_min` are the same over launches that rotate through copies of the
+buffers larger in sum than the caches, so every launch fetches its operands from HBM.
 """
 from __future__ import annotations
 
@@ -48,13 +50,24 @@ def dev(a):
 
 
 class Workload:
-    """One configuration: device buffers, a launch closure, op and byte counts."""
+    """One configuration: device buffers, a call that takes them, op and byte counts."""
 
-    def __init__(self, name, kind, dtype, ops_count, bytes_count, launch, kernel):
+    def __init__(self, name, kind, dtype, ops_count, bytes_count, call, buffers, kernel):
         self.name, self.kind, self.dtype = name, kind, dtype
         self.ops, self.bytes = ops_count, bytes_count
-        self.launch = launch
+        self.call = call  # call(*buffers) launches the workload on that set of device buffers (None entries stay None)
+        self.buffers = buffers
         self.kernel = kernel  # kernel family, as it shows up in a rocprofv3 kernel trace
+
+    def launch(self):
+        self.call(*self.buffers)
+
+    def buffer_copies(self, count):
+        """`count` further sets of the same buffers, each in memory of its own."""
+        return [[None if t is None else t.clone() for t in self.buffers] for _ in range(count)]
+
+    def buffer_bytes(self):
+        return sum(t.numel() * t.element_size() for t in self.buffers if t is not None)
 
 
 def make_workloads():
@@ -65,29 +78,29 @@ def make_workloads():
         nbytes = ops.ac_gemm_i8_workspace_bytes(case.M, case.N, case.K)
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
         wl.append(Workload(case.name, "gemm_i8", "i8", case.ops, case.bytes,
-                           lambda A=A, B=B, bias=bias, C=C, c=case, ws=ws: ops.ac_gemm_i8(A, B, bias, C, c.shift, c.act, workspace=ws),
-                           "gemm_dtl_kernel<TypeI8,...,AMODE=0>"))
+                           lambda A, B, bias, C, ws, c=case: ops.ac_gemm_i8(A, B, bias, C, c.shift, c.act, workspace=ws),
+                           [A, B, bias, C, ws], "gemm_dtl_kernel<TypeI8,...,AMODE=0>"))
     for case in inputs.CONV_I8:
         x, w, bias = (dev(t) for t in inputs.conv_i8_case_inputs(case))
         out = torch.empty((case.Nb, case.OH, case.OW, case.Cout), dtype=torch.int8, device="cuda")
         nbytes = ops.ac_gemm_i8_workspace_bytes(*case.gemm_mnk)
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
         wl.append(Workload(case.name, "conv2d_i8", "i8", case.ops, case.bytes,
-                           lambda x=x, w=w, bias=bias, out=out, c=case, ws=ws: ops.ac_conv2d_i8(x, w, bias, out, c.stride, c.pad, c.shift, c.act, workspace=ws),
-                           "gemm_dtl_kernel<TypeI8,...,AMODE=1>"))
+                           lambda x, w, bias, out, ws, c=case: ops.ac_conv2d_i8(x, w, bias, out, c.stride, c.pad, c.shift, c.act, workspace=ws),
+                           [x, w, bias, out, ws], "gemm_dtl_kernel<TypeI8,...,AMODE=1>"))
     for case in inputs.GEMM_BF16:
         A, B = (dev(t) for t in inputs.gemm_bf16_case_inputs(case))
         C = torch.empty((case.M, case.N), dtype=torch.float32, device="cuda")
         wl.append(Workload(case.name, "gemm_bf16", "bf16", case.ops, case.bytes,
-                           lambda A=A, B=B, C=C: ops.ac_gemm_bf16(A, B, C, 1.0, 0.0),
-                           "gemm_dtl_kernel<TypeBF16,EpilogueF32,256,256,2,4,0,4,64,true>"))
+                           lambda A, B, C: ops.ac_gemm_bf16(A, B, C, 1.0, 0.0),
+                           [A, B, C], "gemm_dtl_kernel<TypeBF16,EpilogueF32,256,256,2,4,0,4,64,true>"))
     case = inputs.BATCHED_F32
     A, B, x, d = (dev(t) for t in inputs.batched_f32_case_inputs(case))
     C = torch.empty((case.batch, case.n, case.n), dtype=torch.float32, device="cuda")
     y = torch.empty((case.batch, case.n), dtype=torch.float32, device="cuda")
     wl.append(Workload(case.name, "batched_f32", "f32", case.ops, case.bytes,
-                       lambda A=A, B=B, C=C, x=x, d=d, y=y: ops.ac_batched_gemm_f32(A, B, C, x, d, y),
-                       "batched12_stream_kernel"))
+                       lambda A, B, C, x, d, y: ops.ac_batched_gemm_f32(A, B, C, x, d, y),
+                       [A, B, C, x, d, y], "batched12_stream_kernel"))
     return wl
 
 
@@ -158,6 +171,39 @@ def isolated_stats(w, stream, reps=20, rounds=5):
             stream.synchronize()
             ts.append(e0.elapsed_time(e1) / (reps * replays))
     return float(np.median(ts)), float(np.min(ts))
+
+
+COLD_BYTES = 640 << 20  # the buffer sets a cold measurement rotates through hold at least this much (the Infinity Cache holds 256 MB)
+
+
+def isolated_cold_stats(w, stream, rounds=5):
+    """One workload with its operands cold: the launches rotate through at least three sets of buffers, together
+    at least COLD_BYTES, so that a set has left every cache before its turn comes again.  One HIP graph holds one
+    launch per set; it is replayed once untimed, then `rounds` regions of at least MIN_REGION_MS are timed as in
+    isolated_stats.  Returns (median, min) ms per launch and the number of sets."""
+    sets = min(4096, max(3, -(-COLD_BYTES // max(1, w.buffer_bytes()))))
+    copies = [w.buffers] + w.buffer_copies(sets - 1)
+    with torch.cuda.stream(stream):
+        stream.synchronize()
+        g = capture(lambda: [w.call(*bufs) for bufs in copies], stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g.replay()
+        e0.record(stream)
+        g.replay()
+        e1.record(stream)
+        stream.synchronize()
+        replays = max(1, int(np.ceil(MIN_REGION_MS / max(e0.elapsed_time(e1), 1e-3))))
+        ts = []
+        for _ in range(rounds):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(replays):
+                g.replay()
+            e1.record(stream)
+            stream.synchronize()
+            ts.append(e0.elapsed_time(e1) / (sets * replays))
+    del g, copies
+    return float(np.median(ts)), float(np.min(ts)), sets
 
 
 def isolated_time(w, stream, reps=20, rounds=5):
@@ -232,7 +278,7 @@ def supplementary(stream, only=None):
             B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda", generator=g)
             bias = torch.randint(-(1 << 15), 1 << 15, (N,), dtype=torch.int32, device="cuda", generator=g)
             C = torch.empty((M, N), dtype=torch.int8, device="cuda")
-            w = Workload("supplementary_gemm_i8_8192", "gemm_i8", "i8", 2 * M * N * K, 0, lambda: ops.ac_gemm_i8(A, B, bias, C, 12, 1), "")
+            w = Workload("supplementary_gemm_i8_8192", "gemm_i8", "i8", 2 * M * N * K, 0, lambda: ops.ac_gemm_i8(A, B, bias, C, 12, 1), [], "")
             ms = isolated_time(w, stream, reps=5, rounds=3)
             out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"]})
             del A, B, C
@@ -247,7 +293,7 @@ def supplementary(stream, only=None):
             o = torch.empty((Nb, case.OH, case.OW, case.Cout), dtype=torch.int8, device="cuda")
             opsn = case.ops * Nb // case.Nb
             ww = Workload(name, "conv2d_i8", "i8", opsn, 0,
-                          lambda x=x, wt=wt, bs=bs, o=o, c=case: ops.ac_conv2d_i8(x, wt, bs, o, c.stride, c.pad, c.shift, c.act), "")
+                          lambda x=x, wt=wt, bs=bs, o=o, c=case: ops.ac_conv2d_i8(x, wt, bs, o, c.stride, c.pad, c.shift, c.act), [], "")
             ms = isolated_time(ww, stream, reps=5, rounds=3)
             out.append({"name": ww.name, "ms": ms, "tops": opsn / ms / 1e9, "frac_mfma_peak": opsn / ms / 1e9 / PEAK["i8"]})
             del x, wt, bs, o
@@ -263,7 +309,7 @@ def supplementary(stream, only=None):
             nbytes = 4 * batch * (nx + 2 * hz * nu + (hz + 1) * nx)  # x0, d read; u, x written
             flops = batch * hz * (2 * nu * nx + nu + 2 * nx * nx + 2 * nx * nu)
             ww = Workload(name, "tinympc_forward_f32", "f32", flops, nbytes,
-                          lambda: ops.ac_tinympc_forward_f32(Ad, Bd, Ki, x0, dd, uo, xo), "")
+                          lambda: ops.ac_tinympc_forward_f32(Ad, Bd, Ki, x0, dd, uo, xo), [], "")
             ms = isolated_time(ww, stream, reps=5, rounds=3)
             out.append({"name": name, "ms": ms, "gbs": nbytes / ms / 1e6, "frac_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS,
                         "gflops": flops / ms / 1e6})
@@ -284,7 +330,7 @@ def supplementary_paper_shapes(stream, only):
             bias = torch.randint(-(1 << 15), 1 << 15, (case.N,), dtype=torch.int32, device="cuda", generator=g)
             C = torch.empty((case.M, case.N), dtype=torch.int8, device="cuda")
             w = Workload("paper_shape_" + case.name, "gemm_i8", "i8", case.ops, case.bytes,
-                         lambda A=A, B=B, bias=bias, C=C, c=case: ops.ac_gemm_i8(A, B, bias, C, c.shift, c.act), "")
+                         lambda A=A, B=B, bias=bias, C=C, c=case: ops.ac_gemm_i8(A, B, bias, C, c.shift, c.act), [], "")
             ms = isolated_time(w, stream, reps=20, rounds=3)
             out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"],
                         "plan": list(ops.ac_gemm_i8_auto_plan(case.M, case.N, case.K, False))})
@@ -295,7 +341,7 @@ def supplementary_paper_shapes(stream, only):
             B = torch.randn((case.K, case.N), device="cuda", generator=g).to(torch.bfloat16)
             C = torch.empty((case.M, case.N), dtype=torch.float32, device="cuda")
             w = Workload("paper_shape_" + case.name, "gemm_bf16", "bf16", case.ops, case.bytes,
-                         lambda A=A, B=B, C=C: ops.ac_gemm_bf16(A, B, C), "")
+                         lambda A=A, B=B, C=C: ops.ac_gemm_bf16(A, B, C), [], "")
             ms = isolated_time(w, stream, reps=5, rounds=3)
             line = {"name": w.name, "ms": ms, "tflops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["bf16"],
                     "gbs": w.bytes / ms / 1e6, "plan": list(ops.ac_gemm_bf16_auto_plan(case.M, case.N, case.K))}
@@ -369,6 +415,7 @@ def main():
     per = []
     for w, ms in zip(wl, kt):
         iso, iso_min = (None, None) if args.no_isolated else isolated_stats(w, stream)
+        cold, cold_min, cold_sets = (None, None, None) if args.no_isolated else isolated_cold_stats(w, stream)
         rate = w.ops / ms / 1e9
         peak = PEAK[w.dtype]
         t_mfma_us = w.ops / (peak * 1e12) * 1e6
@@ -378,7 +425,10 @@ def main():
             "ms_in_pass": round(float(ms), 5),
             "ms_isolated_warm": None if iso is None else round(iso, 5),
             "ms_isolated_warm_min": None if iso is None else round(iso_min, 5),
+            "ms_isolated_cold": None if cold is None else round(cold, 5),
+            "ms_isolated_cold_min": None if cold is None else round(cold_min, 5), "cold_buffer_sets": cold_sets,
             "tops_in_pass": round(rate, 2), "tops_isolated_warm": None if iso is None else round(w.ops / iso / 1e9, 2),
+            "tops_isolated_cold": None if cold is None else round(w.ops / cold / 1e9, 2),
             "frac_mfma_peak": round(rate / peak, 4) if w.dtype != "f32" else None,
             "gbs_in_pass": round(w.bytes / ms / 1e6, 1), "frac_hbm_peak": round(w.bytes / ms / 1e6 / HBM_PEAK_GBS, 4),
             "attainable_us": round(max(t_mfma_us, t_hbm_us), 3),

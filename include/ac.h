@@ -221,7 +221,8 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           per tile for tile 256, 128 bytes otherwise), each slice a workgroup of its own.  Needs operands
  *           that qualify for the direct-to-LDS kernels: base pointers and row pitches of A and B multiples of
  *           16 bytes, K and N multiples of 16 (int8) or 8 (bf16) elements, C 4-byte (int8) or 16-byte (bf16)
- *           aligned with ldc a multiple of 4.
+ *           aligned with ldc a multiple of 4, and row pitches below 13 MB (A) and 33 MB (B): a tile's rows are
+ *           addressed with 32-bit byte offsets from the tile's first row.
  *           int8: slices leave int32 partial sums in `workspace`, which must hold
  *           ac_gemm_i8_planned_workspace_bytes() bytes; a second kernel sums them and applies the output stage.
  *           bf16, with a workspace of ac_gemm_bf16_planned_workspace_bytes() bytes: slices leave fp32 partial

@@ -139,6 +139,13 @@ hipError_t launch_gemm_i8(const GemmParams& p, hipStream_t stream, const GemmPla
 hipError_t launch_gemm_i8_acc32(const GemmParams& p, hipStream_t stream);
 hipError_t launch_gemm_i8_trans(const GemmParams& p, bool trans_a, bool trans_b, hipStream_t stream);
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
+// The direct-to-LDS loaders address a lane's 16-byte chunk as a wave-uniform 64-bit base plus a 32-bit byte offset
+// that spans up to 320 rows of A or 128 rows of B.  Row pitches beyond these limits (rows of 13 MB and more) take the
+// generic kernels, whose lanes carry 64-bit addresses.
+inline bool lane_offsets_fit(int64_t a_pitch_bytes, int64_t b_pitch_bytes) {
+  const int64_t span = (1ll << 32) - 65536;
+  return a_pitch_bytes * 320 < span && b_pitch_bytes * 128 < span;
+}
 // True when the weight-stationary kernel behind `tile` (320 / 160) can run p: bias absent or a row, K resident.
 bool wstat_eligible(const GemmParams& p, int tile);
 // True when the convolution patch kernel behind `tile` (321 / 161) can run the convolution described by p.

@@ -61,7 +61,8 @@ __global__ void __launch_bounds__(256) splitk_reduce_f32_kernel(const GemmParams
 
 bool gemm_bf16_fast_path(const GemmParams& p) {
   return (((uintptr_t)p.A & 15) == 0) && (((uintptr_t)p.B & 15) == 0) && (p.lda % 8 == 0) && (p.ldb % 8 == 0) &&
-         (((uintptr_t)p.C & 15) == 0) && (p.ldc % 4 == 0) && (p.K % 8 == 0) && (p.N % 8 == 0);
+         (((uintptr_t)p.C & 15) == 0) && (p.ldc % 4 == 0) && (p.K % 8 == 0) && (p.N % 8 == 0) &&
+         lane_offsets_fit(2 * (int64_t)p.lda, 2 * (int64_t)p.ldb);
 }
 
 hipError_t launch_gemm_bf16(const GemmParams& p0, hipStream_t stream, const GemmPlan* forced) {

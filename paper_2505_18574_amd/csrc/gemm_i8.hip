@@ -282,7 +282,7 @@ static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 // Fast (direct-to-LDS) path: 16-byte aligned operands and pitches, K and N in whole 16-byte chunks.
 bool gemm_i8_fast_path(const GemmParams& p) {
   return aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) && (((uintptr_t)p.C & 3) == 0) &&
-         (p.ldc % 4 == 0) && (p.K % 16 == 0) && (p.N % 16 == 0);
+         (p.ldc % 4 == 0) && (p.K % 16 == 0) && (p.N % 16 == 0) && lane_offsets_fit(p.lda, p.ldb);
 }
 
 // Raw int32 accumulator output: same kernels, epilogue without the output stage (no split-K).
@@ -291,7 +291,7 @@ hipError_t launch_gemm_i8_acc32(const GemmParams& p0, hipStream_t stream) {
   p.splits = 1;
   p.kt_per_split = 0;
   const bool aligned = aligned16(p.A) && aligned16(p.B) && (p.lda % 16 == 0) && (p.ldb % 16 == 0) && aligned16(p.C) && (p.ldc % 4 == 0);
-  const bool fast = aligned && (p.K % 16 == 0) && (p.N % 16 == 0);
+  const bool fast = aligned && (p.K % 16 == 0) && (p.N % 16 == 0) && lane_offsets_fit(p.lda, p.ldb);
   if (fast) return launch_dtl_tile<TypeI8, EpilogueRawI32, 0>(choose_tile(p.M, p.N), p, stream);  // 4-byte output: its own regime, thresholds kept
   return aligned ? launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, true>(p, stream)
                  : launch_tile<TypeI8, EpilogueRawI32, 64, 64, 2, 2, 0, false>(p, stream);
@@ -311,7 +311,7 @@ bool conv_i8_fast_path(const GemmParams& p) {
                        (((uintptr_t)p.C & 3) == 0) && (p.ldc % 4 == 0);
   const int64_t lim = 1ll << 32;
   return aligned && p.KH >= 1 && p.KH * p.KW <= 32 && (int64_t)p.K * p.Cin < lim && (int64_t)p.M * p.OW < lim &&
-         ((int64_t)p.M / (p.OW > 0 ? p.OW : 1) + 1) * p.OH < lim && p.a_bytes > 0;
+         ((int64_t)p.M / (p.OW > 0 ? p.OW : 1) + 1) * p.OH < lim && p.a_bytes > 0 && lane_offsets_fit(0, p.ldb);
 }
 
 hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmPlan* forced) {

@@ -77,6 +77,11 @@ def test_planned_entry_validation_without_gpu():
     assert ops.ac_gemm_i8_planned_workspace_bytes(64, 64, 4096, 7, 4) == 0
     # a split over operands that cannot take the direct-to-LDS kernels (K not a multiple of 16)
     assert L.ac_gemm_i8_planned(p, 1000, p + 256, 64, None, 0, p + 512, 64, 64, 64, 1000, 0, 0, p + 4096, 1 << 20, 64, 2, None) == ops.AC_ERR_PLAN
+    # ... or whose rows lie so far apart that a tile's rows span more than 32 bits of byte offset
+    need = ops.ac_gemm_i8_planned_workspace_bytes(64, 64, 4096, 64, 2)
+    assert L.ac_gemm_i8_planned(p, 1 << 24, p + 256, 64, None, 0, p + 512, 64, 64, 64, 4096, 0, 0, p + 4096, need, 64, 2, None) == ops.AC_ERR_PLAN
+    assert L.ac_gemm_i8_planned(p, 4096, p + 256, 1 << 26, None, 0, p + 512, 64, 64, 64, 4096, 0, 0, p + 4096, need, 64, 2, None) == ops.AC_ERR_PLAN
+    assert L.ac_gemm_bf16_planned(p, 1 << 23, p + 256, 64, p + 512, 64, 64, 64, 4096, 1.0, 0.0, None, 0, 64, 2, None) == ops.AC_ERR_PLAN
     bf = lambda tile, splits, K=4096, ws=None, wsb=0: L.ac_gemm_bf16_planned(
         p, K, p + 256, 64, p + 512, 64, 64, 64, K, 1.0, 0.0, ws, wsb, tile, splits, None)
     assert bf(32, 1) == ops.AC_ERR_PLAN

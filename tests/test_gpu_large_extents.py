@@ -99,3 +99,50 @@ def test_bf16_row_pitch_beyond_32_bit_lane_offsets():
     ops.ac_gemm_bf16(Ad, dev(B), C, 1.0, 0.0)
     torch.cuda.synchronize()
     assert rel_fro(host(C), want) <= 1e-3
+
+
+def sample_items(batch, item_bytes, seed):
+    items = {0, 1, 2, 3, batch - 5, batch - 4, batch - 3, batch - 2, batch - 1}
+    for mark in (1 << 31, 1 << 32):
+        b = mark // item_bytes
+        items.update(x for x in range(b - 2, b + 3) if 0 <= x < batch)
+    items.update(int(x) for x in np.random.default_rng(seed).integers(0, batch, 200))
+    return np.array(sorted(items), dtype=np.int64)
+
+
+def test_batched_f32_arrays_beyond_4_gib():
+    """8 million items of 12 x 12 (A, B and C are 4.6 GB each; a ragged last group), inputs drawn on the device
+    from a seeded generator; sampled items against the oracle."""
+    batch, n = 8_000_003, 12
+    g = torch.Generator(device="cuda").manual_seed(9105)
+    u01 = lambda *shape: torch.rand(shape, device="cuda", generator=g) * 2.0 - 1.0
+    A, B, x, d = u01(batch, n, n), u01(batch, n, n), u01(batch, n), u01(batch, n)
+    C = torch.full((batch, n, n), float("nan"), dtype=torch.float32, device="cuda")
+    y = torch.full((batch, n), float("nan"), dtype=torch.float32, device="cuda")
+    ops.ac_batched_gemm_f32(A, B, C, x, d, y)
+    torch.cuda.synchronize()
+    idx = sample_items(batch, 4 * n * n, 4)
+    assert idx.max() * 4 * n * n >= 1 << 32
+    t = torch.from_numpy(idx).cuda()
+    Cw, yw = oracle.batched_gemm_f32(host(A[t]), host(B[t]), host(x[t]), host(d[t]))
+    assert rel_fro(host(C[t]), Cw) <= 1e-5 and rel_fro(host(y[t]), yw) <= 1e-5
+    assert bool(torch.isfinite(y).all())  # every item was written
+
+
+def test_tinympc_forward_arrays_beyond_4_gib():
+    """15 million problems: the state trajectories are 4.3 GB; sampled problems against the oracle."""
+    batch, nx, nu, hz = 15_000_001, 12, 4, 5
+    g = torch.Generator(device="cuda").manual_seed(9106)
+    u01 = lambda *shape: torch.rand(shape, device="cuda", generator=g) * 2.0 - 1.0
+    Ad, Bd, Ki = u01(nx, nx) * 0.3, u01(nx, nu), u01(nu, nx) * 0.3
+    x0, dd = u01(batch, nx), u01(batch, hz, nu)
+    u = torch.full((batch, hz, nu), float("nan"), dtype=torch.float32, device="cuda")
+    xs = torch.full((batch, hz + 1, nx), float("nan"), dtype=torch.float32, device="cuda")
+    ops.ac_tinympc_forward_f32(Ad, Bd, Ki, x0, dd, u, xs)
+    torch.cuda.synchronize()
+    idx = sample_items(batch, 4 * (hz + 1) * nx, 5)
+    assert idx.max() * 4 * (hz + 1) * nx >= 1 << 32
+    t = torch.from_numpy(idx).cuda()
+    uw, xw = oracle.tinympc_forward(host(Ad), host(Bd), host(Ki), host(x0[t]), host(dd[t]), return_x=True)
+    assert rel_fro(host(u[t]), uw) <= 1e-5 and rel_fro(host(xs[t]), xw) <= 1e-5
+    assert bool(torch.isfinite(u).all())

@@ -161,6 +161,23 @@ ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_
                        float alpha, float beta, void* stream);
 
 /*
+ * ac_gemm_bf16 with an optional device workspace (same operands and result).  Where ac_gemm_bf16 cuts K, its
+ * slices add into C with atomic adds in no fixed order; with a workspace of at least
+ * ac_gemm_bf16_workspace_bytes(M, N, K) bytes (16-byte aligned) the slices leave fp32 partial products there and
+ * a second kernel sums them in slice order, so the result is the same on every run.  The workspace rules are
+ * those of ac_gemm_i8: contents unspecified on entry and exit, not shared by concurrent calls, NULL / 0 always
+ * accepted (then the call is ac_gemm_bf16), too small or misaligned gives AC_ERR_WORKSPACE.  Operands that do
+ * not qualify for the direct-to-LDS kernels (see the planned launches) are not cut and leave the workspace unused.
+ */
+ac_status ac_gemm_bf16_ws(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
+                          float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                          float alpha, float beta, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace with which ac_gemm_bf16_ws sums its K slices in a fixed order for this shape (0 when the
+ * shape is not cut).  Pure host arithmetic. */
+size_t ac_gemm_bf16_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+/*
  * Batched small fp32 linear algebra (the fine-grained workload of Section
  * 5.1.3: small dense products chained with matrix-vector products and
  * element-wise adds), for each item b independently:

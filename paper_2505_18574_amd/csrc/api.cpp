@@ -51,6 +51,14 @@ size_t ac_gemm_i8_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32
   return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t);
 }
 
+size_t ac_gemm_bf16_workspace_bytes(int32_t M, int32_t N, int32_t K) {
+  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  const ac::GemmPlan plan = ac::plan_gemm_bf16(M, N, K);
+  if (plan.splits <= 1) return 0;
+  // fp32 partial products of every K slice
+  return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float);
+}
+
 size_t ac_gemm_bf16_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits) {
   ac::GemmPlan plan;
   if (M <= 0 || N <= 0 || K <= 0 || !ac::make_plan_bf16(K, tile, splits, &plan) || plan.splits <= 1) return 0;
@@ -115,9 +123,8 @@ ac_status gemm_bf16_entry(const uint16_t* A, int64_t lda, const uint16_t* B, int
   ac::GemmPlan plan;
   if (planned && !ac::make_plan_bf16(K, tile, splits, &plan)) return AC_ERR_PLAN;
   if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;
-  if (workspace && (((uintptr_t)workspace & 15) != 0 ||
-                    workspace_bytes < ac_gemm_bf16_planned_workspace_bytes(M, N, K, tile, splits)))
-    return AC_ERR_WORKSPACE;
+  const size_t need = planned ? ac_gemm_bf16_planned_workspace_bytes(M, N, K, tile, splits) : ac_gemm_bf16_workspace_bytes(M, N, K);
+  if (workspace && (((uintptr_t)workspace & 15) != 0 || workspace_bytes < need)) return AC_ERR_WORKSPACE;
   if (M == 0 || N == 0) return AC_OK;
   if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
   if ((const void*)C == (const void*)A || (const void*)C == (const void*)B) return AC_ERR_ALIAS;
@@ -255,6 +262,12 @@ ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_
                        float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
                        float alpha, float beta, void* stream) {
   return gemm_bf16_entry(A, lda, B, ldb, C, ldc, M, N, K, alpha, beta, nullptr, 0, false, 0, 0, stream);
+}
+
+ac_status ac_gemm_bf16_ws(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
+                          float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                          float alpha, float beta, void* workspace, size_t workspace_bytes, void* stream) {
+  return gemm_bf16_entry(A, lda, B, ldb, C, ldc, M, N, K, alpha, beta, workspace, workspace_bytes, false, 0, 0, stream);
 }
 
 ac_status ac_gemm_bf16_planned(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,

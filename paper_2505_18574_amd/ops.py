@@ -26,7 +26,7 @@ AC_ACT_NONE, AC_ACT_RELU = 0, 1
 EXPORTS = ("ac_gemm_i8", "ac_gemm_i8_workspace_bytes", "ac_conv2d_i8", "ac_gemm_bf16", "ac_batched_gemm_f32",
            "ac_tinympc_forward_f32", "ac_gemm_i8_acc32",
            "ac_gemm_i8_t", "ac_gemm_i8_planned", "ac_conv2d_i8_planned", "ac_gemm_i8_planned_workspace_bytes", "ac_gemm_bf16_planned",
-           "ac_gemm_bf16_planned_workspace_bytes",
+           "ac_gemm_bf16_planned_workspace_bytes", "ac_gemm_bf16_ws", "ac_gemm_bf16_workspace_bytes",
            "ac_gemm_i8_auto_plan", "ac_gemm_bf16_auto_plan",
            "ac_status_string", "ac_version")
 
@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.ac_gemm_i8_planned.argtypes = L.ac_gemm_i8.argtypes[:-1] + [i32, i32, vp]
         L.ac_gemm_i8_planned_workspace_bytes.restype = sz
         L.ac_gemm_i8_planned_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.ac_gemm_bf16_ws.restype = i32
+        L.ac_gemm_bf16_ws.argtypes = L.ac_gemm_bf16.argtypes[:-1] + [vp, sz, vp]
+        L.ac_gemm_bf16_workspace_bytes.restype = sz
+        L.ac_gemm_bf16_workspace_bytes.argtypes = [i32, i32, i32]
         L.ac_gemm_bf16_planned.restype = i32
         L.ac_gemm_bf16_planned.argtypes = L.ac_gemm_bf16.argtypes[:-1] + [vp, sz, i32, i32, vp]
         L.ac_gemm_bf16_planned_workspace_bytes.restype = sz
@@ -105,6 +109,10 @@ def ac_gemm_i8_workspace_bytes(M: int, N: int, K: int) -> int:
 
 def ac_gemm_i8_planned_workspace_bytes(M: int, N: int, K: int, tile: int, splits: int) -> int:
     return int(lib().ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits))
+
+
+def ac_gemm_bf16_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().ac_gemm_bf16_workspace_bytes(M, N, K))
 
 
 def ac_gemm_bf16_planned_workspace_bytes(M: int, N: int, K: int, tile: int, splits: int) -> int:
@@ -261,6 +269,15 @@ def ac_gemm_bf16(A, B, C, alpha: float = 1.0, beta: float = 0.0, stream=None):
     st = lib().ac_gemm_bf16(*_gemm_bf16_args(A, B, C), float(alpha), float(beta), _stream(stream))
     if st != AC_OK:
         raise AcError(st, "ac_gemm_bf16")
+    return C
+
+
+def ac_gemm_bf16_ws(A, B, C, alpha: float = 1.0, beta: float = 0.0, workspace=None, stream=None):
+    """ac_gemm_bf16 that sums the slices of a cut K range through `workspace` (in a fixed order) when one is given.  Returns C."""
+    wp, wb = _ws(workspace)
+    st = lib().ac_gemm_bf16_ws(*_gemm_bf16_args(A, B, C), float(alpha), float(beta), wp, wb, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_gemm_bf16_ws")
     return C
 
 

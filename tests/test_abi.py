@@ -193,7 +193,7 @@ def test_workspace_size_matches_the_automatic_plan():
     rng = random.Random(7)
     dims = [1, 7, 49, 64, 65, 196, 256, 300, 784, 1000, 1024, 1100, 1280, 2048, 3136, 4096, 8192, 12544, 50176]
     ks = [1, 16, 64, 100, 256, 576, 1152, 2304, 4096, 4608, 9216, 16384, 65536, 524288]
-    split_seen = 0
+    split_seen = bf16_split_seen = 0
     for _ in range(400):
         M, N, K = rng.choice(dims), rng.choice(dims), rng.choice(ks)
         tile, splits = ops.ac_gemm_i8_auto_plan(M, N, K, True)
@@ -208,7 +208,29 @@ def test_workspace_size_matches_the_automatic_plan():
         assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[1] == 1
         t2, s2 = ops.ac_gemm_bf16_auto_plan(M, N, K)
         assert t2 in (64, 128, 192, 256) and s2 >= 1
-    assert split_seen > 20
+        need2 = ops.ac_gemm_bf16_workspace_bytes(M, N, K)
+        assert need2 == ops.ac_gemm_bf16_planned_workspace_bytes(M, N, K, t2, s2)
+        assert need2 == (s2 * M * N * 4 if s2 > 1 else 0)
+        bf16_split_seen += s2 > 1
+    assert split_seen > 20 and bf16_split_seen > 20
+    assert ops.ac_gemm_bf16_workspace_bytes(0, 8, 8) == 0 and ops.ac_gemm_bf16_workspace_bytes(8, 8, -1) == 0
+
+
+def test_bf16_workspace_validation_without_gpu():
+    """The workspace of ac_gemm_bf16_ws is checked on the host like the one of ac_gemm_i8."""
+    L = ops.lib()
+    p = 0x1000  # never dereferenced
+    M, N, K = 64, 64, 65536
+    need = ops.ac_gemm_bf16_workspace_bytes(M, N, K)
+    assert need > 0
+    call = lambda ws, wsb: L.ac_gemm_bf16_ws(p, K, p + 256, N, p + 512, N, M, N, K, 1.0, 0.0, ws, wsb, None)
+    assert call(p + 4096, need - 4) == ops.AC_ERR_WORKSPACE    # too small
+    assert call(p + 4100, need) == ops.AC_ERR_WORKSPACE        # misaligned
+    assert call(None, 64) == ops.AC_ERR_WORKSPACE              # a size without a pointer
+    assert call(p + 4096, 0) == ops.AC_ERR_WORKSPACE           # a pointer without a size
+    assert L.ac_gemm_bf16_ws(p, K, p + 256, N, p + 512, N, M, N, -1, 1.0, 0.0, None, 0, None) == ops.AC_ERR_SHAPE
+    assert L.ac_gemm_bf16_ws(p, K - 8, p + 256, N, p + 512, N, M, N, K, 1.0, 0.0, None, 0, None) == ops.AC_ERR_STRIDE
+    assert L.ac_gemm_bf16_ws(None, K, p + 256, N, p + 512, N, 0, N, K, 1.0, 0.0, None, 0, None) == ops.AC_OK  # nothing to do
 
 
 def test_missing_library_fails_loudly(monkeypatch):

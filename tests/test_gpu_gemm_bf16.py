@@ -66,6 +66,58 @@ def test_few_tiles_deep_k_auto_plan(M, N, K, plan):
     check_full(A, B, 0.5, -1.5, C_in)
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 256, 65536), (200, 120, 40000), (64, 64, 100000), (1024, 256, 8192)])
+def test_workspace_call_sums_slices_in_a_fixed_order(M, N, K):
+    """ac_gemm_bf16_ws with the workspace it asks for: the oracle's result within the bound, the same bits on
+    every run, and the same bits as the planned call on the library's own plan."""
+    tile, splits = ops.ac_gemm_bf16_auto_plan(M, N, K)
+    need = ops.ac_gemm_bf16_workspace_bytes(M, N, K)
+    assert splits > 1 and need == splits * M * N * 4
+    A, B = inputs.gemm_bf16_inputs(M, N, K, seed=M + N + K + 1)
+    C_in = np.random.default_rng(K).standard_normal((M, N)).astype(np.float32)
+    want = oracle.gemm_bf16(A, B, 0.5, -1.5, C_in)
+    Ad, Bd = dev(A), dev(B)
+    ws = torch.full((need + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    runs = []
+    for _ in range(3):
+        C = dev(C_in).clone()
+        ops.ac_gemm_bf16_ws(Ad, Bd, C, 0.5, -1.5, workspace=ws[:need])
+        torch.cuda.synchronize()
+        runs.append(host(C))
+    assert rel_fro(runs[0], want) <= 1e-3
+    np.testing.assert_array_equal(runs[1], runs[0])
+    np.testing.assert_array_equal(runs[2], runs[0])
+    assert bool((ws[need:] == 0xA5).all())  # nothing written beyond the reported size
+    C = dev(C_in).clone()
+    ops.ac_gemm_bf16_planned(Ad, Bd, C, 0.5, -1.5, tile, splits, workspace=ws[:need])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C), runs[0])
+    # without a workspace the call is ac_gemm_bf16 (atomic adds): same result up to the summation order
+    C = dev(C_in).clone()
+    ops.ac_gemm_bf16_ws(Ad, Bd, C, 0.5, -1.5)
+    torch.cuda.synchronize()
+    assert rel_fro(host(C), want) <= 1e-3
+
+
+def test_workspace_call_on_shapes_that_are_not_cut():
+    """A shape with many tiles, and operands the direct-to-LDS kernels do not take: the workspace stays unused and
+    the result is ac_gemm_bf16's, bit for bit."""
+    for M, N, K, cut in [(512, 512, 256, False), (130, 124, 40004, True)]:
+        A, B = inputs.gemm_bf16_inputs(M, N, K, seed=M + K)
+        Ad, Bd = dev(A), dev(B)
+        need = ops.ac_gemm_bf16_workspace_bytes(M, N, K)
+        assert (need > 0) == cut
+        ws = torch.full((max(need, 1024),), 0x5A, dtype=torch.uint8, device="cuda")
+        C1 = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        C2 = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        ops.ac_gemm_bf16_ws(Ad, Bd, C1, 1.0, 0.0, workspace=ws)
+        ops.ac_gemm_bf16(Ad, Bd, C2, 1.0, 0.0)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(C1), host(C2))
+        assert bool((ws == 0x5A).all())
+        assert rel_fro(host(C1), oracle.gemm_bf16(A, B)) <= 1e-3
+
+
 def test_alpha_beta():
     A, B = inputs.gemm_bf16_inputs(200, 264, 136, seed=1)
     Cin = np.random.default_rng(2).standard_normal((200, 264)).astype(np.float32)

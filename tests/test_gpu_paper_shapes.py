@@ -52,3 +52,14 @@ def test_bf16_paper_shapes_sampled(case):
     Ad = inputs.bf16_bits_to_f32(A).astype(np.float64)
     Bd = inputs.bf16_bits_to_f32(B).astype(np.float64)
     assert rel_fro(colsum, Ad.sum(axis=0) @ Bd) <= 1e-4
+    # the form the benchmark times: a cut K range summed through a workspace (the uncut shapes run the same kernel)
+    need = ops.ac_gemm_bf16_workspace_bytes(M, N, K)
+    if need:
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        C2 = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        ops.ac_gemm_bf16_ws(dev(A), dev(B), C2, 1.0, 0.0, workspace=ws)
+        torch.cuda.synchronize()
+        g2 = host(C2[torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda()]).astype(np.float64)
+        assert rel_fro(g2, want) <= 1e-3
+        assert (np.abs(g2 - want) <= 4.0 * (K + 2) * 2.0 ** -24 * mag + 1e-30).all()
+        assert rel_fro(host(ones @ C2.double()), Ad.sum(axis=0) @ Bd) <= 1e-4

@@ -83,6 +83,26 @@ def test_beam_keeps_correct_and_faster_candidates_only():
     assert res.best_us <= cost((64, 1))  # the beam never ends worse than its seed
 
 
+def test_finalists_are_measured_again_before_the_best_is_named():
+    """The quick measurement ranks (here: with an error that favours a slower plan); the three best by it are
+    measured again with the longer one, which decides."""
+    true = lambda p: 10.0 + abs(p[0] - 128) / 16.0 + p[1]
+    quick = lambda p: true(p) - (5.0 if p == (64, 1) else 0.0)  # the quick look flatters (64, 1)
+    prob = FakeProblem(quick)
+    prob.confirm = lambda fn: true(prob.launched[-1])
+    res = tune._search(prob, None, [], 1, 0, exhaustive=True)
+    assert quick((64, 1)) < quick((128, 1)) and res.best == (128, 1) and res.best_us == true((128, 1))
+    by_plan = {t.plan: t.us for t in res.trials}
+    assert by_plan[(64, 1)] == true((64, 1))          # a finalist: carries the longer measurement
+    assert by_plan[(256, 1)] == quick((256, 1))       # not a finalist: the quick one
+    # the plan a beam search starts from is measured again even when the quick look ranks it last
+    quick2 = lambda p: true(p) + (100.0 if p == (128, 1) else 0.0)
+    prob = FakeProblem(quick2)
+    prob.confirm = lambda fn: true(prob.launched[-1])
+    res = tune._search(prob, None, [(128, 1)], beam=3, iterations=2, exhaustive=False)
+    assert res.best == (128, 1) and res.best_us == true((128, 1))
+
+
 def test_beam_stops_when_no_child_improves():
     prob = FakeProblem(lambda p: 10.0 + abs(p[0] - 128) + p[1])  # (128, 1) is a strict local and global minimum
     res = tune._search(prob, None, [(128, 1)], beam=3, iterations=5, exhaustive=False)

@@ -81,3 +81,74 @@ def test_conv_random_geometries():
         torch.cuda.synchronize()
         np.testing.assert_array_equal(host(out), oracle.conv2d_i8(x, w, b, stride, pad, 7, idx % 2),
                                       err_msg=f"conv {(Nb, H, W, Cin, Cout, KH, KW, stride, pad)}")
+
+
+ALL_I8_TILES = (64, 128, 192, 256, 160, 320)
+PATCH_TILES = (161, 321)
+
+
+def test_every_plan_on_random_int8_gemms():
+    """Seeded random GEMM shapes the direct-to-LDS kernels take, each through every kernel / tile code and several K
+    splits by name; a plan the library refuses (AC_ERR_PLAN: K too deep for resident weights, more slices than K
+    tiles) drops out, every plan it accepts must reproduce the oracle bit for bit."""
+    rng = np.random.default_rng(606)
+    ran = {t: 0 for t in ALL_I8_TILES}
+    for idx in range(14):
+        M = int(rng.integers(1, 900))
+        N = 16 * int(rng.integers(1, 40))
+        K = 16 * int(rng.integers(1, 120))
+        A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=9200 + idx)
+        shift, act = int(idx % 11), int(idx % 2)
+        want = oracle.gemm_i8(A, B, bias, shift, act)
+        Ad, Bd, bd = dev(A), dev(B), dev(bias)
+        for tile in ALL_I8_TILES:
+            for splits in (1, 2, 5):
+                need = ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits)
+                ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+                C = torch.full((M, N), 91, dtype=torch.int8, device="cuda")
+                try:
+                    ops.ac_gemm_i8_planned(Ad, Bd, bd, C, shift, act, tile, splits, workspace=ws)
+                except ops.AcError as e:
+                    assert e.status == ops.AC_ERR_PLAN, (M, N, K, tile, splits)
+                    continue
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(host(C), want, err_msg=f"shape {(M, N, K)} plan {(tile, splits)}")
+                ran[tile] += 1
+    assert all(n >= 10 for n in ran.values()), ran
+
+
+def test_every_plan_on_random_convolutions():
+    """The same for seeded random convolution geometries (channel counts in multiples of 16), with the patch kernel
+    codes added."""
+    rng = np.random.default_rng(707)
+    ran = {t: 0 for t in ALL_I8_TILES + PATCH_TILES}
+    for idx in range(16):
+        Nb, H, W = int(rng.integers(1, 7)), int(rng.integers(4, 40)), int(rng.integers(4, 40))
+        KH, KW = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride, pad = int(rng.integers(1, 4)), int(rng.integers(0, 3))
+        if KH > H + 2 * pad or KW > W + 2 * pad:
+            continue
+        Cin, Cout = 16 * int(rng.integers(1, 7)), 16 * int(rng.integers(1, 9))
+        if idx % 2 == 0:  # every other geometry is one the patch kernel can hold in LDS: 3 x 3, few channels
+            KH, KW, stride, Cin = 3, 3, 1 + idx // 2 % 2, 16 * int(rng.integers(2, 5))
+        x, w, b = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=9300 + idx)
+        shift, act = 6 + idx % 5, idx % 2
+        want = oracle.conv2d_i8(x, w, b, stride, pad, shift, act)
+        OH, OW = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+        M, K = Nb * OH * OW, KH * KW * Cin
+        xd, wd, bd = dev(x), dev(w), dev(b)
+        for tile in ALL_I8_TILES + PATCH_TILES:
+            for splits in (1, 3):
+                need = ops.ac_gemm_i8_planned_workspace_bytes(M, Cout, K, tile, splits)
+                ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+                out = torch.full((Nb, OH, OW, Cout), 17, dtype=torch.int8, device="cuda")
+                try:
+                    ops.ac_conv2d_i8(xd, wd, bd, out, stride, pad, shift, act, workspace=ws, plan=(tile, splits))
+                except ops.AcError as e:
+                    assert e.status == ops.AC_ERR_PLAN, (Nb, H, W, Cin, Cout, KH, KW, stride, pad, tile, splits)
+                    continue
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(host(out), want,
+                                              err_msg=f"conv {(Nb, H, W, Cin, Cout, KH, KW, stride, pad)} plan {(tile, splits)}")
+                ran[tile] += 1
+    assert all(n >= 5 for n in ran.values()), ran

@@ -152,3 +152,34 @@ def test_every_plan_on_random_convolutions():
                                               err_msg=f"conv {(Nb, H, W, Cin, Cout, KH, KW, stride, pad)} plan {(tile, splits)}")
                 ran[tile] += 1
     assert all(n >= 5 for n in ran.values()), ran
+
+
+def test_every_plan_on_random_bf16_gemms():
+    """Seeded random bf16 shapes (N and K in multiples of 8), each through every tile code and several K splits, the
+    slices summed through a workspace and with atomic adds; every accepted plan within the bf16 bar of the oracle."""
+    rng = np.random.default_rng(808)
+    ran = 0
+    for idx in range(10):
+        M = int(rng.integers(1, 700))
+        N = 8 * int(rng.integers(1, 70))
+        K = 8 * int(rng.integers(1, 260))
+        A, B = inputs.gemm_bf16_inputs(M, N, K, seed=9400 + idx)
+        alpha, beta = (1.0, 0.0) if idx % 2 else (-0.5, 2.0)
+        C_in = np.random.default_rng(idx).standard_normal((M, N)).astype(np.float32)
+        want = oracle.gemm_bf16(A, B, alpha, beta, C_in if beta else None)
+        Ad, Bd = dev(A), dev(B)
+        for tile in (64, 128, 192, 256):
+            for splits in (1, 2, 5):
+                for with_ws in ((False,) if splits == 1 else (False, True)):
+                    need = ops.ac_gemm_bf16_planned_workspace_bytes(M, N, K, tile, splits) if with_ws else 0
+                    ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+                    C = dev(C_in).clone() if beta else torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+                    try:
+                        ops.ac_gemm_bf16_planned(Ad, Bd, C, alpha, beta, tile, splits, workspace=ws)
+                    except ops.AcError as e:
+                        assert e.status == ops.AC_ERR_PLAN, (M, N, K, tile, splits)
+                        continue
+                    torch.cuda.synchronize()
+                    assert rel_fro(host(C), want) <= 1e-3, (M, N, K, tile, splits, with_ws)
+                    ran += 1
+    assert ran >= 150, ran

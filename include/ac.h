@@ -22,6 +22,8 @@
  *    error a negative ac_status is returned and no work is enqueued.
  *    No C++ exception crosses this boundary.
  *  - Zero-sized problems (M, N or batch == 0) return AC_OK without a launch.
+ *  - GEMM sizes (for a convolution: those of its implicit GEMM) are supported up to 2^29 per dimension and
+ *    2^31 - 1 blocks of 64 x 64 outputs; larger ones return AC_ERR_SHAPE.
  */
 #ifndef AC_H_
 #define AC_H_

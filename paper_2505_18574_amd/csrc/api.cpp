@@ -9,6 +9,15 @@ namespace {
 
 bool fits_i32(int64_t v) { return v >= 0 && v <= INT_MAX; }
 
+// Sizes of an (implicit) GEMM the kernels and planners index without overflow: every dimension at most 2^29 (row
+// lengths in bytes and rounded-up tile counts are 32-bit) and at most 2^31 - 1 tiles of 64 x 64 (work counters are
+// 32-bit; such an output would be 8 TB).
+bool gemm_dims_supported(int64_t M, int64_t N, int64_t K) {
+  const int64_t lim = 1ll << 29;
+  if (M < 0 || N < 0 || K < 0 || M > lim || N > lim || K > lim) return false;
+  return ((M + 63) / 64) * ((N + 63) / 64) <= INT_MAX;
+}
+
 ac_status check_stage(int32_t shift, int32_t act) {
   if (shift < 0 || shift > 31) return AC_ERR_SHIFT;
   if (act != AC_ACT_NONE && act != AC_ACT_RELU) return AC_ERR_ACT;
@@ -38,7 +47,7 @@ const char* ac_status_string(ac_status status) {
 int32_t ac_version(void) { return 100; }
 
 size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K) {
-  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  if (M <= 0 || N <= 0 || K <= 0 || !gemm_dims_supported(M, N, K)) return 0;
   const ac::GemmPlan plan = ac::plan_gemm_i8(M, N, K, true);
   if (plan.splits <= 1) return 0;
   // int32 partial sums of every K slice
@@ -47,12 +56,12 @@ size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K) {
 
 size_t ac_gemm_i8_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits) {
   ac::GemmPlan plan;
-  if (M <= 0 || N <= 0 || K <= 0 || !ac::make_plan_i8(K, tile, splits, &plan) || plan.splits <= 1) return 0;
+  if (M <= 0 || N <= 0 || K <= 0 || !gemm_dims_supported(M, N, K) || !ac::make_plan_i8(K, tile, splits, &plan) || plan.splits <= 1) return 0;
   return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t);
 }
 
 size_t ac_gemm_bf16_workspace_bytes(int32_t M, int32_t N, int32_t K) {
-  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  if (M <= 0 || N <= 0 || K <= 0 || !gemm_dims_supported(M, N, K)) return 0;
   const ac::GemmPlan plan = ac::plan_gemm_bf16(M, N, K);
   if (plan.splits <= 1) return 0;
   // fp32 partial products of every K slice
@@ -61,18 +70,20 @@ size_t ac_gemm_bf16_workspace_bytes(int32_t M, int32_t N, int32_t K) {
 
 size_t ac_gemm_bf16_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t tile, int32_t splits) {
   ac::GemmPlan plan;
-  if (M <= 0 || N <= 0 || K <= 0 || !ac::make_plan_bf16(K, tile, splits, &plan) || plan.splits <= 1) return 0;
+  if (M <= 0 || N <= 0 || K <= 0 || !gemm_dims_supported(M, N, K) || !ac::make_plan_bf16(K, tile, splits, &plan) || plan.splits <= 1) return 0;
   return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float);
 }
 
 void ac_gemm_i8_auto_plan(int32_t M, int32_t N, int32_t K, int32_t have_workspace, int32_t* tile, int32_t* splits) {
-  const ac::GemmPlan plan = ac::plan_gemm_i8(M < 0 ? 0 : M, N < 0 ? 0 : N, K < 0 ? 0 : K, have_workspace != 0);
+  if (!gemm_dims_supported(M, N, K)) M = N = K = 0;  // sizes the calls refuse: the plan of the empty problem
+  const ac::GemmPlan plan = ac::plan_gemm_i8(M, N, K, have_workspace != 0);
   if (tile) *tile = plan.tile;
   if (splits) *splits = plan.splits;
 }
 
 void ac_gemm_bf16_auto_plan(int32_t M, int32_t N, int32_t K, int32_t* tile, int32_t* splits) {
-  const ac::GemmPlan plan = ac::plan_gemm_bf16(M < 0 ? 0 : M, N < 0 ? 0 : N, K < 0 ? 0 : K);
+  if (!gemm_dims_supported(M, N, K)) M = N = K = 0;
+  const ac::GemmPlan plan = ac::plan_gemm_bf16(M, N, K);
   if (tile) *tile = plan.tile;
   if (splits) *splits = plan.splits;
 }
@@ -86,7 +97,7 @@ ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t l
                         const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
                         int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
                         void* workspace, size_t workspace_bytes, bool planned, int32_t tile, int32_t splits, void* stream) {
-  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (!gemm_dims_supported(M, N, K)) return AC_ERR_SHAPE;
   if (ac_status s = check_stage(shift, act)) return s;
   if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
   if (bias && bias_ld != 0 && bias_ld < N) return AC_ERR_STRIDE;
@@ -118,7 +129,7 @@ ac_status gemm_bf16_entry(const uint16_t* A, int64_t lda, const uint16_t* B, int
                           float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
                           float alpha, float beta, void* workspace, size_t workspace_bytes,
                           bool planned, int32_t tile, int32_t splits, void* stream) {
-  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (!gemm_dims_supported(M, N, K)) return AC_ERR_SHAPE;
   if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
   ac::GemmPlan plan;
   if (planned && !ac::make_plan_bf16(K, tile, splits, &plan)) return AC_ERR_PLAN;
@@ -154,7 +165,7 @@ ac_status ac_gemm_i8_t(const int8_t* A, int64_t lda, const int8_t* B, int64_t ld
                        const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
                        int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
                        int32_t trans_a, int32_t trans_b, void* stream) {
-  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (!gemm_dims_supported(M, N, K)) return AC_ERR_SHAPE;
   if (ac_status s = check_stage(shift, act)) return s;
   if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return AC_ERR_STRIDE;
   if (bias_ld < 0 || (bias && bias_ld != 0 && bias_ld < N)) return AC_ERR_STRIDE;
@@ -180,7 +191,7 @@ ac_status ac_gemm_i8_planned(const int8_t* A, int64_t lda, const int8_t* B, int6
 ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                            const int32_t* bias, int64_t bias_ld, int32_t* C, int64_t ldc,
                            int32_t M, int32_t N, int32_t K, void* stream) {
-  if (M < 0 || N < 0 || K < 0) return AC_ERR_SHAPE;
+  if (!gemm_dims_supported(M, N, K)) return AC_ERR_SHAPE;
   if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
   if (bias_ld < 0 || (bias && bias_ld != 0 && bias_ld < N)) return AC_ERR_STRIDE;
   if (M == 0 || N == 0) return AC_OK;
@@ -207,7 +218,7 @@ static ac_status conv2d_i8_entry(const int8_t* in, const int8_t* w, const int32_
   const int64_t M = (int64_t)Nb * OH * OW, K = (int64_t)KH * KW * Cin;
   const int64_t in_elems = (int64_t)Nb * H * W * Cin;
   // the kernel indexes the image and the implicit GEMM with 32-bit offsets
-  if (!fits_i32(M) || !fits_i32(K) || !fits_i32(in_elems + (int64_t)KH * W * Cin)) return AC_ERR_SHAPE;
+  if (!gemm_dims_supported(M, Cout, K) || !fits_i32(in_elems + (int64_t)KH * W * Cin)) return AC_ERR_SHAPE;
   ac::GemmPlan plan;
   if (planned && !ac::make_plan_i8((int32_t)K, tile, splits, &plan)) return AC_ERR_PLAN;
   if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;

@@ -56,6 +56,28 @@ def test_validation_without_gpu():
     assert ops.ac_gemm_i8_workspace_bytes(0, 8, 8) == 0
 
 
+def test_sizes_beyond_the_supported_range_are_refused():
+    """Dimensions above 2^29, or more than 2^31 - 1 blocks of 64 x 64 outputs, are refused on the host by every GEMM-like
+    entry point; the size and plan queries answer as for an empty problem."""
+    L = ops.lib()
+    p = 0x1000  # never dereferenced
+    big, imax = (1 << 29) + 1, (1 << 31) - 1
+    for M, N, K in [(big, 16, 16), (16, big, 16), (16, 16, big), (imax, 16, 16), (1 << 29, 1 << 21, 16)]:
+        ld = 1 << 40
+        assert L.ac_gemm_i8(p, ld, p + 256, ld, None, 0, p + 512, ld, M, N, K, 0, 0, None, 0, None) == ops.AC_ERR_SHAPE
+        assert L.ac_gemm_i8_acc32(p, ld, p + 256, ld, None, 0, p + 512, ld, M, N, K, None) == ops.AC_ERR_SHAPE
+        assert L.ac_gemm_i8_t(p, ld, p + 256, ld, None, 0, p + 512, ld, M, N, K, 0, 0, 1, 1, None) == ops.AC_ERR_SHAPE
+        assert L.ac_gemm_bf16(p, ld, p + 256, ld, p + 512, ld, M, N, K, 1.0, 0.0, None) == ops.AC_ERR_SHAPE
+        assert L.ac_gemm_bf16_ws(p, ld, p + 256, ld, p + 512, ld, M, N, K, 1.0, 0.0, None, 0, None) == ops.AC_ERR_SHAPE
+        assert L.ac_gemm_i8_planned(p, ld, p + 256, ld, None, 0, p + 512, ld, M, N, K, 0, 0, None, 0, 64, 1, None) == ops.AC_ERR_SHAPE
+        assert ops.ac_gemm_i8_workspace_bytes(M, N, K) == 0 and ops.ac_gemm_bf16_workspace_bytes(M, N, K) == 0
+        assert ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, 64, 2) == 0
+        assert ops.ac_gemm_i8_auto_plan(M, N, K, True) == ops.ac_gemm_i8_auto_plan(0, 0, 0, True)
+        assert ops.ac_gemm_bf16_auto_plan(M, N, K) == ops.ac_gemm_bf16_auto_plan(0, 0, 0)
+    # a convolution whose implicit GEMM has more than 2^29 rows (input of 2^31 - 1 elements or fewer, so that only M decides)
+    assert L.ac_conv2d_i8(p, p + 256, None, p + 512, 40000, 120, 120, 1, 16, 1, 1, 1, 0, 0, 0, None, 0, None) == ops.AC_ERR_SHAPE
+
+
 def test_planned_entry_validation_without_gpu():
     """Tile / split arguments of the planned launches are checked on the host before anything else runs."""
     L = ops.lib()

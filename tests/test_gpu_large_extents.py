@@ -146,3 +146,114 @@ def test_tinympc_forward_arrays_beyond_4_gib():
     uw, xw = oracle.tinympc_forward(host(Ad), host(Bd), host(Ki), host(x0[t]), host(dd[t]), return_x=True)
     assert rel_fro(host(u[t]), uw) <= 1e-5 and rel_fro(host(xs[t]), xw) <= 1e-5
     assert bool(torch.isfinite(u).all())
+
+
+MAX_DIM = 1 << 29  # the largest dimension the library accepts
+
+
+def _rows_of(M, row_bytes, seed):
+    return torch.from_numpy(sample_rows(M, row_bytes, seed)).cuda()
+
+
+@pytest.mark.parametrize("N,K", [(16, 16), (12, 10)])
+def test_int8_gemm_with_the_largest_row_count(N, K):
+    """M = 2^29 (8 million blocks of 64 rows; operands drawn on the device, 8.6 GB each): the library's own plan, two
+    named tiles, the int32 accumulator read and the transposed-A form, on sampled rows.  N = 12, K = 10 takes the
+    kernels without alignment requirements."""
+    M = MAX_DIM
+    g = torch.Generator(device="cuda").manual_seed(9107)
+    A = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda", generator=g)
+    B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda", generator=g)
+    bias = torch.randint(-(1 << 15), 1 << 15, (N,), dtype=torch.int32, device="cuda", generator=g)
+    rows = _rows_of(M, N, 6)
+    want, acc = oracle.gemm_i8(host(A[rows]), host(B), host(bias), 4, 1, return_acc=True)
+    C = torch.full((M, N), 91, dtype=torch.int8, device="cuda")
+    ops.ac_gemm_i8(A, B, bias, C, 4, 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C[rows]), want)
+    if N % 16 == 0 and K % 16 == 0:
+        for tile in (64, 256):
+            C.fill_(91)
+            ops.ac_gemm_i8_planned(A, B, bias, C, 4, 1, tile, 1)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(host(C[rows]), want, err_msg=f"tile {tile}")
+    del C
+    C32 = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+    ops.ac_gemm_i8_acc32(A, B, bias, C32)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C32[rows]).astype(np.int64), acc)
+    del C32
+    At = A.t().contiguous()  # K x M
+    del A
+    C = torch.full((M, N), 91, dtype=torch.int8, device="cuda")
+    ops.ac_gemm_i8_t(At, B, bias, C, 4, 1, trans_a=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C[rows]), want)
+
+
+def test_bf16_gemm_with_the_largest_row_count():
+    M, N, K = MAX_DIM, 8, 8
+    g = torch.Generator(device="cuda").manual_seed(9108)
+    A = torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16)
+    B = torch.randn((K, N), device="cuda", generator=g).to(torch.bfloat16)
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    ops.ac_gemm_bf16(A, B, C, 1.0, 0.0)
+    torch.cuda.synchronize()
+    rows = _rows_of(M, 4 * N, 7)
+    bits = lambda t: host(t.view(torch.int16)).view(np.uint16)
+    want = oracle.gemm_bf16(bits(A[rows]), bits(B))
+    assert rel_fro(host(C[rows]), want) <= 1e-3
+    assert bool(torch.isfinite(C).all())
+
+
+def _deep_k_operands(M, N, K, dtype):
+    """A[i][k] = +1 / -1 by row, B[k][j] = (k + j) mod 3 - 1: every exact sum has a closed form (no oracle pass over
+    2^29 terms), every partial sum stays far inside int32 and is exact in fp32."""
+    sign = np.where(np.arange(M) % 2 == 0, 1, -1).astype(np.int64)
+    A = torch.from_numpy(sign).to(dtype).cuda()[:, None].expand(M, K).contiguous()
+    B = torch.empty((K, N), dtype=dtype, device="cuda")
+    step = 1 << 24
+    cols = torch.arange(N, device="cuda", dtype=torch.int32)[None, :]
+    for k0 in range(0, K, step):
+        k = torch.arange(k0, min(K, k0 + step), device="cuda", dtype=torch.int32)[:, None]
+        B[k0:k0 + step] = ((k + cols) % 3 - 1).to(dtype)
+    # sum_k B[k][j]: residues r = (k + j) mod 3 contribute r - 1, so the sum is (#r == 2) - (#r == 0)
+    ks = np.arange(3)
+    count = np.array([(K - 1 - ks[r]) // 3 + 1 if ks[r] < K else 0 for r in range(3)], dtype=np.int64)  # k == r mod 3
+    colsum = np.array([count[(2 - j) % 3] - count[(0 - j) % 3] for j in range(N)], dtype=np.int64)
+    return A, B, sign[:, None] * colsum[None, :]
+
+
+def test_int8_gemm_with_the_deepest_k():
+    """K = 2^29 (four million K tiles) on a 16 x 16 output: cut into slices with a workspace, one workgroup without;
+    the expected accumulators come from the closed form and pass through the oracle's output stage."""
+    M, N, K = 16, 16, MAX_DIM
+    A, B, acc = _deep_k_operands(M, N, K, torch.int8)
+    assert np.abs(acc).max() <= 1 and K % 3 != 0  # the three residues nearly cancel: small sums, so add a bias that matters
+    bias = (np.arange(N, dtype=np.int64) - 8) * 100000
+    want = oracle.requantise_vec(acc + bias[None, :], 12, 0)
+    need = ops.ac_gemm_i8_workspace_bytes(M, N, K)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    for workspace in (ws, None):
+        C = torch.full((M, N), 91, dtype=torch.int8, device="cuda")
+        ops.ac_gemm_i8(A, B, dev(bias.astype(np.int32)), C, 12, 0, workspace=workspace)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(C), want)
+    C32 = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+    ops.ac_gemm_i8_acc32(A, B, dev(bias.astype(np.int32)), C32)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C32).astype(np.int64), acc + bias[None, :])
+
+
+def test_bf16_gemm_with_the_deepest_k():
+    M, N, K = 16, 16, MAX_DIM
+    A, B, acc = _deep_k_operands(M, N, K, torch.bfloat16)
+    need = ops.ac_gemm_bf16_workspace_bytes(M, N, K)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    for workspace in (ws, None):
+        C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        ops.ac_gemm_bf16_ws(A, B, C, 1.0, 0.0, workspace=workspace)
+        torch.cuda.synchronize()
+        # every product is -1, 0 or +1 and the sums of a slice stay below 2^24 in magnitude: fp32 is exact here
+        np.testing.assert_array_equal(host(C), acc.astype(np.float32))

@@ -599,8 +599,9 @@ static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
   constexpr int per_cu = (160 * 1024) / (G::LDS_BYTES > 0 ? G::LDS_BYTES : 1);
   int slots = compute_units() * (per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu));
   slots -= slots % 8;
-  const int nwork = ntiles * (p.splits > 1 ? p.splits : 1);
-  const int grid = nwork < slots ? nwork : slots;
+  const int64_t nwork = (int64_t)ntiles * (p.splits > 1 ? p.splits : 1);
+  if (nwork > INT32_MAX) return hipErrorInvalidValue;  // the kernel counts (tile, K slice) items in 32 bits
+  const int grid = nwork < slots ? (int)nwork : slots;
   // multiplier for the division by the band size of the tile order (0: too many tiles for it, divide)
   const unsigned band = 4u * (unsigned)tiles_n;
   const unsigned band_magic = (uint64_t)ntiles * band < (1ull << 32) ? FastDiv::make(band).magic : 0u;

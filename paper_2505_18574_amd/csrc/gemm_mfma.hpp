@@ -174,9 +174,9 @@ struct EpilogueI8 {
   // loads carry no branches: columns beyond N, and every column when there is no row bias, come back as zeros.
   static __device__ __forceinline__ void prefetch(const GemmParams& p, int ncol0, int lane, Pre& pre) {
     const bool row_bias = p.bias != nullptr && p.bias_ld == 0;
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.bias, 0, row_bias && p.N <= (1 << 29) ? p.N * 4 : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.bias, 0, row_bias && p.N < (1 << 29) ? p.N * 4 : 0, 0x00020000);
     const int off = (ncol0 + 4 * (lane >> 5)) * 4;
-    if (p.N <= (1 << 29)) {  // wave-uniform; byte offsets fit the 32-bit buffer arithmetic
+    if (p.N < (1 << 29)) {  // wave-uniform; byte offsets fit the signed 32-bit buffer arithmetic
 #pragma unroll
       for (int q = 0; q < 4; q++) pre.bias[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + 32 * q, 0, 0);
     } else {

@@ -257,3 +257,45 @@ def test_bf16_gemm_with_the_deepest_k():
         torch.cuda.synchronize()
         # every product is -1, 0 or +1 and the sums of a slice stay below 2^24 in magnitude: fp32 is exact here
         np.testing.assert_array_equal(host(C), acc.astype(np.float32))
+
+
+def _cols_of(N, seed):
+    cols = {0, 1, N - 2, N - 1}
+    cols.update(int(x) for x in np.random.default_rng(seed).integers(0, N, 300))
+    return np.array(sorted(cols), dtype=np.int64)
+
+
+@pytest.mark.parametrize("N", [(1 << 25) - 1024, MAX_DIM])
+def test_gemms_with_the_widest_outputs(N):
+    """A 16-row product with N = 2^25 - 1024 columns (the longest B rows the direct-to-LDS kernels address) and with
+    N = 2^29 (the largest the library accepts; rows of B half a gigabyte apart): sampled columns against the oracle
+    for the int8 call, the accumulator read and the bf16 call."""
+    M, K = 16, 16
+    g = torch.Generator(device="cuda").manual_seed(9109)
+    A = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda", generator=g)
+    B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda", generator=g)
+    bias = torch.randint(-(1 << 15), 1 << 15, (N,), dtype=torch.int32, device="cuda", generator=g)
+    cols = _cols_of(N, 8)
+    ct = torch.from_numpy(cols).cuda()
+    want, acc = oracle.gemm_i8(host(A), host(B[:, ct]), host(bias[ct]), 5, 0, return_acc=True)
+    C = torch.full((M, N), 91, dtype=torch.int8, device="cuda")
+    ops.ac_gemm_i8(A, B, bias, C, 5, 0)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C[:, ct]), want)
+    assert int((C[:, -4096:] == 91).sum()) < 4096  # the last columns were written (a stray 91 is a legitimate value)
+    del C
+    C32 = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+    ops.ac_gemm_i8_acc32(A, B, bias, C32)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C32[:, ct]).astype(np.int64), acc)
+    del C32, B, bias
+    Ab = torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16)
+    Bb = torch.empty((K, N), dtype=torch.bfloat16, device="cuda")
+    for k in range(K):  # row by row: a whole fp32 draw of B would be 34 GB
+        Bb[k] = torch.randn((N,), device="cuda", generator=g).to(torch.bfloat16)
+    Cf = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    ops.ac_gemm_bf16(Ab, Bb, Cf, 1.0, 0.0)
+    torch.cuda.synchronize()
+    bits = lambda t: host(t.contiguous().view(torch.int16)).view(np.uint16)
+    assert rel_fro(host(Cf[:, ct]), oracle.gemm_bf16(bits(Ab), bits(Bb[:, ct]))) <= 1e-3
+    assert bool(torch.isfinite(Cf[:, -4096:]).all())

@@ -299,3 +299,35 @@ def test_gemms_with_the_widest_outputs(N):
     bits = lambda t: host(t.contiguous().view(torch.int16)).view(np.uint16)
     assert rel_fro(host(Cf[:, ct]), oracle.gemm_bf16(bits(Ab), bits(Bb[:, ct]))) <= 1e-3
     assert bool(torch.isfinite(Cf[:, -4096:]).all())
+
+
+def test_convolution_on_the_largest_input():
+    """An NHWC input of 2^31 - 1 MB elements (2047 images of 128 x 128 x 64; the library takes inputs below 2^31
+    elements): the library's own choice and every kernel family by name, on images sampled from both ends and from
+    the 2^30 byte mark, against the oracle run on those images alone (images are independent)."""
+    Nb, H, W, Cin, Cout = 2047, 128, 128, 64, 16
+    g = torch.Generator(device="cuda").manual_seed(9110)
+    x = torch.randint(-128, 128, (Nb, H, W, Cin), dtype=torch.int8, device="cuda", generator=g)
+    w = torch.randint(-128, 128, (3, 3, Cin, Cout), dtype=torch.int8, device="cuda", generator=g)
+    b = torch.randint(-(1 << 15), 1 << 15, (Cout,), dtype=torch.int32, device="cuda", generator=g)
+    imgs = torch.tensor([0, 1023, 1024, 2046], device="cuda")
+    want = oracle.conv2d_i8(host(x[imgs]), host(w), host(b), 1, 1, 11, 1)
+    out = torch.full((Nb, H, W, Cout), 17, dtype=torch.int8, device="cuda")
+    M, K = Nb * H * W, 9 * Cin
+    ran = 0
+    for plan in (None, (64, 1), (256, 1), (192, 1), (320, 1), (321, 1), (64, 2)):
+        out.fill_(17)
+        need = ops.ac_gemm_i8_planned_workspace_bytes(M, Cout, K, *plan) if plan else ops.ac_gemm_i8_workspace_bytes(M, Cout, K)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+        try:
+            ops.ac_conv2d_i8(x, w, b, out, 1, 1, 11, 1, workspace=ws, plan=plan)
+        except ops.AcError as e:
+            assert plan is not None and e.status == ops.AC_ERR_PLAN, plan
+            continue
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(out[imgs]), want, err_msg=f"plan {plan}")
+        ran += 1
+    assert ran == 7  # this geometry qualifies for every family
+    # one more image would pass 2^31 elements: refused before anything is launched
+    st = ops.lib().ac_conv2d_i8(x.data_ptr(), w.data_ptr(), b.data_ptr(), out.data_ptr(), Nb + 1, H, W, Cin, Cout, 3, 3, 1, 1, 11, 1, None, 0, None)
+    assert st == ops.AC_ERR_SHAPE

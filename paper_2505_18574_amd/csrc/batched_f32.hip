@@ -149,7 +149,7 @@ constexpr int B12_WAVES = 4;                     // waves per workgroup
 // Every input byte is read exactly once: the loads carry the non-temporal hint, so that the stream does not claim
 // cache lines (the memory-side cache then holds the kernel's output and its neighbours' instead of dead inputs).
 static __device__ __forceinline__ void b12_dma(const void* g, unsigned lds) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds), "v"(g) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds), "v"(g) : "memory");
 }
 
 __global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const BatchedParams p) {

@@ -30,19 +30,20 @@ __device__ __attribute__((aligned(16))) const int g_zero16[4] = {0, 0, 0, 0};
 // One direct-to-LDS wave instruction: lane i copies 16 bytes from gptr to
 // lds_base + 16*i.  Issued through inline assembly so that the compiler does not
 // serialise later LDS reads against it; ordering is enforced explicitly with
-// wait_vm<N>() + a barrier.
+// wait_vm<N>() + a barrier.  The s_nop is the wait state that an LDS-DMA instruction needs after a scalar write
+// of M0 (the compiler pads its own such pairs; it cannot see into the assembly).  It costs nothing measurable.
 static __device__ __forceinline__ void load_to_lds16(const void* gptr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
 // Same, with the source given as a wave-uniform base pointer plus a 32-bit byte offset per lane.
 static __device__ __forceinline__ void load_to_lds16_so(const void* sbase, unsigned voff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
 }
 // The same through a buffer descriptor with a 32-bit byte offset per lane: a lane whose offset lies beyond the
 // descriptor's size receives zeros (the hardware bounds check), which is how the convolution gather writes its
 // padding: no pointer select, no block of zeros.
 static __device__ __forceinline__ void buffer_to_lds16(v4i rsrc, unsigned voff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
 }
 // Workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() would also drain every
 // outstanding global store, which would serialise one tile's epilogue with the next tile's main loop.

@@ -141,8 +141,11 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
     // boundary case: 49 x 2048 x 4608 (9.4 MB of weights behind 32 tiles) takes four slices, 9.3 us instead of
     // 7.9 us on warm operands but 12.7 instead of 22.2 us when the weights come from HBM, as they do whenever
     // anything else ran since the last call (a compute unit sustains only some 50 GB/s of cold misses, so few
-    // workgroups cannot stream weights however deep their prefetch).
-    static const SliceModel model = {{60e3, 45e3, 40e3, 25e3}, {0.066, 0.132, 0.198, 0.24}, 5.0, 4e5};
+    // workgroups cannot stream weights however deep their prefetch).  For the same reason the stream rate of a
+    // 64 x 64 workgroup is the cold one (its four 16 KB stages in flight over some 2 us of HBM latency: 32 GB/s;
+    // the warm tables gave 60): over eighteen further few-tile shapes the library's choices then take 214 us in
+    // sum on operands from HBM against 260 us, and 152 against 158 us on operands from the caches.
+    static const SliceModel model = {{32e3, 45e3, 40e3, 25e3}, {0.066, 0.132, 0.198, 0.24}, 5.0, 4e5};
     int tile = 64, splits = 1;
     plan_few_tiles(M, N, K, have_workspace, model, &tile, &splits);
     make_plan_i8(K, tile, splits, &plan);

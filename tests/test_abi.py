@@ -168,7 +168,8 @@ def test_auto_plans_are_host_arithmetic():
     # several microseconds, so the 18 K tiles of 196 x 1024 x 2304 stay whole while the weight-streaming
     # 49 x 2048 x 4608 is sliced
     assert ops.ac_gemm_i8_auto_plan(196, 1024, 2304, True) == (64, 1)
-    assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, True) == (64, 4)
+    assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, True) == (64, 8)
+    assert ops.ac_gemm_i8_auto_plan(16, 4096, 4096, True) == (64, 4)      # weight streaming: slices although 64 tiles exist
     assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608, False) == (64, 1)
     tile, splits = ops.ac_gemm_i8_auto_plan(49, 512, 9216, True)
     assert tile == 64 and splits > 1

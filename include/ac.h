@@ -95,6 +95,27 @@ ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
 size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
 /*
+ * ac_gemm_i8 for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same operands, same plan and same result
+ * (bit for bit) as ac_gemm_i8 with a workspace of ac_gemm_i8_workspace_bytes(M, N, K) bytes; the int32 partial
+ * sums of a cut K range go through a buffer of AC_STATIC_SCRATCH_BYTES bytes that is part of the library's
+ * device code (every GPU that runs the library holds its own copy until the process ends).  The call allocates
+ * and frees nothing and calls no allocating routine; the first call on a GPU whose plan cuts K resolves that
+ * GPU's copy of the buffer (one symbol lookup, no stream work), so make one such call before a capture.
+ *   - A shape whose partial sums need more than AC_STATIC_SCRATCH_BYTES returns AC_ERR_WORKSPACE and nothing is
+ *     launched (ac_gemm_i8_workspace_bytes tells in advance); shapes the library does not cut never touch the buffer.
+ *   - Nothing in the buffer has to start at zero: every partial sum that is read was written by the same call.
+ *   - All calls on one GPU share that GPU's buffer: calls that may overlap in time on one GPU (different streams,
+ *     or graphs replayed concurrently) race on it and must be serialised by the caller.
+ *   - The GPU that is current at the call must be the one `stream` belongs to.
+ * Validation, error codes and operand rules otherwise as for ac_gemm_i8.
+ */
+#define AC_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+ac_status ac_gemm_i8_static(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                            const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                            int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act, void* stream);
+
+/*
  * int8 GEMM with the raw accumulator as output: C32[i][j] = sum_k A[i][k] * B[k][j] + bias(i, j) in int32,
  * with no scaling and no activation.  This is the accumulator-type read of the paper's accelerator
  * (Appendix C, Fig. 15: bit 29 of an accumulator read address selects the full accumulator value and skips

@@ -96,7 +96,8 @@ namespace {
 ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                         const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
                         int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
-                        void* workspace, size_t workspace_bytes, bool planned, int32_t tile, int32_t splits, void* stream) {
+                        void* workspace, size_t workspace_bytes, bool planned, int32_t tile, int32_t splits, void* stream,
+                        bool static_workspace = false) {
   if (!gemm_dims_supported(M, N, K)) return AC_ERR_SHAPE;
   if (ac_status s = check_stage(shift, act)) return s;
   if (lda < K || ldb < N || ldc < N) return AC_ERR_STRIDE;
@@ -108,10 +109,16 @@ ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t l
   const size_t need = planned ? ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits) : ac_gemm_i8_workspace_bytes(M, N, K);
   if (workspace && (((uintptr_t)workspace & 15) != 0 || workspace_bytes < need)) return AC_ERR_WORKSPACE;
   if (planned && need > 0 && !workspace) return AC_ERR_WORKSPACE;
+  if (static_workspace && need > AC_STATIC_SCRATCH_BYTES) return AC_ERR_WORKSPACE;  // partial sums beyond the library's own buffer
   if (M == 0 || N == 0) return AC_OK;
   if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
   if ((const void*)C == (const void*)A || (const void*)C == (const void*)B || (const void*)C == (const void*)bias)
     return AC_ERR_ALIAS;
+  if (static_workspace && need > 0) {
+    // the call is valid and its plan cuts K: the partial sums go through the current GPU's copy of the library's buffer
+    if (ac::static_scratch(&workspace) != hipSuccess) return AC_ERR_LAUNCH;
+    workspace_bytes = AC_STATIC_SCRATCH_BYTES;
+  }
 
   ac::GemmParams p = {};
   p.A = A; p.B = B; p.C = C; p.bias = bias;
@@ -159,6 +166,13 @@ ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                      int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
                      void* workspace, size_t workspace_bytes, void* stream) {
   return gemm_i8_entry(A, lda, B, ldb, bias, bias_ld, C, ldc, M, N, K, shift, act, workspace, workspace_bytes, false, 0, 0, stream);
+}
+
+ac_status ac_gemm_i8_static(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                            const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,
+                            int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act, void* stream) {
+  static_assert(AC_STATIC_SCRATCH_BYTES == ac::STATIC_SCRATCH_BYTES, "header and library disagree on the scratch size");
+  return gemm_i8_entry(A, lda, B, ldb, bias, bias_ld, C, ldc, M, N, K, shift, act, nullptr, 0, false, 0, 0, stream, true);
 }
 
 ac_status ac_gemm_i8_t(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,

@@ -151,6 +151,10 @@ bool wstat_eligible(const GemmParams& p, int tile);
 // True when the convolution patch kernel behind `tile` (321 / 161) can run the convolution described by p.
 bool conv_halo_eligible(const GemmParams& p, int tile);
 hipError_t launch_gemm_bf16(const GemmParams& p, hipStream_t stream, const GemmPlan* forced = nullptr);
+// Size of the partial-sum buffer that lives in the code object (AC_STATIC_SCRATCH_BYTES of the C header), and the
+// device address of the current GPU's copy of it (resolved on the first call per GPU, kept afterwards).
+constexpr size_t STATIC_SCRATCH_BYTES = 16u << 20;
+hipError_t static_scratch(void** ptr);
 hipError_t launch_batched_f32(const BatchedParams& p, hipStream_t stream);
 bool gemm_i8_fast_path(const GemmParams& p);
 bool conv_i8_fast_path(const GemmParams& p);

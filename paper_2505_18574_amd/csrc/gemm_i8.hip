@@ -3,8 +3,35 @@
 #include "gemm_wstat.hpp"
 
 #include <algorithm>
+#include <mutex>
 
 namespace ac {
+
+// Partial-sum buffer of ac_gemm_i8_static, the entry point for callers that cannot allocate device memory.  It
+// lives in the code object: every GPU that loads the library holds its own copy, at its own address, until the
+// process ends.  In host code the name below is only a handle for hipGetSymbolAddress; the device address it
+// resolves to (one per GPU) is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+hipError_t static_scratch(void** ptr) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex lock;
+  static void* resolved[MAX_DEVICES] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> guard(lock);
+  if (resolved[dev] == nullptr) {  // first call on this GPU (it is the current one): resolve its copy's address
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    resolved[dev] = p;
+  }
+  *ptr = resolved[dev];
+  return hipSuccess;
+}
 
 static int ktb_of_tile(int tile) { return tile == 256 ? 64 : 128; }  // K bytes per tile of the kernel behind a tile code
 

@@ -24,7 +24,7 @@ AC_ACT_NONE, AC_ACT_RELU = 0, 1
 
 # every symbol include/ac.h declares
 EXPORTS = ("ac_gemm_i8", "ac_gemm_i8_workspace_bytes", "ac_conv2d_i8", "ac_gemm_bf16", "ac_batched_gemm_f32",
-           "ac_tinympc_forward_f32", "ac_gemm_i8_acc32",
+           "ac_tinympc_forward_f32", "ac_gemm_i8_acc32", "ac_gemm_i8_static",
            "ac_gemm_i8_t", "ac_gemm_i8_planned", "ac_conv2d_i8_planned", "ac_gemm_i8_planned_workspace_bytes", "ac_gemm_bf16_planned",
            "ac_gemm_bf16_planned_workspace_bytes", "ac_gemm_bf16_ws", "ac_gemm_bf16_workspace_bytes",
            "ac_gemm_i8_auto_plan", "ac_gemm_bf16_auto_plan",
@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         vp, i64, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t, ctypes.c_float
         L.ac_gemm_i8.restype = i32
         L.ac_gemm_i8.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.ac_gemm_i8_static.restype = i32
+        L.ac_gemm_i8_static.argtypes = L.ac_gemm_i8.argtypes[:-3] + [vp]
         L.ac_gemm_i8_workspace_bytes.restype = sz
         L.ac_gemm_i8_workspace_bytes.argtypes = [i32, i32, i32]
         L.ac_conv2d_i8.restype = i32
@@ -181,6 +183,17 @@ def ac_gemm_i8(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, workspace=None
     st = lib().ac_gemm_i8(*_gemm_i8_args(A, B, bias, C), shift, act, wp, wb, _stream(stream))
     if st != AC_OK:
         raise AcError(st, "ac_gemm_i8")
+    return C
+
+
+AC_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def ac_gemm_i8_static(A, B, bias, C, shift: int, act: int = AC_ACT_NONE, stream=None):
+    """ac_gemm_i8 whose K-slice partial sums go through the buffer inside the library (no workspace, no allocation).  Returns C."""
+    st = lib().ac_gemm_i8_static(*_gemm_i8_args(A, B, bias, C), shift, act, _stream(stream))
+    if st != AC_OK:
+        raise AcError(st, "ac_gemm_i8_static")
     return C
 
 

@@ -261,3 +261,15 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ops, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libac_mi355x.so"))
     with pytest.raises(ImportError):
         ops.lib()
+
+
+def test_static_entry_refuses_on_the_host():
+    """ac_gemm_i8_static validates like ac_gemm_i8 and refuses partial sums beyond its buffer, all before any GPU call."""
+    L = ops.lib()
+    p = 0x1000  # never dereferenced
+    assert L.ac_gemm_i8_static(p, 4608, p + 256, 2048, None, 0, p + 512, 2048, 49, 2048, 4608, 32, 0, None) == ops.AC_ERR_SHIFT
+    assert L.ac_gemm_i8_static(p, 4608, p + 256, 2048, None, 0, p + 512, 2000, 49, 2048, 4608, 3, 0, None) == ops.AC_ERR_STRIDE
+    assert L.ac_gemm_i8_static(p, 4608, p + 256, 2048, None, 0, None, 2048, 49, 2048, 4608, 3, 0, None) == ops.AC_ERR_NULL
+    assert L.ac_gemm_i8_static(None, 8, None, 8, None, 0, None, 8, 0, 8, 8, 0, 0, None) == ops.AC_OK
+    assert ops.ac_gemm_i8_workspace_bytes(1024, 1024, 65536) > ops.AC_STATIC_SCRATCH_BYTES
+    assert L.ac_gemm_i8_static(p, 65536, p + 256, 1024, None, 0, p + 512, 1024, 1024, 1024, 65536, 3, 0, None) == ops.AC_ERR_WORKSPACE

@@ -201,34 +201,38 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   const int kbytes = p.K * EB, nbytes = p.N * EB;
   const unsigned char* zero = (const unsigned char*)g_zero16;
   const int ntiles = tiles_m * tiles_n;
-
-  // Persistent workgroups: each takes output tiles blockIdx.x, blockIdx.x + gridDim.x, ...  The stores of one
-  // tile drain while the loads and MFMAs of the next are already running.  gridDim.x is a multiple of the
-  // number of XCDs (or equals ntiles), so a workgroup's tiles all map to its own XCD in tile_coords().
-  // With split-K (int8 only) a work item is (tile, K slice): slice s covers K tiles s * kt_per_split ...
   const int nwork = ntiles * p.splits;
-  // The launcher never starts more workgroups than work items, so the first pass needs no test; without an early
-  // exit ahead of them the kernel arguments load in one round instead of three (0.1 us on a 4 us launch).
-  int work = blockIdx.x;
-  do {
-  const int split = p.splits > 1 ? work / ntiles : 0;
-  const int tile = work - split * ntiles;
-  const int kt0 = split * p.kt_per_split;  // first K tile of this slice
-  int tm, tn;
-  tile_coords_mul(tile, ntiles, tiles_m, tiles_n, band_magic, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN;
 
-  // ---- per-lane source addressing of the direct-to-LDS loads -------------------------------------------
+  // Cross-item prefetch (ping-pong GEMM only): a persistent workgroup requests the first STAGES-1 K tiles of its
+  // next output tile before it runs the output stage of the current one, so that the pipeline fill of the next
+  // tile and the drain of this tile's stores overlap.  Vector-memory operations of a wave complete in issue order,
+  // so the waits of the next tile's first trips name the stores that lie between its loads.
+  constexpr bool XPF = PINGPONG && AMODE == 0;
+  // lower bound of the vector-memory operations one wave issues in the output stage of a FULL tile
+  constexpr int EPI_VM = EPI::LDS_STAGED ? G::TM * 2 * (16 / (64 / (G::WTN / 4))) : G::TM * G::TN;
+  static_assert(!XPF || (STAGES - 2) * (G::A_INSTR + G::B_INSTR) + EPI_VM <= 63, "vmcnt is a 6-bit counter");
+
+  // ---- item-independent lane roles ---------------------------------------------------------------------
+  constexpr int NVAR = G::KTB == 128 ? 2 : 1;
+  int a_chunk[NVAR];
+#pragma unroll
+  for (int v = 0; v < NVAR; v++) a_chunk[v] = (lane % G::A_SPR) ^ G::a_xor(v * G::A_ROWS_PER_INSTR + lane / G::A_SPR);
+  const int64_t b_step = (int64_t)G::BK * p.ldb * EB;
+  v4i a_rsrc = {0, 0, 0, 0};  // buffer descriptor of the input image: base, size in bytes, raw dword format
+  if constexpr (AMODE == 1) {
+    const uint64_t ab = (uint64_t)(uintptr_t)p.A;
+    a_rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)ab);
+    a_rsrc[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(ab >> 32));
+    a_rsrc[2] = __builtin_amdgcn_readfirstlane(p.a_bytes);
+    a_rsrc[3] = 0x00020000;
+  }
+
+  // ---- state of the item whose loads are being issued: per-lane source addressing ------------------------
   // A: wave instruction j (j = wave * A_INSTR + i) fills A_ROWS_PER_INSTR tile rows; lane l -> row
   // j * A_ROWS_PER_INSTR + l / A_SPR, physical slot l % A_SPR, holding logical chunk (l % A_SPR) ^ a_xor(row).
   // The XOR term takes NVAR distinct values per lane as j varies (2 for 128-byte rows, 1 for 64-byte rows).
   // B: wave instruction j fills B_ROWS_PER_INSTR k-rows; lane l -> row j * B_ROWS_PER_INSTR + l / B_SPR,
   // physical slot l % B_SPR.
-  constexpr int NVAR = G::KTB == 128 ? 2 : 1;
-  int a_chunk[NVAR];
-#pragma unroll
-  for (int v = 0; v < NVAR; v++) a_chunk[v] = (lane % G::A_SPR) ^ G::a_xor(v * G::A_ROWS_PER_INSTR + lane / G::A_SPR);
-
   // GEMM (AMODE 0): a wave-uniform base pointer per operand that advances by one K tile per issue, plus a
   // constant 32-bit byte offset per lane and instruction.  Rows beyond M and columns beyond N are clamped
   // to valid ones (their products land in accumulators that are never stored); only a partial last K tile
@@ -238,61 +242,64 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   // says whether the tap falls inside the image (g_mask, bit kh * KW + kw; the host keeps KH * KW <= 32).  A
   // load then costs an add, a bit test and an OR: a lane whose tap is padding, whose row is beyond M or whose K
   // position is beyond K gets the offset 0xffffffff and the bounds check of the buffer load writes its zeros.
+  // The lane's chunk sits at K byte g_kb (the K position of its chunk in the next K tile to be requested), i.e.
+  // tap g_kb / Cin, channel g_kb % Cin; both come from two multiply-high divisions per K tile instead of a carried
+  // (kh, kw, ci) counter with its loops.
+  int split = 0, kt0 = 0, m0 = 0, n0 = 0;
   unsigned a_voff[G::A_INSTR], b_voff[G::B_INSTR];
   int b_krow[G::B_INSTR];
   int g_base[G::A_INSTR];
   unsigned g_mask[G::A_INSTR];
-#pragma unroll
-  for (int i = 0; i < G::A_INSTR; i++) {
-    const int row = (wave * G::A_INSTR + i) * G::A_ROWS_PER_INSTR + lane / G::A_SPR;
-    const int v = (wave * G::A_INSTR + i) & (NVAR - 1);
-    g_base[i] = 0, g_mask[i] = 0u, a_voff[i] = 0;
-    if constexpr (AMODE == 0) {
-      const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
-      a_voff[i] = (unsigned)rclamp * (unsigned)(p.lda * EB) + a_chunk[v] * 16;
-    } else {
-      const int m = m0 + row;
-      const unsigned mm = m < p.M ? (unsigned)m : 0u;
-      const unsigned q = p.dOW.div(mm), img = p.dOH.div(q);
-      const int ow = (int)(mm - q * p.OW), oh = (int)(q - img * p.OH);
-      const int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
-      g_base[i] = (((int)img * p.H + ih0) * p.W + iw0) * p.Cin;
-      auto span = [](int first, int n, int extent) {  // bits k = 0 .. n-1 with 0 <= first + k < extent
-        const int lo = first < 0 ? -first : 0, hi = extent - first < n ? extent - first : n;
-        if (hi <= lo) return 0u;
-        return (hi >= 32 ? ~0u : (1u << hi) - 1u) & ~((1u << lo) - 1u);
-      };
-      const unsigned rows = span(ih0, p.KH, p.H), cols = span(iw0, p.KW, p.W);
-      unsigned mask = 0u;
-      for (int kh = 0; kh < p.KH; kh++)
-        if ((rows >> kh) & 1u) mask |= cols << (kh * p.KW);
-      g_mask[i] = m < p.M ? mask : 0u;
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < G::B_INSTR; i++) {
-    const int row = (wave * G::B_INSTR + i) * G::B_ROWS_PER_INSTR + lane / G::B_SPR;
-    const int ls = BSwizzle<EB, G::B_ROW>::slot(lane % G::B_SPR, row);
-    b_krow[i] = row;
-    b_voff[i] = (unsigned)row * (unsigned)(p.ldb * EB) + (n0 * EB + ls * 16 < nbytes ? ls * 16 : 0);
-  }
-  const int64_t b_step = (int64_t)G::BK * p.ldb * EB;
-  const unsigned char* a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda * EB : 0) + (int64_t)kt0 * G::KTB;
-  const unsigned char* b_base = (const unsigned char*)p.B + (int64_t)n0 * EB + kt0 * b_step;
+  unsigned g_kb[NVAR];
+  const unsigned char* a_base = nullptr;
+  const unsigned char* b_base = nullptr;
 
-  // convolution: the lane's chunk sits at K byte g_kb, i.e. tap g_kb / Cin, channel g_kb % Cin; both come from
-  // two multiply-high divisions per K tile instead of a carried (kh, kw, ci) counter with its loops
-  unsigned g_kb[NVAR];  // K position (bytes) of the lane's chunk in the next K tile to be requested
+  auto setup = [&](int w) {
+    split = p.splits > 1 ? w / ntiles : 0;
+    const int tile = w - split * ntiles;
+    kt0 = split * p.kt_per_split;  // first K tile of this slice
+    int tm, tn;
+    tile_coords_mul(tile, ntiles, tiles_m, tiles_n, band_magic, tm, tn);
+    m0 = tm * BM, n0 = tn * BN;
 #pragma unroll
-  for (int v = 0; v < NVAR; v++) g_kb[v] = (unsigned)(kt0 * G::KTB + a_chunk[v] * 16);
-  v4i a_rsrc = {0, 0, 0, 0};  // buffer descriptor of the input image: base, size in bytes, raw dword format
-  if constexpr (AMODE == 1) {
-    const uint64_t ab = (uint64_t)(uintptr_t)p.A;
-    a_rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)ab);
-    a_rsrc[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(ab >> 32));
-    a_rsrc[2] = __builtin_amdgcn_readfirstlane(p.a_bytes);
-    a_rsrc[3] = 0x00020000;
-  }
+    for (int i = 0; i < G::A_INSTR; i++) {
+      const int row = (wave * G::A_INSTR + i) * G::A_ROWS_PER_INSTR + lane / G::A_SPR;
+      const int v = (wave * G::A_INSTR + i) & (NVAR - 1);
+      g_base[i] = 0, g_mask[i] = 0u, a_voff[i] = 0;
+      if constexpr (AMODE == 0) {
+        const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
+        a_voff[i] = (unsigned)rclamp * (unsigned)(p.lda * EB) + a_chunk[v] * 16;
+      } else {
+        const int m = m0 + row;
+        const unsigned mm = m < p.M ? (unsigned)m : 0u;
+        const unsigned q = p.dOW.div(mm), img = p.dOH.div(q);
+        const int ow = (int)(mm - q * p.OW), oh = (int)(q - img * p.OH);
+        const int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
+        g_base[i] = (((int)img * p.H + ih0) * p.W + iw0) * p.Cin;
+        auto span = [](int first, int n, int extent) {  // bits k = 0 .. n-1 with 0 <= first + k < extent
+          const int lo = first < 0 ? -first : 0, hi = extent - first < n ? extent - first : n;
+          if (hi <= lo) return 0u;
+          return (hi >= 32 ? ~0u : (1u << hi) - 1u) & ~((1u << lo) - 1u);
+        };
+        const unsigned rows = span(ih0, p.KH, p.H), cols = span(iw0, p.KW, p.W);
+        unsigned mask = 0u;
+        for (int kh = 0; kh < p.KH; kh++)
+          if ((rows >> kh) & 1u) mask |= cols << (kh * p.KW);
+        g_mask[i] = m < p.M ? mask : 0u;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < G::B_INSTR; i++) {
+      const int row = (wave * G::B_INSTR + i) * G::B_ROWS_PER_INSTR + lane / G::B_SPR;
+      const int ls = BSwizzle<EB, G::B_ROW>::slot(lane % G::B_SPR, row);
+      b_krow[i] = row;
+      b_voff[i] = (unsigned)row * (unsigned)(p.ldb * EB) + (n0 * EB + ls * 16 < nbytes ? ls * 16 : 0);
+    }
+    a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda * EB : 0) + (int64_t)kt0 * G::KTB;
+    b_base = (const unsigned char*)p.B + (int64_t)n0 * EB + kt0 * b_step;
+#pragma unroll
+    for (int v = 0; v < NVAR; v++) g_kb[v] = (unsigned)(kt0 * G::KTB + a_chunk[v] * 16);
+  };
 
   // Tiles are issued strictly in order 0, 1, 2, ...: the running bases and tap decode rely on it.
   auto issue_loads = [&](int kt_local, int buf) {
@@ -344,15 +351,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   };
 
   typename T::accv acc[G::TM][G::TN];
-#pragma unroll
-  for (int i = 0; i < G::TM; i++)
-#pragma unroll
-    for (int j = 0; j < G::TN; j++) acc[i][j] = T::zero();
-
-  // operands of the output stage that do not depend on the product (bias) are requested before the K loop
-  typename EPI::Pre pre[G::TN];
-#pragma unroll
-  for (int j = 0; j < G::TN; j++) EPI::prefetch(p, n0 + wn * G::WTN + j * 32, lane, pre[j]);
 
   // ---- fragments ---------------------------------------------------------------------------------------
   // the lane's A row within a 32-row MFMA tile is lane & 31; tile origins are multiples of 32 rows and do
@@ -377,18 +375,9 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
 #pragma unroll
       for (int j = 0; j < G::TN; j++) acc[i][j] = EPI::SWAP ? T::mfma(f.b[j], f.a[i], acc[i][j]) : T::mfma(f.a[i], f.b[j], acc[i][j]);
   };
-
-  // ---- main loop ---------------------------------------------------------------------------------------
   const int nkt_total = (kbytes + G::KTB - 1) / G::KTB;
-  const int nkt = p.splits > 1 ? (nkt_total - kt0 < p.kt_per_split ? nkt_total - kt0 : p.kt_per_split) : nkt_total;
   constexpr int PER_TILE = G::A_INSTR + G::B_INSTR;  // outstanding vector-memory ops per tile per wave
   static_assert((STAGES - 1) * PER_TILE <= 63, "vmcnt is a 6-bit counter");
-
-  // Steady state (plain GEMM operands): both loops below run STAGES tiles per trip for as long as the tile being
-  // requested is a whole one.  With the stage index a compile-time constant every LDS address of a step is a
-  // fixed per-lane register plus an immediate, the loads take the uniform-base form, and no decision is left
-  // inside a step.  (A wave has an issue slot only every few cycles: every scalar branch and address add of
-  // a memory phase is time the MFMAs wait for.)
   using SW = BSwizzle<EB, G::B_ROW>;
   constexpr int ROWS_PER_CHUNK = 16 / EB;  // k-rows of B that 16 bytes of K span
   static_assert(ROWS_PER_CHUNK % SW::RPW == 0 && ((ROWS_PER_CHUNK / SW::RPW) & SW::MASK) == 0, "the B swizzle term must not depend on the K-step");
@@ -398,6 +387,21 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   for (int ks = 0; ks < G::KSTEPS; ks++) a_fo[ks] = a_lane_off + (((2 * ks + (lane >> 5)) ^ a_swz) << 4);
 #pragma unroll
   for (int j = 0; j < G::TN; j++) b_fo[j] = G::A_BYTES + dtl_col_off<T, G::B_ROW>((lane >> 5) * 16, wn * G::TN + j, lane);
+  // The immediate offset of an LDS read has 16 bits: stages that begin 64 KB or more into LDS are read through a
+  // second set of lane addresses, 64 KB up (made opaque, or the compiler folds them back into one register per read).
+  constexpr bool HI_STAGES = (STAGES - 1) * G::STAGE >= 65536;
+  static_assert((STAGES - 1) * G::STAGE < 2 * 65536, "a third set of lane addresses would be needed");
+  int a_fo_hi[G::KSTEPS], b_fo_hi[G::TN];
+#pragma unroll
+  for (int ks = 0; ks < G::KSTEPS; ks++) {
+    a_fo_hi[ks] = a_fo[ks] + 65536;
+    if constexpr (HI_STAGES) asm volatile("" : "+v"(a_fo_hi[ks]));
+  }
+#pragma unroll
+  for (int j = 0; j < G::TN; j++) {
+    b_fo_hi[j] = b_fo[j] + 65536;
+    if constexpr (HI_STAGES) asm volatile("" : "+v"(b_fo_hi[j]));
+  }
   // K slices keep the general loops; the convolution gather handles a partial last tile itself
   const int nkt_whole = p.splits > 1 ? 0 : (AMODE == 0 ? kbytes / G::KTB : nkt_total);
   auto issue_whole = [&](auto lbufc) {  // the next tile in order, a whole one, into stage LBUF
@@ -409,13 +413,45 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     a_base += G::KTB;
     b_base += b_step;
   };
+  auto issue_whole_rt = [&](int lbuf) {  // the same with the stage as a value (constant after unrolling)
+#pragma unroll
+    for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], lds0 + lbuf * G::STAGE + (wave * G::A_INSTR + i) * 1024);
+#pragma unroll
+    for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], lds0 + lbuf * G::STAGE + G::A_BYTES + (wave * G::B_INSTR + i) * 1024);
+    a_base += G::KTB;
+    b_base += b_step;
+  };
   auto read_frags_at = [&](auto bufc, int ks, Frag& f) {  // read_frags with the stage as a constant
     constexpr int BUF = decltype(bufc)::value;
+    constexpr bool HI = BUF * G::STAGE >= 65536;
+    constexpr int SOFF = BUF * G::STAGE - (HI ? 65536 : 0);
 #pragma unroll
-    for (int i = 0; i < G::TM; i++) f.a[i] = *(const v4i*)(smem + (a_fo[ks] + (BUF * G::STAGE + i * 32 * G::KTB)));
+    for (int i = 0; i < G::TM; i++) f.a[i] = *(const v4i*)(smem + ((HI ? a_fo_hi[ks] : a_fo[ks]) + (SOFF + i * 32 * G::KTB)));
 #pragma unroll
-    for (int j = 0; j < G::TN; j++) f.b[j] = dtl_read_col_at<T, G::B_ROW>(smem + (b_fo[j] + (BUF * G::STAGE + ks * KS_B)));
+    for (int j = 0; j < G::TN; j++) f.b[j] = dtl_read_col_at<T, G::B_ROW>(smem + ((HI ? b_fo_hi[j] : b_fo[j]) + (SOFF + ks * KS_B)));
   };
+
+  // Persistent workgroups: each takes output tiles blockIdx.x, blockIdx.x + gridDim.x, ...  gridDim.x is a multiple
+  // of the number of XCDs (or equals ntiles), so a workgroup's tiles all map to its own XCD in tile_coords().
+  // With split-K a work item is (tile, K slice): slice s covers K tiles s * kt_per_split ...
+  // The launcher never starts more workgroups than work items, so the first pass needs no test.
+  int work = blockIdx.x;
+  bool started = false;  // the item's addressing is set up and its first STAGES-1 tiles are requested
+  bool pf_stores = false;  // ... and EPI_VM stores of a full tile were issued after those requests
+  do {
+  if (!started) setup(work);
+  const int nkt = p.splits > 1 ? (nkt_total - kt0 < p.kt_per_split ? nkt_total - kt0 : p.kt_per_split) : nkt_total;
+
+#pragma unroll
+  for (int i = 0; i < G::TM; i++)
+#pragma unroll
+    for (int j = 0; j < G::TN; j++) acc[i][j] = T::zero();
+
+  // operands of the output stage that do not depend on the product (bias) are requested before the K loop
+  typename EPI::Pre pre[G::TN];
+#pragma unroll
+  for (int j = 0; j < G::TN; j++) EPI::prefetch(p, n0 + wn * G::WTN + j * 32, lane, pre[j]);
+
   if constexpr (PINGPONG) {
     // ---- ping-pong main loop ---------------------------------------------------------------------------
     // Eight waves, two per SIMD, in two groups of four (one wave of each group on every SIMD).  A wave
@@ -433,23 +469,27 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     static_assert(!PINGPONG || STAGES >= 3, "ping-pong needs at least three LDS stages");
     const int grp = wave >> 2;
     Frag fr[G::KSTEPS];
+    if (!started) {
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; s++)
-      if (s < nkt) issue_loads(s, s);
-    if (STAGES - 2 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
+      for (int s = 0; s < STAGES - 1; s++)
+        if (s < nkt) issue_loads(s, s);
+    }
+    // tile 0 has landed: the younger tiles (and, after a prefetch, the stores behind them) may still be in flight
+    if (XPF && started && pf_stores) wait_vm<(STAGES - 2) * PER_TILE + (XPF ? EPI_VM : 0)>();
+    else if (STAGES - 2 < nkt) wait_vm<(STAGES - 2) * PER_TILE>();
     else wait_vm<0>();
     block_sync();                  // tile 0 is visible
     if (grp == 1) block_sync();    // hold group 1 back by one phase
     int buf = 0;
     int kt = 0;
     {
-      auto trip = [&](auto bufc) {
+      auto trip = [&](auto bufc, auto extrac) {
         constexpr int BUF = decltype(bufc)::value, LBUF = (BUF + STAGES - 1) % STAGES;
         if constexpr (AMODE == 0) issue_whole(std::integral_constant<int, LBUF>{});
         else issue_loads(kt + BUF + STAGES - 1, LBUF);  // the gather keeps its per-lane addressing; kt is a multiple of STAGES here
 #pragma unroll
         for (int ks = 0; ks < G::KSTEPS; ks++) read_frags_at(bufc, ks, fr[ks]);
-        wait_vm<(STAGES - 2) * PER_TILE>();
+        wait_vm<(STAGES - 2) * PER_TILE + decltype(extrac)::value>();
         block_sync();
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
@@ -457,9 +497,20 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
         __builtin_amdgcn_s_setprio(0);
         block_sync();
       };
+      if constexpr (XPF) {
+        // first round after a prefetch across full-tile stores: the loads that trips 0 .. STAGES-3 wait for are
+        // older than those stores, so their waits name them instead of draining them
+        if (started && pf_stores && kt + 2 * STAGES - 2 < nkt_whole && kt + 2 * STAGES - 2 < nkt) {
+          for_each_stage([&](auto bc) {
+            if constexpr (decltype(bc)::value < STAGES - 2) trip(bc, std::integral_constant<int, EPI_VM>{});
+            else trip(bc, std::integral_constant<int, 0>{});
+          }, std::make_integer_sequence<int, STAGES>{});
+          kt += STAGES;
+        }
+      }
       // tiles kt + STAGES - 1 .. kt + 2 STAGES - 2, the ones a round of trips requests, are whole
       for (; kt + 2 * STAGES - 2 < nkt_whole && kt + 2 * STAGES - 2 < nkt; kt += STAGES)
-        for_each_stage(trip, std::make_integer_sequence<int, STAGES>{});
+        for_each_stage([&](auto bc) { trip(bc, std::integral_constant<int, 0>{}); }, std::make_integer_sequence<int, STAGES>{});
     }
     for (; kt < nkt; kt++) {
       // memory phase
@@ -540,23 +591,39 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   }
   }
 
-  // ---- epilogue ----------------------------------------------------------------------------------------
+  // ---- output stage of the finished item; with XPF the next item's first tiles are requested ahead of it ----
+  const int em0 = m0, en0 = n0, esplit = split;
+  const bool efull = em0 + BM <= p.M && en0 + BN <= p.N;  // wave-uniform: no store of this tile is masked
+  started = false;
+  if constexpr (XPF) {
+    // every item of a launch has the same K range here (no K slices); the fill needs STAGES - 1 whole tiles
+    if (work + (int)gridDim.x < nwork && p.splits == 1 && nkt_whole >= STAGES - 1) {
+      block_sync();  // every wave has read its last fragments: stages 0 .. STAGES-2 can take the next item's tiles
+      setup(work + (int)gridDim.x);
+#pragma unroll
+      for (int s = 0; s < STAGES - 1; s++) issue_whole_rt(s);
+      started = true;
+      pf_stores = efull;
+    }
+  }
   if constexpr (EPI::LDS_STAGED) {
     // 4-byte outputs through LDS: the accumulator layout gives a lane one column of many rows, so straight
     // stores are dwords (one 128-byte row segment per half-wave and instruction, 128 instructions per wave for
     // a 64 x 128 wave tile, each about as slow to issue as a 16-byte one).  Every wave instead transposes 16
-    // rows of its tile at a time through a private LDS region (row pitch WTN + 8 values: the two half-waves,
-    // four rows apart, hit different banks) and stores 16 bytes per lane, whole 128-byte lines per 8 lanes.
-    // (Cycle stamps: 11000 -> 6800 per 256 x 256 fp32 tile; writing the next chunk under the reads of this one
-    // did not shorten it further: the LDS writes and the store issue are the time, not the LDS latency.)
+    // rows of its tile at a time through a private LDS region and stores 16 bytes per lane, whole 128-byte lines
+    // per 8 lanes.  With XPF the region lies in the last LDS stage, which the next item does not fill before its
+    // first trip: row pitch WTN values with the two half-rows exchanged in rows 4..7 and 12..15, so that the two
+    // half-waves, four rows apart, still hit different banks.  Otherwise: row pitch WTN + 8 from the LDS base.
     using SV = typename EPI::StagedValue;
     typedef SV sv4 __attribute__((ext_vector_type(4)));
-    constexpr int PITCH = G::WTN + 8;
+    constexpr int PITCH = XPF ? G::WTN : G::WTN + 8;
     constexpr int LPR = G::WTN / 4, RPI = 64 / LPR, NI = 16 / RPI;  // lanes per row, rows per instruction, instructions per 16 rows
-    static_assert(G::WAVES * 16 * PITCH * 4 <= G::LDS_BYTES && 64 % LPR == 0 && 16 % RPI == 0 && sizeof(SV) == 4, "staging region");
-    block_sync();  // every wave has read its last fragments: the stages are free
-    SV* region = (SV*)smem + wave * (16 * PITCH);
+    static_assert(G::WAVES * 16 * PITCH * 4 <= (XPF ? G::STAGE : G::LDS_BYTES) && 64 % LPR == 0 && 16 % RPI == 0 && sizeof(SV) == 4, "staging region");
+    static_assert(!XPF || (G::WTN % 64 == 0), "the half-row exchange needs rows of whole 32-value halves");
+    if (!started) block_sync();  // every wave has read its last fragments: the stages are free
+    SV* region = (SV*)(smem + (XPF ? (STAGES - 1) * G::STAGE : 0)) + wave * (16 * PITCH);
     const int h = lane >> 5, c = lane & 31;
+    auto body = [&](auto fullc) {
 #pragma unroll
     for (int i = 0; i < G::TM; i++) {
 #pragma unroll
@@ -564,24 +631,31 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
 #pragma unroll
         for (int j = 0; j < G::TN; j++)
 #pragma unroll
-          for (int rr = 0; rr < 8; rr++)
-            region[(8 * (rr / 4) + 4 * h + rr % 4) * PITCH + 32 * j + c] = EPI::staged_in(p, acc[i][j][hf * 8 + rr]);
+          for (int rr = 0; rr < 8; rr++) {
+            const int row = 8 * (rr / 4) + 4 * h + rr % 4;
+            const int col = XPF ? ((32 * j + c) ^ (h << 5)) : 32 * j + c;  // rows 4 h + ... have bit 2 == h
+            region[row * PITCH + col] = EPI::staged_in(p, acc[i][j][hf * 8 + rr]);
+          }
 #pragma unroll
         for (int q = 0; q < NI; q++) {
           const int row = q * RPI + lane / LPR, col = (lane % LPR) * 4;
-          const sv4 o = *(const sv4*)(region + row * PITCH + col);
-          const int m = m0 + wm * G::WTM + i * 32 + hf * 16 + row, n = n0 + wn * G::WTN + col;
+          const int pcol = XPF ? (col ^ (((row >> 2) & 1) << 5)) : col;
+          const sv4 o = *(const sv4*)(region + row * PITCH + pcol);
+          const int m = em0 + wm * G::WTM + i * 32 + hf * 16 + row, n = en0 + wn * G::WTN + col;
           // N is a multiple of 4 on this path: a group of four columns is inside or outside
-          if (m < p.M && n < p.N) EPI::staged_out(p, m, n, o, split);
+          if (decltype(fullc)::value || (m < p.M && n < p.N)) EPI::staged_out(p, m, n, o, esplit);
         }
       }
     }
+    };
+    if (XPF && efull) body(std::true_type{});
+    else body(std::false_type{});
   } else {
 #pragma unroll
   for (int i = 0; i < G::TM; i++) {
-    const int mrow0 = m0 + wm * G::WTM + i * 32;
+    const int mrow0 = em0 + wm * G::WTM + i * 32;
 #pragma unroll
-    for (int j = 0; j < G::TN; j++) EPI::tile(p, mrow0, n0 + wn * G::WTN + j * 32, acc[i][j], lane, split, pre[j]);
+    for (int j = 0; j < G::TN; j++) EPI::tile(p, mrow0, en0 + wn * G::WTN + j * 32, acc[i][j], lane, esplit, pre[j]);
   }
   }
   block_sync();  // all LDS reads of this tile are done before the next tile refills the LDS stages

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import oracle
-from gpu_util import dev, host, rel_fro
+from gpu_util import check_bf16_product_in_full, dev, host, rel_fro
 from paper_2505_18574_amd import inputs, ops
 
 pytestmark = pytest.mark.gpu
@@ -166,23 +166,16 @@ def test_strided_views_and_guard_bands():
 
 
 @pytest.mark.parametrize("case", inputs.GEMM_BF16, ids=lambda c: c.name)
-def test_workload_configs_sampled(case):
-    """Full-size workloads as the benchmark launches them: sampled elements and whole rows against the
-    oracle, plus a whole-matrix property, C v == A (B v), evaluated in fp64."""
+def test_workload_configs_in_full(case):
+    """Full-size workloads as the benchmark launches them: every output element against the oracle (norm and
+    element-wise bound), plus a whole-matrix property, C v == A (B v), evaluated in fp64."""
     A, B = inputs.gemm_bf16_case_inputs(case)
     got = run_gpu(A, B)
-    assert np.isfinite(got).all()
+    check_bf16_product_in_full(A, B, got)
     rng = np.random.default_rng(0)
-    M, N, K = case.M, case.N, case.K
-    r = np.concatenate([rng.integers(0, M, 6000), [0, 0, M - 1, M - 1], np.repeat(rng.integers(0, M, 4), N)])
-    c = np.concatenate([rng.integers(0, N, 6000), [0, N - 1, 0, N - 1], np.tile(np.arange(N), 4)])
-    want, mag = oracle.gemm_bf16_at(A, B, r, c)
-    g = got[r, c].astype(np.float64)
-    assert rel_fro(g, want) <= REL_FRO_TOL
-    assert (np.abs(g - want) <= 4.0 * (K + 2) * 2.0 ** -24 * mag + 1e-30).all()
     Ad = inputs.bf16_bits_to_f32(A).astype(np.float64)
     Bd = inputs.bf16_bits_to_f32(B).astype(np.float64)
-    v = rng.standard_normal((N, 3))
+    v = rng.standard_normal((case.N, 3))
     assert rel_fro(got.astype(np.float64) @ v, Ad @ (Bd @ v)) <= 1e-4
 
 

@@ -9,11 +9,18 @@
  * TinyMPC study (Section 4.4.3, Appendix D.2).
  *
  * Conventions shared by every entry point
- *  - Every data pointer is a DEVICE pointer into memory owned by the caller.
- *    The library allocates nothing, frees nothing, keeps no state between
- *    calls and never synchronises: work is enqueued on `stream` (a
+ *  - Every data pointer is a DEVICE pointer into ordinary (coarse-grained)
+ *    device memory owned by the caller.  The library allocates nothing, frees
+ *    nothing and never synchronises: work is enqueued on `stream` (a
  *    hipStream_t passed as void*; NULL = the default stream) and the call
  *    returns once the kernels are launched.
+ *  - No result depends on an earlier call.  What the library does keep for the
+ *    life of the process is set-up, not results: it serves ONE GPU per process
+ *    (the compute-unit count of the device that is current at the first call
+ *    sizes every launch), each kernel is configured for its LDS size the first
+ *    time it is launched, and ac_gemm_i8_static owns a partial-sum buffer.  The
+ *    kernel / tile choices are calibrated on the 256 compute units in 8 XCDs of
+ *    an MI355X; on another count they stay correct and are merely untuned.
  *  - All matrices are row-major.  Leading dimensions (lda, ...) are in
  *    ELEMENTS and may exceed the row length.
  *  - An output must not share its base address with an input
@@ -176,8 +183,12 @@ ac_status ac_conv2d_i8(const int8_t* in, const int8_t* w, const int32_t* bias, i
  *   K == 0 gives C = beta * C.
  * Products are exact in fp32; sums are accumulated in fp32 in an unspecified
  * order.  Shapes with few output tiles and a deep K are cut along K (see the
- * planned launches below): their sums may differ in the last bits from run to
- * run.
+ * planned launches below) where the library's estimate, the cost of the
+ * combining atomic adds included, is at least a fifth below that of the best
+ * uncut plan: the slices then add into C with fp32 atomic adds, and the sums
+ * may differ in the last bits from run to run (ac_gemm_bf16_ws with a
+ * workspace gives the same bits every run).  C must be ordinary device memory
+ * as the conventions above say: the atomic adds are the hardware's own.
  */
 ac_status ac_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb,
                        float* C, int64_t ldc, int32_t M, int32_t N, int32_t K,
@@ -202,7 +213,7 @@ size_t ac_gemm_bf16_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
 /*
  * Batched small fp32 linear algebra (the fine-grained workload of Section
- * 5.1.3: small dense products chained with matrix-vector products and
+ * 4.4.3: small dense products chained with matrix-vector products and
  * element-wise adds), for each item b independently:
  *
  *   C_b = A_b . B_b                 (n x n)

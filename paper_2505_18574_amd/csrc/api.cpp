@@ -9,6 +9,13 @@ namespace {
 
 bool fits_i32(int64_t v) { return v >= 0 && v <= INT_MAX; }
 
+// *out = a * b for non-negative factors that each fit int32, false when the product does not fit int32.
+bool mul_i32(int64_t a, int64_t b, int64_t* out) {
+  if (!fits_i32(a) || !fits_i32(b)) return false;
+  *out = a * b;  // below 2^62
+  return fits_i32(*out);
+}
+
 // Sizes of an (implicit) GEMM the kernels and planners index without overflow: every dimension at most 2^29 (row
 // lengths in bytes and rounded-up tile counts are 32-bit) and at most 2^31 - 1 tiles of 64 x 64 (work counters are
 // 32-bit; such an output would be 8 TB).
@@ -110,6 +117,16 @@ ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t l
   if (workspace && (((uintptr_t)workspace & 15) != 0 || workspace_bytes < need)) return AC_ERR_WORKSPACE;
   if (planned && need > 0 && !workspace) return AC_ERR_WORKSPACE;
   if (static_workspace && need > AC_STATIC_SCRATCH_BYTES) return AC_ERR_WORKSPACE;  // partial sums beyond the library's own buffer
+
+  ac::GemmParams p = {};
+  p.A = A; p.B = B; p.C = C; p.bias = bias;
+  p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.bias_ld = bias_ld;
+  p.M = M; p.N = N; p.K = K; p.shift = shift; p.act = act;
+  p.splits = 1;
+  // what a named plan asks of the operands is checked for every call, empty problems included
+  if (planned && plan.splits > 1 && !ac::gemm_i8_fast_path(p)) return AC_ERR_PLAN;
+  if (planned && (tile == 320 || tile == 160) && !(ac::gemm_i8_fast_path(p) && ac::wstat_eligible(p, tile))) return AC_ERR_PLAN;
+  if (planned && (tile == 321 || tile == 161)) return AC_ERR_PLAN;  // the patch kernel is a convolution kernel
   if (M == 0 || N == 0) return AC_OK;
   if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
   if ((const void*)C == (const void*)A || (const void*)C == (const void*)B || (const void*)C == (const void*)bias)
@@ -119,16 +136,7 @@ ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t l
     if (ac::static_scratch(&workspace) != hipSuccess) return AC_ERR_LAUNCH;
     workspace_bytes = AC_STATIC_SCRATCH_BYTES;
   }
-
-  ac::GemmParams p = {};
-  p.A = A; p.B = B; p.C = C; p.bias = bias;
-  p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.bias_ld = bias_ld;
-  p.M = M; p.N = N; p.K = K; p.shift = shift; p.act = act;
-  p.splits = 1;
   p.partial = (int32_t*)workspace;
-  if (planned && plan.splits > 1 && !ac::gemm_i8_fast_path(p)) return AC_ERR_PLAN;
-  if (planned && (tile == 320 || tile == 160) && !(ac::gemm_i8_fast_path(p) && ac::wstat_eligible(p, tile))) return AC_ERR_PLAN;
-  if (planned && (tile == 321 || tile == 161)) return AC_ERR_PLAN;  // the patch kernel is a convolution kernel
   return ac::launch_gemm_i8(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }
 
@@ -143,10 +151,6 @@ ac_status gemm_bf16_entry(const uint16_t* A, int64_t lda, const uint16_t* B, int
   if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;
   const size_t need = planned ? ac_gemm_bf16_planned_workspace_bytes(M, N, K, tile, splits) : ac_gemm_bf16_workspace_bytes(M, N, K);
   if (workspace && (((uintptr_t)workspace & 15) != 0 || workspace_bytes < need)) return AC_ERR_WORKSPACE;
-  if (M == 0 || N == 0) return AC_OK;
-  if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
-  if ((const void*)C == (const void*)A || (const void*)C == (const void*)B) return AC_ERR_ALIAS;
-
   ac::GemmParams p = {};
   p.A = A; p.B = B; p.C = C;
   p.lda = lda; p.ldb = ldb; p.ldc = ldc;
@@ -154,6 +158,10 @@ ac_status gemm_bf16_entry(const uint16_t* A, int64_t lda, const uint16_t* B, int
   p.splits = 1;
   p.partial = (int32_t*)workspace;
   if (planned && plan.splits > 1 && !ac::gemm_bf16_fast_path(p)) return AC_ERR_PLAN;
+  if (M == 0 || N == 0) return AC_OK;
+  if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
+  if ((const void*)C == (const void*)A || (const void*)C == (const void*)B) return AC_ERR_ALIAS;
+
   return ac::launch_gemm_bf16(p, (hipStream_t)stream, planned ? &plan : nullptr) == hipSuccess ? AC_OK : AC_ERR_LAUNCH;
 }
 
@@ -229,10 +237,15 @@ static ac_status conv2d_i8_entry(const int8_t* in, const int8_t* w, const int32_
   if ((int64_t)KH > (int64_t)H + 2 * (int64_t)pad || (int64_t)KW > (int64_t)W + 2 * (int64_t)pad) return AC_ERR_SHAPE;
   if (H > 32767 - pad || W > 32767 - pad) return AC_ERR_SHAPE;  // image coordinates are kept in 16 bits
   const int64_t OH = ((int64_t)H + 2 * pad - KH) / stride + 1, OW = ((int64_t)W + 2 * pad - KW) / stride + 1;
-  const int64_t M = (int64_t)Nb * OH * OW, K = (int64_t)KH * KW * Cin;
-  const int64_t in_elems = (int64_t)Nb * H * W * Cin;
-  // the kernel indexes the image and the implicit GEMM with 32-bit offsets
-  if (!gemm_dims_supported(M, Cout, K) || !fits_i32(in_elems + (int64_t)KH * W * Cin)) return AC_ERR_SHAPE;
+  // The kernel indexes the image and the implicit GEMM with 32-bit offsets.  Every product below is formed one
+  // factor at a time and refused as soon as it leaves int32, so that none of them can overflow int64 first
+  // (a large stride keeps OH * OW tiny while Nb, H * W and Cin are all near 2^31).
+  int64_t M = 0, K = 0, in_elems = 0, window = 0;
+  if (!mul_i32(Nb, OH, &M) || !mul_i32(M, OW, &M)) return AC_ERR_SHAPE;
+  if (!mul_i32(KH, KW, &K) || !mul_i32(K, Cin, &K)) return AC_ERR_SHAPE;
+  if (!mul_i32(Nb, H, &in_elems) || !mul_i32(in_elems, W, &in_elems) || !mul_i32(in_elems, Cin, &in_elems)) return AC_ERR_SHAPE;
+  if (!mul_i32(KH, W, &window) || !mul_i32(window, Cin, &window)) return AC_ERR_SHAPE;
+  if (!gemm_dims_supported(M, Cout, K) || !fits_i32(in_elems + window)) return AC_ERR_SHAPE;
   ac::GemmPlan plan;
   if (planned && !ac::make_plan_i8((int32_t)K, tile, splits, &plan)) return AC_ERR_PLAN;
   if ((workspace == nullptr) != (workspace_bytes == 0)) return AC_ERR_WORKSPACE;

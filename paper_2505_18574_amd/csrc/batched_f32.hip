@@ -152,6 +152,18 @@ static __device__ __forceinline__ void b12_dma(const void* g, unsigned lds) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds), "v"(g) : "memory");
 }
 
+// The stores of a step are written as instructions as well: the waits below count the vector-memory operations
+// between a group's loads and the point of the wait, so that number has to be a property of the source, not of
+// how the compiler happens to split or merge stores.  (A store wider than 8 bytes needs wait states before its
+// data registers may be overwritten; the compiler pads its own stores and cannot see into the assembly.)
+typedef float b12_v3f __attribute__((ext_vector_type(3)));
+static __device__ __forceinline__ void b12_store16(float* g, v4f v) {
+  asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" ::"v"(g), "v"(v) : "memory");
+}
+static __device__ __forceinline__ void b12_store12(float* g, b12_v3f v) {
+  asm volatile("global_store_dwordx3 %0, %1, off\n\ts_nop 1" ::"v"(g), "v"(v) : "memory");
+}
+
 __global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const BatchedParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_b[];
   const int lane = threadIdx.x & 63;
@@ -188,8 +200,9 @@ __global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const 
   // a step names how many younger operations may still be pending instead of draining everything: the loads of
   // the next group are followed by the stores of the previous step, the loads of the group after, and the stores
   // of this step.  Waiting for the stores themselves would put a write round trip into every step.
-  // A full group issues 8 loads (3 + 3 for A and B, x, d) and the step 3 + 1 stores (C rows, y); any other case
-  // (a partial last group, absent operands) takes the plain wait for everything.
+  // A full group issues 8 loads (3 + 3 for A and B, x, d) and the step 3 + 1 stores (C rows, y), every one of them
+  // an instruction written out above; any other case (a partial last group, absent operands) takes the plain wait
+  // for everything.
   constexpr int LOADS = 8, STORES = 4;
   const bool counted = has_x && has_d && p.C != nullptr;
   int64_t g = (int64_t)blockIdx.x * B12_WAVES + wave;
@@ -227,7 +240,7 @@ __global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const 
       if (p.C && bj < 3) {
         float* Cg = p.C + item * 144 + 3 * bi * 12 + 4 * bj;
 #pragma unroll
-        for (int i = 0; i < 3; i++) *(v4f*)(Cg + i * 12) = c[i];
+        for (int i = 0; i < 3; i++) b12_store16(Cg + i * 12, c[i]);  // three store instructions
       }
       if (has_x) {
         const v4f xv = *(const v4f*)((const float*)(Wn + 2 * B12_MAT + it * 48) + 4 * cb);
@@ -244,9 +257,8 @@ __global__ void __launch_bounds__(64 * B12_WAVES) batched12_stream_kernel(const 
         }
         if (bj == 0) {
           const float* dv = (const float*)(Wn + 2 * B12_MAT + B12_VEC + it * 48) + 3 * bi;
-          typedef float v3f __attribute__((ext_vector_type(3)));
-          const v3f yv = {s[0] + (has_d ? dv[0] : 0.f), s[1] + (has_d ? dv[1] : 0.f), s[2] + (has_d ? dv[2] : 0.f)};
-          *(v3f*)(p.y + item * 12 + 3 * bi) = yv;  // one 12-byte store instruction (the wait below counts instructions)
+          const b12_v3f yv = {s[0] + (has_d ? dv[0] : 0.f), s[1] + (has_d ? dv[1] : 0.f), s[2] + (has_d ? dv[2] : 0.f)};
+          b12_store12(p.y + item * 12 + 3 * bi, yv);  // one store instruction
         }
       }
     }

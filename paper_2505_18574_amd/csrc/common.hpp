@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace ac {
 
 typedef int v2i __attribute__((ext_vector_type(2)));
@@ -34,11 +36,20 @@ inline int compute_units() {
   return cus;
 }
 
-// Raises a kernel's dynamic-LDS limit.  Launchers keep the result in a function-local static, so the call is
-// made once per kernel instantiation, safely under concurrent first launches.
+// Raises a kernel's dynamic-LDS limit.
 template <class K>
 inline hipError_t allow_dynamic_lds(K kern, int bytes) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+// The same, once per kernel instantiation: `done` is the launcher's function-local flag.  Only success is
+// remembered; a failure goes back to the caller and the next launch tries again.  Concurrent first launches may
+// both make the call, which is harmless.
+template <class K>
+inline hipError_t allow_dynamic_lds_once(std::atomic<bool>& done, K kern, int bytes) {
+  if (done.load(std::memory_order_acquire)) return hipSuccess;
+  const hipError_t e = allow_dynamic_lds(kern, bytes);
+  if (e == hipSuccess) done.store(true, std::memory_order_release);
+  return e;
 }
 
 // One descriptor serves the int8 GEMM, the int8 implicit-GEMM convolution and
@@ -123,10 +134,13 @@ int choose_tile_bf16(int32_t M, int32_t N, int32_t K);
 // A bigger tile requests each operand fewer times but offers fewer, slower-starting streams; slicing restores the
 // stream count until the traffic of the partial sums outweighs it.  Slices keep at least four K tiles and fit
 // the chip in one round.  The constants are fitted to plan tables measured on this chip, one set per data type.
+// bf16 slices that add into C with atomics make the last bits of the result vary from run to run, so the bf16
+// model cuts K only where that clearly pays (split_margin 0.8); int8 sums are exact in any order (1.0).
 struct SliceModel {
   double stream[4];    // r of the tile codes 64, 128, 192, 256 (bytes/us)
   double ktile_us[4];  // time of one K tile of those kernels
   double slice_fix_us, combine_per_us;
+  double split_margin;  // a cut plan is taken only if its estimate is below this fraction of the best uncut plan's
 };
 void plan_few_tiles(int32_t M, int32_t N, int64_t kbytes, bool may_slice, const SliceModel& model, int* tile, int* splits);
 bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan);

@@ -360,8 +360,8 @@ static inline bool conv_halo_plan(const GemmParams& p, int bm, ConvHaloParams* h
 template <int BM, int NKS>
 static hipError_t launch_conv_halo_nks(const GemmParams& p, const ConvHaloParams& h, size_t lds, hipStream_t stream) {
   auto kern = conv_i8_halo_kernel<BM, NKS>;
-  static const hipError_t configured = allow_dynamic_lds(kern, 160 * 1024);
-  if (configured != hipSuccess) return configured;
+  static std::atomic<bool> configured{false};
+  if (const hipError_t e = allow_dynamic_lds_once(configured, kern, 160 * 1024)) return e;
   const int cus = compute_units();
   const int n_blocks = (p.N + 63) / 64;
   int wgs = cus / n_blocks;

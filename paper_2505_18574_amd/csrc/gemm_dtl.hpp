@@ -666,14 +666,15 @@ template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMOD
 static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
   using G = DtlGeometry<T, BM, BN, WAVES_M, WAVES_N, STAGES, KTB_>;
   auto kern = gemm_dtl_kernel<T, EPI, BM, BN, WAVES_M, WAVES_N, AMODE, STAGES, KTB_, PINGPONG>;
-  static const hipError_t configured = G::LDS_BYTES > 64 * 1024 ? allow_dynamic_lds(kern, G::LDS_BYTES) : hipSuccess;
-  if (configured != hipSuccess) return configured;
+  static std::atomic<bool> configured{G::LDS_BYTES <= 64 * 1024};
+  if (const hipError_t e = allow_dynamic_lds_once(configured, kern, G::LDS_BYTES)) return e;
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const int ntiles = tiles_m * tiles_n;
   // one persistent workgroup per LDS-limited slot of every compute unit
   constexpr int per_cu = (160 * 1024) / (G::LDS_BYTES > 0 ? G::LDS_BYTES : 1);
   int slots = compute_units() * (per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu));
   slots -= slots % 8;
+  if (slots < 8) slots = 8;  // fewer than eight compute units: still a grid, the tile order is a bijection for any size
   const int64_t nwork = (int64_t)ntiles * (p.splits > 1 ? p.splits : 1);
   if (nwork > INT32_MAX) return hipErrorInvalidValue;  // the kernel counts (tile, K slice) items in 32 bits
   const int grid = nwork < slots ? (int)nwork : slots;

@@ -61,21 +61,26 @@ int choose_tile(int32_t M, int32_t N) {
 }
 
 namespace {
+// The plan tables and fits below were measured on the 256 compute units of an MI355X, and the planners are pure host
+// arithmetic (the workspace size they imply must not depend on which device happens to be current): they count
+// rounds and slots for that chip.  On another compute-unit count the plans stay valid and are merely untuned; the
+// launchers size their grids from the device's own count.
+constexpr int PLAN_CUS = 256;
 struct TiledCost { double c0, per_round, per_round_k; };
 struct StationaryCost { double c0, per_k, per_row_tile, per_row_tile_k; };
 // time estimate (us) of a tiled code: bm x bn tiles, per_cu workgroups resident per compute unit
 double tiled_estimate(const TiledCost& c, int bm, int bn, int per_cu, int32_t M, int32_t N, int64_t k128) {
-  const int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn), slots = 256 * per_cu;
+  const int64_t tiles = (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn), slots = PLAN_CUS * per_cu;
   const double rounds = (double)((tiles + slots - 1) / slots);
   return c.c0 + rounds * (c.per_round + c.per_round_k * (double)k128);
 }
 // ... of a weight-stationary code: every column block of 64 gets the same number of persistent workgroups
 double stationary_estimate(const StationaryCost& c, int bm, int32_t M, int32_t N, int64_t k128) {
   const int64_t nblk = (N + 63) / 64, tm = (M + bm - 1) / bm;
-  int64_t wgs = nblk <= 256 ? 256 / nblk : 1;
+  int64_t wgs = nblk <= PLAN_CUS ? PLAN_CUS / nblk : 1;
   if (wgs > tm) wgs = tm;
   if (wgs < 1) wgs = 1;
-  const double per = (double)((tm + wgs - 1) / wgs), rounds = (double)((wgs * nblk + 255) / 256);
+  const double per = (double)((tm + wgs - 1) / wgs), rounds = (double)((wgs * nblk + PLAN_CUS - 1) / PLAN_CUS);
   return c.c0 + rounds * (c.per_k * (double)k128 + c.per_row_tile * per + c.per_row_tile_k * per * (double)k128);
 }
 int cheapest_tiled(const TiledCost (&c)[4], int32_t M, int32_t N, int64_t k128, double* cost) {
@@ -172,7 +177,7 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
     // 64 x 64 workgroup is the cold one (its four 16 KB stages in flight over some 2 us of HBM latency: 32 GB/s;
     // the warm tables gave 60): over eighteen further few-tile shapes the library's choices then take 214 us in
     // sum on operands from HBM against 260 us, and 152 against 158 us on operands from the caches.
-    static const SliceModel model = {{32e3, 45e3, 40e3, 25e3}, {0.066, 0.132, 0.198, 0.24}, 5.0, 4e5};
+    static const SliceModel model = {{32e3, 45e3, 40e3, 25e3}, {0.066, 0.132, 0.198, 0.24}, 5.0, 4e5, 1.0};
     int tile = 64, splits = 1;
     plan_few_tiles(M, N, K, have_workspace, model, &tile, &splits);
     make_plan_i8(K, tile, splits, &plan);
@@ -217,7 +222,8 @@ void plan_few_tiles(int32_t M, int32_t N, int64_t kbytes, bool may_slice, const 
   static const int codes[4] = {64, 128, 192, 256};
   static const int per_cu[4] = {2, 1, 1, 1};  // workgroups of that kernel a compute unit holds (LDS)
   const double once = (double)kbytes * ((double)M + N);
-  double best = 0.0;
+  double best = 0.0, best_uncut = 0.0;
+  int tile_uncut = 64;
   *tile = 64, *splits = 1;
   if (M < 1 || N < 1 || kbytes < 1) return;
   if ((int64_t)((M + 63) / 64) * ((N + 63) / 64) > 512) return;  // more than one round of 64 x 64 tiles: outside the fitted range
@@ -226,9 +232,9 @@ void plan_few_tiles(int32_t M, int32_t N, int64_t kbytes, bool may_slice, const 
     tile_dims(codes[c], &bm, &bn);
     const int ktb = ktb_of_tile(codes[c]);
     const int64_t tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn;
-    const int64_t nkt = (kbytes + ktb - 1) / ktb, slots = 256 * per_cu[c];
+    const int64_t nkt = (kbytes + ktb - 1) / ktb, slots = PLAN_CUS * per_cu[c];
     const double requested = (double)kbytes * ((double)tm * bm * tn + (double)tn * bn * tm);
-    for (int s = 1; s <= 256; s *= 2) {
+    for (int s = 1; s <= PLAN_CUS; s *= 2) {
       const int64_t items = tm * tn * s;
       if (s > 1 && (!may_slice || items > slots || (int64_t)s * 4 > nkt)) break;
       const double rate = (double)(items < slots ? items : slots) * model.stream[c];
@@ -236,8 +242,10 @@ void plan_few_tiles(int32_t M, int32_t N, int64_t kbytes, bool may_slice, const 
       const double serial = (double)((items + slots - 1) / slots) * (double)((nkt + s - 1) / s) * model.ktile_us[c];
       const double est = std::max(mem, serial) + (s > 1 ? model.slice_fix_us + (double)s * M * N / model.combine_per_us : 0.0);
       if ((c == 0 && s == 1) || est < best) best = est, *tile = codes[c], *splits = s;
+      if (s == 1 && (c == 0 || est < best_uncut)) best_uncut = est, tile_uncut = codes[c];
     }
   }
+  if (*splits > 1 && best > model.split_margin * best_uncut) *tile = tile_uncut, *splits = 1;
 }
 
 // Output stage of a split-K launch: sum the K slices, then bias / shift / saturate / ReLU, 4 outputs per thread.

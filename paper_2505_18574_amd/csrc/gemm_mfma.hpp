@@ -626,8 +626,8 @@ template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMOD
 static hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
   using G = TileGeometry<T, BM, BN, WAVES_M, WAVES_N>;
   auto kern = gemm_mfma_kernel<T, EPI, BM, BN, WAVES_M, WAVES_N, AMODE, ALIGNED>;
-  static const hipError_t configured = G::LDS_BYTES > 64 * 1024 ? allow_dynamic_lds(kern, G::LDS_BYTES) : hipSuccess;
-  if (configured != hipSuccess) return configured;
+  static std::atomic<bool> configured{G::LDS_BYTES <= 64 * 1024};
+  if (const hipError_t e = allow_dynamic_lds_once(configured, kern, G::LDS_BYTES)) return e;
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(G::THREADS), G::LDS_BYTES, stream, p, tiles_m, tiles_n);
   return hipGetLastError();

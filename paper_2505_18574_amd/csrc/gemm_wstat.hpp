@@ -284,8 +284,8 @@ template <int BM, int AMODE, int STAGES>
 static hipError_t launch_wstat(const GemmParams& p, hipStream_t stream) {
   using G = WstatGeometry<BM, STAGES>;
   auto kern = gemm_i8_wstat_kernel<BM, AMODE, STAGES>;
-  static const hipError_t configured = allow_dynamic_lds(kern, 160 * 1024);
-  if (configured != hipSuccess) return configured;
+  static std::atomic<bool> configured{false};
+  if (const hipError_t e = allow_dynamic_lds_once(configured, kern, 160 * 1024)) return e;
   const int nkt = (p.K + G::KTB - 1) / G::KTB;
   if (nkt < 1 || nkt > G::MAX_KT) return hipErrorInvalidValue;
   const int cus = compute_units();

@@ -85,8 +85,9 @@ __global__ void __launch_bounds__(256) tinympc_forward_12_4_5_kernel(const TinyM
   float* win = tinympc_lds + wave * 64 * XPITCH;
   // Persistent waves: wave-block k is problems 64 k .. 64 k + 63; a wave takes blocks first, first + stride, ...
   // and requests the inputs of its next block before it computes and stores the current one, so that the reads of
-  // one block travel while the writes of the previous one drain (the wait for those inputs counts the stores
-  // issued after them instead of draining them: vector-memory operations complete in issue order).
+  // one block travel while the writes of the previous one drain (these are ordinary loads and stores, so the waits
+  // are the compiler's own: it counts the stores it issued after the loads instead of draining them, since
+  // vector-memory operations complete in issue order).
   const int64_t nblk = (p.batch + 63) / 64, stride = (int64_t)gridDim.x * 4;
   int64_t blk = (int64_t)blockIdx.x * 4 + wave;
   if (blk >= nblk) return;
@@ -243,11 +244,9 @@ hipError_t launch_tinympc_forward(const TinyMpcParams& p, hipStream_t stream) {
   const bool aligned16 = ((((uintptr_t)p.x0) | ((uintptr_t)p.d) | ((uintptr_t)p.u) | ((uintptr_t)p.x_out)) & 15) == 0;
   if (p.nx == 12 && p.nu == 4 && p.horizon == 5 && aligned16) {
     constexpr int LDS = (4 * 64 * 76 + 12 * 12 + 12 * 4 + 4 * 12) * (int)sizeof(float);  // 78784 bytes
-    static const hipError_t configured = [] {
-      const hipError_t e = allow_dynamic_lds(tinympc_forward_12_4_5_kernel<true>, LDS);
-      return e != hipSuccess ? e : allow_dynamic_lds(tinympc_forward_12_4_5_kernel<false>, LDS);
-    }();
-    if (configured != hipSuccess) return configured;
+    static std::atomic<bool> configured_x{false}, configured_u{false};
+    if (const hipError_t e = allow_dynamic_lds_once(configured_x, tinympc_forward_12_4_5_kernel<true>, LDS)) return e;
+    if (const hipError_t e = allow_dynamic_lds_once(configured_u, tinympc_forward_12_4_5_kernel<false>, LDS)) return e;
     const int cus = compute_units();
     const int64_t wgs = blocks < (int64_t)cus * TINYMPC_WGS_PER_CU ? blocks : (int64_t)cus * TINYMPC_WGS_PER_CU;  // persistent waves
     if (p.x_out) hipLaunchKernelGGL(tinympc_forward_12_4_5_kernel<true>, dim3((unsigned)wgs), dim3(256), LDS, stream, p);

@@ -5,8 +5,8 @@ oracle.  It holds no arithmetic of the operations themselves: only shapes,
 random draws and the float32 -> bfloat16 rounding of input data.
 
 The shapes stand in for the paper's workloads, none of which ships with it:
-ResNet-50 GEMM and convolution layers on the int8 accelerator (Section 4.4.1,
-5.1.2), the 4096^3 GEMM of the GPU study (Appendix A, Table 5) and the
+ResNet-50 GEMM and convolution layers on the int8 accelerator (Sections 4.4.1
+and 4.4.2), the 4096^3 GEMM of the GPU study (Appendix A, Table 5) and the
 12x12 fine-grained linear algebra of the TinyMPC study (Section 4.4.3,
 Appendix D.2).  Values are uniform int8 / int32 / [-1,1) fp32 or N(0,1).
 

@@ -273,3 +273,17 @@ def test_static_entry_refuses_on_the_host():
     assert L.ac_gemm_i8_static(None, 8, None, 8, None, 0, None, 8, 0, 8, 8, 0, 0, None) == ops.AC_OK
     assert ops.ac_gemm_i8_workspace_bytes(1024, 1024, 65536) > ops.AC_STATIC_SCRATCH_BYTES
     assert L.ac_gemm_i8_static(p, 65536, p + 256, 1024, None, 0, p + 512, 1024, 1024, 1024, 65536, 3, 0, None) == ops.AC_ERR_WORKSPACE
+
+
+def test_convolution_sizes_whose_products_would_overflow_are_refused():
+    """A large stride keeps the implicit GEMM tiny while batch, image and channel counts are near 2^31: the input
+    size is refused factor by factor, before any product can leave int64."""
+    L = ops.lib()
+    p = 0x1000  # never dereferenced
+    big = (1 << 29) + 7
+    for Nb, Cin in [(big, big), (1 << 30, 1 << 30), ((1 << 31) - 1, (1 << 31) - 1), (big, 16), (16, big)]:
+        assert L.ac_conv2d_i8(p, p + 256, None, p + 512, Nb, 32767, 32767, Cin, 16, 1, 1, 32767, 0, 0, 0, None, 0, None) == ops.AC_ERR_SHAPE
+    # kernel taps times channels beyond int32
+    assert L.ac_conv2d_i8(p, p + 256, None, p + 512, 1, 30000, 30000, 1 << 20, 16, 30000, 30000, 1, 0, 0, 0, None, 0, None) == ops.AC_ERR_SHAPE
+    # the same geometry at a size that fits is only refused for what it is asked to read (NULL operands), not for its shape
+    assert L.ac_conv2d_i8(None, None, None, p + 512, 2, 32767, 32767, 1, 16, 1, 1, 32767, 0, 0, 0, None, 0, None) == ops.AC_ERR_NULL

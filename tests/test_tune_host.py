@@ -122,3 +122,34 @@ def test_plan_book_reuse_rule(tmp_path):
     path = str(tmp_path / "plans.json")
     book.save(path)
     assert tune.PlanBook.load(path).plans == book.plans
+
+
+def test_tile_tables_agree_with_the_library():
+    """tune.py restates the library's tile codes, K-tile depths and residency limits on the host side: every code,
+    over a sweep of K and split counts, is checked against what the planned entry points accept (empty problems,
+    so nothing is launched and no pointer is read) and against the workspace they ask for."""
+    from paper_2505_18574_amd import ops
+
+    L = ops.lib()
+    codes = list(tune.TILES) + list(tune.WS_TILES) + list(tune.HALO_TILES) + [0, 32, 96, 255, 512]
+    for kind in ("i8", "bf16"):
+        for tile in codes:
+            for K in (16, 64, 128, 640, 1024, 1536, 1552, 2048, 2064, 4096, 8192 + 16):
+                for splits in (1, 2, 3, 8, 16, 33, 64, 65, 1000):
+                    if kind == "i8":
+                        st = L.ac_gemm_i8_planned(None, K, None, 64, None, 0, None, 64, 0, 64, K, 8, 0, None, 0, tile, splits, None)
+                    else:
+                        st = L.ac_gemm_bf16_planned(None, K, None, 64, None, 64, 0, 64, K, 1.0, 0.0, None, 0, tile, splits, None)
+                    # on an empty problem only the plan itself can be refused; the patch kernel is a convolution kernel
+                    want = tune.valid(kind, 0, 64, K, (tile, splits))
+                    assert (st == ops.AC_OK) == want, (kind, tile, K, splits, st)
+                    assert st in (ops.AC_OK, ops.AC_ERR_PLAN)
+                    if want and tile in tune.TILES:
+                        t, s = tune.normalise(kind, K, (tile, splits))
+                        M, N = 192, 128
+                        fn = ops.ac_gemm_i8_planned_workspace_bytes if kind == "i8" else ops.ac_gemm_bf16_planned_workspace_bytes
+                        assert fn(M, N, K, tile, splits) == (s * M * N * 4 if s > 1 else 0), (kind, tile, K, splits)
+    # the convolution entry point takes the patch-kernel codes and refuses a K split of them
+    for tile in tune.HALO_TILES:
+        assert L.ac_conv2d_i8_planned(None, None, None, None, 0, 56, 56, 64, 64, 3, 3, 1, 1, 9, 1, None, 0, tile, 1, None) == ops.AC_OK
+        assert L.ac_conv2d_i8_planned(None, None, None, None, 0, 56, 56, 64, 64, 3, 3, 1, 1, 9, 1, None, 0, tile, 2, None) == ops.AC_ERR_PLAN

@@ -263,6 +263,11 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           B stays in LDS for all of K while tiles of A stream past it, the arrangement of the paper's best
  *           accelerator schedule, Appendix D.1).  It takes splits == 1, operands that qualify for the
  *           direct-to-LDS kernels (below), no bias or a bias row (bias_ld == 0), and K <= 1536 (320) / 2048 (160).
+ *           ac_gemm_i8_planned only: 32 = one wave per 32 x 32 output tile, four independent waves per
+ *           workgroup and no barrier anywhere, for the accelerator-sized layers of Section 4.4.1 whose whole
+ *           launch lasts a few microseconds.  It takes splits == 1, operands that qualify for the direct-to-LDS
+ *           kernels, and K a multiple of 64, at least 64.  ac_gemm_i8 picks it for such operands when K <= 640
+ *           and the output has at most 1024 tiles of 32 x 32.
  *           ac_conv2d_i8_planned only: 321 / 161 = the convolution patch kernel with units of 256 / 128 output
  *           pixels: the weights of a 64-channel block AND the image patch a unit needs are both held in LDS, so
  *           every input pixel is fetched once per unit instead of once per kernel tap.  It takes splits == 1,
@@ -282,7 +287,7 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           slice adds alpha * (its product) with fp32 atomic adds, in no fixed order (slow for large M * N).
  *           Workspace rules as for ac_gemm_i8: 16-byte aligned, large enough, else AC_ERR_WORKSPACE.
  *   AC_ERR_PLAN: unknown tile code, splits < 1 or larger than the number of K tiles, or splits > 1 / a
- *           weight-stationary tile with operands that do not qualify.  Everything else as for the unplanned call.
+ *           weight-stationary tile / tile 32 with operands that do not qualify.  Everything else as for the unplanned call.
  * ac_conv2d_i8_planned is ac_conv2d_i8 with the tile and K split of its implicit GEMM (M = Nb OH OW, N = Cout,
  *           K = KH KW Cin) named by the caller; "qualify" there means 16-byte aligned in / w, Cin and Cout
  *           multiples of 16, out 4-byte aligned; workspace size from ac_gemm_i8_planned_workspace_bytes(M, N, K, ...).

@@ -127,6 +127,7 @@ ac_status gemm_i8_entry(const int8_t* A, int64_t lda, const int8_t* B, int64_t l
   if (planned && plan.splits > 1 && !ac::gemm_i8_fast_path(p)) return AC_ERR_PLAN;
   if (planned && (tile == 320 || tile == 160) && !(ac::gemm_i8_fast_path(p) && ac::wstat_eligible(p, tile))) return AC_ERR_PLAN;
   if (planned && (tile == 321 || tile == 161)) return AC_ERR_PLAN;  // the patch kernel is a convolution kernel
+  if (planned && tile == 32 && !ac::gemm_i8_fast_path(p)) return AC_ERR_PLAN;
   if (M == 0 || N == 0) return AC_OK;
   if (!C || (K > 0 && (!A || !B))) return AC_ERR_NULL;
   if ((const void*)C == (const void*)A || (const void*)C == (const void*)B || (const void*)C == (const void*)bias)
@@ -273,6 +274,7 @@ static ac_status conv2d_i8_entry(const int8_t* in, const int8_t* w, const int32_
     // operands, channel counts in multiples of 16, at most 32 kernel taps
     const bool fast = ac::conv_i8_fast_path(p);
     const bool ws = tile == 320 || tile == 160, patch = tile == 321 || tile == 161;
+    if (tile == 32) return AC_ERR_PLAN;  // the one-wave-per-tile kernel is a GEMM kernel
     if ((plan.splits > 1 || ws || patch) && !fast) return AC_ERR_PLAN;
     if (ws && !ac::wstat_eligible(p, tile)) return AC_ERR_PLAN;
     if (patch && !ac::conv_halo_eligible(p, tile)) return AC_ERR_PLAN;

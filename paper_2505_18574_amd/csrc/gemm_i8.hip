@@ -1,5 +1,6 @@
 // int8 GEMM / implicit-GEMM convolution with the accelerator output stage: tile selection, split-K and launch.
 #include "conv_halo.hpp"
+#include "gemm_small.hpp"
 #include "gemm_wstat.hpp"
 
 #include <algorithm>
@@ -33,10 +34,11 @@ hipError_t static_scratch(void** ptr) {
   return hipSuccess;
 }
 
-static int ktb_of_tile(int tile) { return tile == 256 ? 64 : 128; }  // K bytes per tile of the kernel behind a tile code
+static int ktb_of_tile(int tile) { return tile == 256 || tile == 32 ? 64 : 128; }  // K bytes per tile of the kernel behind a tile code
 
 bool tile_dims(int32_t tile, int* bm, int* bn) {
   switch (tile) {
+    case 32: *bm = *bn = 32; return true;    // one wave per tile (gemm_small.hpp), int8 GEMM only
     case 64: *bm = *bn = 64; return true;
     case 128: *bm = *bn = 128; return true;
     case 192: *bm = 256; *bn = 128; return true;
@@ -160,6 +162,13 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace) {
   plan.tile = 64;
   plan.ktb = ktb_of_tile(plan.tile);
   if (M < 1 || N < 1) return plan;
+  // Launches of a few microseconds: up to one round of the one-wave-per-tile kernel (four 32 x 32 tiles per compute
+  // unit) and a K short enough that its per-tile loop does not matter.  A sweep of 14 outputs x 9 depths on this
+  // chip: 3-20 % faster than the 64 x 64 tiles for every K up to 640, level at 768, 13-22 % slower at 1024.
+  if (K >= SMALL_KTB && K % SMALL_KTB == 0 && K <= 640 && (int64_t)((M + 31) / 32) * ((N + 31) / 32) <= 4 * PLAN_CUS) {
+    make_plan_i8(K, 32, 1, &plan);
+    return plan;
+  }
   if (many_tiles(M, N, K)) {
     plan.tile = choose_tile_i8(M, N, K, true);
     plan.ktb = ktb_of_tile(plan.tile);
@@ -209,12 +218,13 @@ bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
   int bm, bn;
   if (!tile_dims(tile, &bm, &bn)) return false;
   if ((wstat_tile_rows(tile, &bm) || halo_tile_rows(tile, &bm)) && splits != 1) return false;  // these kernels keep all of K resident
+  if (tile == 32 && (splits != 1 || K < SMALL_KTB || K % SMALL_KTB != 0)) return false;            // whole K tiles of 64 bytes, never cut
   return make_plan(K, tile, ktb_of_tile(tile), splits, plan);
 }
 
 bool make_plan_bf16(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
   int bm, bn;
-  if (!tile_dims(tile, &bm, &bn) || wstat_tile_rows(tile, &bm) || halo_tile_rows(tile, &bm)) return false;
+  if (!tile_dims(tile, &bm, &bn) || tile == 32 || wstat_tile_rows(tile, &bm) || halo_tile_rows(tile, &bm)) return false;
   return make_plan((int64_t)K * 2, tile, ktb_of_tile(tile), splits, plan);
 }
 
@@ -275,6 +285,8 @@ template <int AMODE>
 hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast, const GemmPlan* forced) {
   GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr);
   int ws_bm;
+  // operands the one-wave-per-tile kernel does not take (and every convolution): the 64 x 64 tiles, uncut as planned
+  if (!forced && plan.tile == 32 && !(AMODE == 0 && fast && small_i8_eligible(p))) make_plan_i8(p.K, 64, 1, &plan);
   if (!forced && wstat_tile_rows(plan.tile, &ws_bm) && !(fast && wstat_eligible(p, plan.tile))) {
     plan.tile = choose_tile_i8(p.M, p.N, p.K, false);  // operands the weight-stationary kernel does not take: the tiled kernels
     plan.ktb = ktb_of_tile(plan.tile);
@@ -285,6 +297,10 @@ hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast
   if (wstat_tile_rows(plan.tile, &ws_bm)) {
     if (!fast || !wstat_eligible(p, plan.tile)) return hipErrorInvalidValue;
     return launch_wstat_tile<AMODE>(plan.tile, p, stream);
+  }
+  if (plan.tile == 32) {
+    if (AMODE != 0 || !fast || !small_i8_eligible(p)) return hipErrorInvalidValue;
+    return launch_small_i8(p, stream);
   }
   if (halo_tile_rows(plan.tile, &ws_bm)) {
     ConvHaloParams h;
@@ -392,7 +408,7 @@ hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmP
     // weight-stationary one, whose gather loses to both (28 x 28 x 128 -> 128, 32 images: 13.9 us against 10.2)
     GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, p.partial != nullptr);
     int ws_bm;
-    if (wstat_tile_rows(plan.tile, &ws_bm)) make_plan_i8(p.K, choose_tile(p.M, p.N), 1, &plan);  // unsplit: no workspace needed
+    if (wstat_tile_rows(plan.tile, &ws_bm) || plan.tile == 32) make_plan_i8(p.K, choose_tile(p.M, p.N), 1, &plan);  // unsplit: no workspace needed
     return dispatch_i8<1>(p, stream, aligned, fast, &plan);
   }
   return dispatch_i8<1>(p, stream, aligned, fast, forced);

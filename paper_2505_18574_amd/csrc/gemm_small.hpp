@@ -1,0 +1,155 @@
+// int8 GEMM for launches that last a few microseconds (the accelerator-sized layers of Section 4.4.1): one wave
+// per 32 x 32 output tile, four independent waves per workgroup.
+//
+// At that size a launch is a chain of latencies, not of throughput: a workgroup of the tiled kernels spends
+// about 1.3 us in some 500 instructions of addressing before its first operand arrives (a wave issues one
+// instruction every 4-5 cycles), 0.5 us in a K loop with two barriers per tile and 0.7 us in the output stage.
+// Here a wave owns its tile alone, so there is no barrier anywhere and no tile-order, K-slice or persistence
+// logic ahead of the first load; the operands stream through a ring of private LDS stages (64 or 128 bytes of K
+// each) and the fragments of the next K tile are read while the MFMAs of the current one run.
+//
+// Operands as for the direct-to-LDS kernels (16-byte aligned, K and N in whole 16-byte chunks), and K a multiple
+// of 64; anything else stays on the tiled kernels.
+#pragma once
+#include "gemm_dtl.hpp"
+
+namespace ac {
+
+constexpr int SMALL_WAVES = 4;   // independent waves (tiles) per workgroup
+constexpr int SMALL_KTB = 64;    // K bytes per stage; 128 when K is a multiple of that (half the per-byte bookkeeping)
+constexpr int SMALL_LDS = 24576; // LDS per wave: six stages of 4 KB or three of 8 KB
+
+template <int KTB>
+__global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const GemmParams p, const int tiles_n, const int ntiles, const unsigned tn_magic) {
+  using T = TypeI8;
+  using EPI = EpilogueI8;
+  constexpr int S = SMALL_LDS / (64 * KTB);
+  using G = DtlGeometry<T, 32, 32, 1, 1, S, KTB>;
+  constexpr int NA = G::A_INSTR, NB = G::B_INSTR, KS = G::KSTEPS;
+  static_assert(NA == KTB / 32 && NB == KTB / 32 && KS == KTB / 32 && G::TM == 1 && G::TN == 1 && G::STAGE == 64 * KTB && S >= 3, "geometry");
+  constexpr int PER_TILE = NA + NB;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int tile = blockIdx.x * SMALL_WAVES + wave;
+  if (tile >= ntiles) return;  // whole waves leave; no wave of this kernel ever waits for another
+  const int tm = tn_magic ? (int)__umulhi((unsigned)tile, tn_magic) : tile / tiles_n;
+  const int tn = tile - tm * tiles_n;
+  const int m0 = tm * 32, n0 = tn * 32;
+  unsigned char* win = smem + wave * (S * G::STAGE);
+  const unsigned lds0 = (unsigned)(uintptr_t)AC_LDS(unsigned char, win);
+
+  // source offsets of the four loads of a K tile (same lane roles as gemm_dtl_kernel, with one wave)
+  unsigned a_voff[NA], b_voff[NB];
+#pragma unroll
+  for (int i = 0; i < NA; i++) {
+    const int row = i * G::A_ROWS_PER_INSTR + lane / G::A_SPR;
+    const int a_chunk = (lane % G::A_SPR) ^ G::a_xor(row);
+    const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
+    a_voff[i] = (unsigned)rclamp * (unsigned)p.lda + a_chunk * 16;
+    const int brow = i * G::B_ROWS_PER_INSTR + lane / G::B_SPR;
+    const int slot = lane % G::B_SPR;
+    b_voff[i] = (unsigned)brow * (unsigned)p.ldb + (n0 + slot * 16 < p.N ? slot * 16 : 0);
+  }
+  const unsigned char* a_base = (const unsigned char*)p.A + (int64_t)m0 * p.lda;
+  const unsigned char* b_base = (const unsigned char*)p.B + n0;
+  const int64_t b_step = (int64_t)G::BK * p.ldb;
+  const int nkt = p.K / KTB;
+
+  // the bias row is requested ahead of the operand loads, so that the counted waits on those see nothing else
+  EPI::Pre pre;
+  EPI::prefetch(p, n0, lane, pre);
+
+  int wr = 0;  // stage that the next requested tile goes to
+  auto issue = [&]() {
+    const unsigned st = lds0 + wr * G::STAGE;
+#pragma unroll
+    for (int i = 0; i < NA; i++) load_to_lds16_so(a_base, a_voff[i], st + i * 1024);
+#pragma unroll
+    for (int i = 0; i < NB; i++) load_to_lds16_so(b_base, b_voff[i], st + G::A_BYTES + i * 1024);
+    a_base += KTB;
+    b_base += b_step;
+    wr = wr + 1 == S ? 0 : wr + 1;
+  };
+#pragma unroll
+  for (int s = 0; s < S - 1; s++)
+    if (s < nkt) issue();
+
+  // fragment addresses: the lane's A row is lane & 31, its 16 K-bytes of K-step ks sit in chunk 2 ks + lane / 32
+  const int a_swz = G::a_xor(lane & 31);
+  int a_fo[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) a_fo[ks] = (lane & 31) * G::KTB + (((2 * ks + (lane >> 5)) ^ a_swz) << 4);
+  const int b_fo = G::A_BYTES + dtl_col_off<T, G::B_ROW>((lane >> 5) * 16, 0, lane);
+  constexpr int KS_B = 32 * G::B_ROW;  // bytes between the B rows of consecutive K-steps
+
+  struct Frag {
+    v4i a[KS], b[KS];
+  };
+  int rd = 0;  // stage of the next tile to be read
+  auto read_frags = [&](Frag& f) {
+    const unsigned char* st = win + rd * G::STAGE;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      f.a[ks] = *(const v4i*)(st + a_fo[ks]);
+      f.b[ks] = dtl_read_col_at<T, G::B_ROW>(st + b_fo + ks * KS_B);
+    }
+    rd = rd + 1 == S ? 0 : rd + 1;
+  };
+
+  typename T::accv acc = T::zero();
+  Frag f[2];
+  if (nkt > 0) {
+    if (S - 1 <= nkt) wait_vm<(S - 2) * PER_TILE>();
+    else wait_vm<0>();
+    read_frags(f[0]);
+  }
+  // Tile kt: request tile kt + S - 1 into the stage tile kt - 1 has left (its fragments were waited for before its
+  // MFMAs), wait for this wave's loads of tile kt + 1, read its fragments, then the MFMAs of tile kt.
+  auto step = [&](int kt, Frag& cur, Frag& nxt) {
+    if (kt + 1 < nkt) {
+      if (kt + S - 1 < nkt) {
+        issue();
+        wait_vm<(S - 2) * PER_TILE>();
+      } else {
+        wait_vm<0>();  // the last S - 2 tiles: everything that is still in flight
+      }
+      read_frags(nxt);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) acc = T::mfma(cur.b[ks], cur.a[ks], acc);  // EPI::SWAP operand order
+  };
+  int kt = 0;
+  for (; kt + 1 < nkt; kt += 2) {
+    step(kt, f[0], f[1]);
+    step(kt + 1, f[1], f[0]);
+  }
+  if (kt < nkt) step(kt, f[0], f[1]);
+
+  EPI::tile(p, m0, n0, acc, lane, 0, pre);
+}
+
+// Whether the small kernel can run p (a GEMM on direct-to-LDS operands, see gemm_i8_fast_path, checked by the caller).
+static inline bool small_i8_eligible(const GemmParams& p) {
+  const int64_t tiles = (int64_t)((p.M + 31) / 32) * ((p.N + 31) / 32);
+  return p.K >= SMALL_KTB && p.K % SMALL_KTB == 0 && tiles <= INT32_MAX && (p.splits <= 1);
+}
+
+template <int KTB>
+static hipError_t launch_small_i8_ktb(const GemmParams& p, hipStream_t stream) {
+  constexpr int LDS = SMALL_WAVES * SMALL_LDS;
+  static std::atomic<bool> configured{false};
+  if (const hipError_t e = allow_dynamic_lds_once(configured, gemm_i8_small_kernel<KTB>, LDS)) return e;
+  const int tiles_m = (p.M + 31) / 32, tiles_n = (p.N + 31) / 32;
+  const int ntiles = tiles_m * tiles_n;
+  const unsigned tn_magic = (uint64_t)ntiles * (unsigned)tiles_n < (1ull << 32) ? FastDiv::make((unsigned)tiles_n).magic : 0u;
+  hipLaunchKernelGGL(gemm_i8_small_kernel<KTB>, dim3((unsigned)((ntiles + SMALL_WAVES - 1) / SMALL_WAVES)), dim3(64 * SMALL_WAVES), LDS, stream, p,
+                     tiles_n, ntiles, tn_magic);
+  return hipGetLastError();
+}
+
+static hipError_t launch_small_i8(const GemmParams& p, hipStream_t stream) {
+  return p.K % 128 == 0 ? launch_small_i8_ktb<128>(p, stream) : launch_small_i8_ktb<64>(p, stream);
+}
+
+}  // namespace ac

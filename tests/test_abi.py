@@ -161,7 +161,11 @@ def test_transposed_entry_validation_without_gpu():
 def test_auto_plans_are_host_arithmetic():
     # the benchmark shapes: big square problems take the 256 tile; narrow ones fall back to 64
     assert ops.ac_gemm_bf16_auto_plan(4096, 4096, 4096) == (256, 1)
-    assert ops.ac_gemm_i8_auto_plan(3136, 64, 576) == (64, 1)
+    assert ops.ac_gemm_i8_auto_plan(3136, 64, 576) == (32, 1)     # a few microseconds, short K: one wave per 32 x 32 tile
+    assert ops.ac_gemm_i8_auto_plan(256, 256, 256) == (32, 1) and ops.ac_gemm_i8_auto_plan(3136, 256, 64) == (32, 1)
+    assert ops.ac_gemm_i8_auto_plan(512, 768, 768) == (64, 1)     # K beyond 640: the 64 x 64 tiles
+    assert ops.ac_gemm_i8_auto_plan(3136, 64, 600) == (64, 1)     # K not in whole 64-byte tiles
+    assert ops.ac_gemm_i8_auto_plan(8192, 256, 64) == (64, 1) or ops.ac_gemm_i8_auto_plan(8192, 256, 64)[0] != 32  # more than one round of small tiles
     assert ops.ac_gemm_i8_auto_plan(65536, 64, 576) == (320, 1)   # long, narrow, short K: weight-stationary kernel
     assert ops.ac_gemm_i8_auto_plan(65536, 64, 4096) == (64, 1)   # K too deep to stay resident
     # few output tiles: tile and K slices come from one cost estimate; slicing needs the workspace and is priced at
@@ -191,7 +195,7 @@ def test_auto_plans_are_host_arithmetic():
     assert ops.ac_gemm_bf16_auto_plan(32768, 32768, 32) == (256, 1)      # beyond the fitted range: the big tile
     for M, N, K in [(5000, 3000, 100), (700, 9000, 3000), (100000, 64, 16), (64, 100000, 4000), (12345, 6789, 1011)]:
         assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[1] == 1 and ops.ac_gemm_bf16_auto_plan(M, N, K)[1] == 1
-        assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[0] in (64, 128, 192, 256, 160, 320)
+        assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[0] in (32, 64, 128, 192, 256, 160, 320)
         assert ops.ac_gemm_bf16_auto_plan(M, N, K)[0] in (64, 128, 192, 256)
         if K > 2048:
             assert ops.ac_gemm_i8_auto_plan(M, N, K, False)[0] not in (160, 320)
@@ -220,7 +224,7 @@ def test_workspace_size_matches_the_automatic_plan():
     for _ in range(400):
         M, N, K = rng.choice(dims), rng.choice(dims), rng.choice(ks)
         tile, splits = ops.ac_gemm_i8_auto_plan(M, N, K, True)
-        assert tile in (64, 128, 192, 256, 160, 320) and splits >= 1
+        assert tile in (32, 64, 128, 192, 256, 160, 320) and splits >= 1
         need = ops.ac_gemm_i8_workspace_bytes(M, N, K)
         assert need == ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, tile, splits)
         assert (need > 0) == (splits > 1)

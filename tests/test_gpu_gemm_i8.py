@@ -178,3 +178,31 @@ def test_raw_accumulator_output(M, N, K):
     ops.ac_gemm_i8_acc32(dev(A), dev(B), None, C)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(host(C8), np.clip(host(C), -128, 127).astype(np.int8))
+
+
+def test_cut_k_launch_replayed_from_a_graph():
+    """A launch that cuts K (slices into the workspace, then the combining kernel) captured in a graph and replayed:
+    three replays on changing inputs, with eager launches of other cut shapes in between, each against the oracle."""
+    M, N, K = 49, 2048, 4608
+    assert ops.ac_gemm_i8_auto_plan(M, N, K, True)[1] > 1
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=424242)
+    dA, dB, dbias = dev(A), dev(B), dev(bias)
+    C = torch.full((M, N), 77, dtype=torch.int8, device="cuda")
+    ws = torch.full((ops.ac_gemm_i8_workspace_bytes(M, N, K),), 0xC3, dtype=torch.uint8, device="cuda")
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        ops.ac_gemm_i8(dA, dB, dbias, C, 10, ops.AC_ACT_RELU, workspace=ws)  # first launch outside the capture
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            ops.ac_gemm_i8(dA, dB, dbias, C, 10, ops.AC_ACT_RELU, workspace=ws)
+        for rep in range(3):
+            A2 = np.roll(A, rep + 1, axis=0)
+            dA.copy_(dev(A2))
+            C.fill_(55)
+            torch.cuda.synchronize()
+            g.replay()
+            s.synchronize()
+            np.testing.assert_array_equal(host(C), oracle.gemm_i8(A2, B, bias, 10, ops.AC_ACT_RELU))
+            # eager launches of other cut shapes share nothing with the captured one
+            check(*inputs.gemm_i8_inputs(16, 512, 4096, seed=rep), 9, ops.AC_ACT_NONE, workspace=True)

@@ -1,0 +1,118 @@
+"""GPU parity of the one-wave-per-tile int8 kernel (tile code 32) against the CPU oracle, bit for bit.
+
+Reached through the planned entry point, so that every shape here runs on that kernel whatever the library's own
+choice would be, and through ac_gemm_i8 on the shapes for which the library picks it: K of one to many stages of the
+private LDS ring (64- and 128-byte stages), ragged M and N, workgroups whose last waves have no tile, every
+output-stage variant.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import dev, host
+from paper_2505_18574_amd import inputs, ops
+
+pytestmark = pytest.mark.gpu
+
+
+def planned_check(A, B, bias, shift, act):
+    M, N = A.shape[0], B.shape[1]
+    C = torch.full((M, N), 77, dtype=torch.int8, device="cuda")
+    ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, shift, act, 32, 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C), oracle.gemm_i8(A, B, bias, shift, act))
+
+
+# K from one stage to well past the ring (3 or 6 stages), odd and even stage counts, both stage widths
+@pytest.mark.parametrize("K", [64, 128, 192, 256, 320, 384, 448, 512, 576, 640, 704, 768, 1024, 1088, 2048, 4160])
+def test_k_depths(K):
+    A, B, bias = inputs.gemm_i8_inputs(100, 80, K, seed=K)
+    planned_check(A, B, bias, 10, ops.AC_ACT_RELU)
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (1, 16, 64), (31, 16, 128), (32, 32, 64), (33, 48, 192), (65, 80, 320), (256, 256, 256), (257, 272, 448),
+    (3136, 64, 576), (3136, 256, 64), (784, 128, 1152), (49, 2048, 512), (1000, 16, 640),
+    (5000, 1008, 128),   # 4 945 tiles: far more workgroups than compute units
+])
+def test_shapes(M, N, K):
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + N + K)
+    planned_check(A, B, bias, 9, ops.AC_ACT_RELU)
+    planned_check(A, B, None, 6, ops.AC_ACT_NONE)
+
+
+@pytest.mark.parametrize("shift", [0, 1, 5, 8, 16, 23, 24, 31])
+@pytest.mark.parametrize("act", [0, 1])
+def test_shifts_and_activation(shift, act):
+    A, B, bias = inputs.gemm_i8_inputs(100, 96, 192, seed=shift, bias_bits=30 if shift > 16 else 15)
+    planned_check(A, B, bias, shift, act)
+
+
+def test_bias_matrix_ties_and_extreme_accumulators():
+    A, B, bias = inputs.gemm_i8_inputs(150, 144, 128, seed=5, bias_matrix=True)
+    planned_check(A, B, bias, 8, 1)
+    for shift in (1, 2, 3, 4):  # small sums: rounding, not saturation, decides
+        A, B, bias = inputs.gemm_i8_inputs(100, 96, 64, seed=shift, lo=-4, hi=4, bias_bits=4)
+        planned_check(A, B, bias, shift, 0)
+    # acc = K + bias sweeps every multiple of half a step
+    M, N, K, shift = 64, 256, 64, 4
+    A = np.ones((M, K), np.int8)
+    B = np.ones((K, N), np.int8)
+    bias = ((np.arange(N, dtype=np.int64) - 128) * 8 - K).astype(np.int32)
+    planned_check(A, B, bias, shift, 0)
+    # sums at the ends of int32: the rounding add must not wrap
+    A = np.zeros((M, K), np.int8)
+    edge = np.array([2**31 - 1, 2**31 - 2, -(2**31), -(2**31) + 1, 2**30, 2**30 - 1, -(2**30), -(2**30) - 1], dtype=np.int64)
+    bias = np.resize(edge, N).astype(np.int32)
+    for shift in (1, 8, 23, 24, 31):
+        planned_check(A, B, bias, shift, 0)
+
+
+def test_strided_operands_and_guard_bands():
+    """Row pitches beyond the row length, and nothing written outside the M x N window of C."""
+    M, N, K = 70, 48, 192
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=11)
+    Ap = torch.zeros((M, K + 64), dtype=torch.int8, device="cuda")
+    Bp = torch.zeros((K, N + 32), dtype=torch.int8, device="cuda")
+    Ap[:, :K] = dev(A)
+    Bp[:, :N] = dev(B)
+    Cp = torch.full((M + 2, N + 16), 55, dtype=torch.int8, device="cuda")
+    ops.ac_gemm_i8_planned(Ap[:, :K], Bp[:, :N], dev(bias), Cp[1:M + 1, :N], 9, 1, 32, 1)
+    torch.cuda.synchronize()
+    got = host(Cp)
+    np.testing.assert_array_equal(got[1:M + 1, :N], oracle.gemm_i8(A, B, bias, 9, 1))
+    assert (got[0] == 55).all() and (got[M + 1] == 55).all() and (got[:, N:] == 55).all()
+
+
+def test_refusals_and_fallbacks():
+    A, B, bias = inputs.gemm_i8_inputs(64, 64, 96, seed=3)
+    C = torch.zeros((64, 64), dtype=torch.int8, device="cuda")
+    with pytest.raises(ops.AcError) as e:  # K not in whole 64-byte stages
+        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, 8, 0, 32, 1)
+    assert e.value.status == ops.AC_ERR_PLAN
+    A, B, bias = inputs.gemm_i8_inputs(64, 64, 128, seed=3)
+    with pytest.raises(ops.AcError) as e:  # never cut
+        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, 8, 0, 32, 2)
+    assert e.value.status == ops.AC_ERR_PLAN
+    with pytest.raises(ops.AcError) as e:  # operands the direct-to-LDS kernels do not take (N = 60)
+        ops.ac_gemm_i8_planned(dev(A), dev(B[:, :60].copy()), dev(bias[:60].copy()), C[:, :60].contiguous(), 8, 0, 32, 1)
+    assert e.value.status == ops.AC_ERR_PLAN
+    # ac_gemm_i8 plans tile 32 for this size; with an unaligned A it must still run (on the generic kernel) and agree
+    assert ops.ac_gemm_i8_auto_plan(64, 64, 128) == (32, 1)
+    Ap = torch.zeros((64, 129), dtype=torch.int8, device="cuda")
+    Ap[:, :128] = dev(A)
+    ops.ac_gemm_i8(Ap[:, :128], dev(B), dev(bias), C, 8, 0)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C), oracle.gemm_i8(A, B, bias, 8, 0))
+
+
+def test_library_choice_runs_it():
+    """Shapes of the accelerator-sized layers (Section 4.4.1) through ac_gemm_i8 itself."""
+    for M, N, K in [(256, 256, 256), (3136, 64, 576), (3136, 256, 64), (512, 512, 512), (128, 128, 128)]:
+        assert ops.ac_gemm_i8_auto_plan(M, N, K) == (32, 1)
+        A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + K)
+        C = torch.full((M, N), 77, dtype=torch.int8, device="cuda")
+        ops.ac_gemm_i8(dev(A), dev(B), dev(bias), C, 9, 1)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(C), oracle.gemm_i8(A, B, bias, 9, 1))

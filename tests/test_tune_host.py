@@ -45,7 +45,11 @@ def test_convolution_plan_space():
     # a convolution adds the patch kernel's two unit sizes to the int8 plan space; they never split K
     M, N, K = 8 * 56 * 56, 64, 576
     plans = tune.all_plans("conv", M, N, K)
-    assert set(tune.all_plans("i8", M, N, K)) | {(161, 1), (321, 1)} == set(plans)
+    # ... and has no one-wave-per-tile kernel, which is a GEMM kernel
+    assert (set(tune.all_plans("i8", M, N, K)) - {(32, 1)}) | {(161, 1), (321, 1)} == set(plans)
+    assert tune.valid("i8", M, N, K, (32, 1)) and not tune.valid("conv", M, N, K, (32, 1)) and not tune.valid("bf16", M, N, K, (32, 1))
+    assert not tune.valid("i8", M, N, K, (32, 2)) and not tune.valid("i8", M, N, 600, (32, 1)) and not tune.valid("i8", M, N, 32, (32, 1))
+    assert (32, 1) in tune.neighbours("i8", M, N, K, (64, 1)) and set(tune.neighbours("i8", M, N, K, (32, 1))) == {(64, 1), (64, 2)}
     assert tune.valid("conv", M, N, K, (321, 1)) and not tune.valid("conv", M, N, K, (321, 2))
     assert not tune.valid("i8", M, N, K, (321, 1)) and not tune.valid("bf16", M, N, K, (161, 1))
     seeds = tune.seed_plans("conv", M, N, K, (64, 1))
@@ -71,7 +75,7 @@ class FakeProblem(tune._Problem):
 
 
 def test_beam_keeps_correct_and_faster_candidates_only():
-    cost = lambda p: {64: 30.0, 128: 20.0, 192: 35.0, 256: 40.0, 160: 50.0, 320: 60.0}[p[0]] / (1 + 0.5 * (p[1] > 1)) + p[1]
+    cost = lambda p: {32: 45.0, 64: 30.0, 128: 20.0, 192: 35.0, 256: 40.0, 160: 50.0, 320: 60.0}[p[0]] / (1 + 0.5 * (p[1] > 1)) + p[1]
     # (128, 2) would be the fastest plan but produces a wrong result: it must never be chosen
     prob = FakeProblem(cost, wrong={(128, 2)})
     res = tune._search(prob, None, [(64, 1)], beam=2, iterations=6, exhaustive=False)

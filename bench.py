@@ -10,8 +10,9 @@ so that host launch overhead does not hide the kernels.
 Prints ONE JSON line: whole-step throughput, per-workload rates and roofline fractions, the roofline
 record of the dominant kernel, and the CPU oracle timed on a bounded sample of the same workloads.
 
-Per workload: `ms_in_pass` is the latency of a single eager launch inside a pass (device events around it:
-includes the host's launch gap, which dominates the microsecond-sized int8 kernels); `ms_isolated_warm` /
+Per workload: `ms_in_pass` is the duration of a single eager launch inside a pass (device events around it; the
+pass is enqueued while a spin kernel holds the stream, so the host's launch gap is not in it, the event pair's
+own few microseconds are); `ms_isolated_warm` /
 `ms_isolated_warm_min` are the median / minimum over five timed regions of at least 20 ms of back-to-back
 launches of that workload on the same buffers replayed from a HIP graph (operands stay in the caches);
 `ms_isolated_cold` / `ms_isolated_cold_min` are the same over launches that rotate through copies of the
@@ -132,13 +133,36 @@ def time_region(fn, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def hold_stream(stream, ms):
+    """Keeps `stream` busy for about `ms` milliseconds (a spin kernel), so that the host can enqueue what follows
+    before the device reaches it.  Calibrated once against device events."""
+    if hold_stream.cycles_per_ms is None:
+        probe = 2_000_000
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            torch.cuda._sleep(probe)
+            e0.record(stream)
+            torch.cuda._sleep(probe)
+            e1.record(stream)
+            stream.synchronize()
+        hold_stream.cycles_per_ms = probe / max(e0.elapsed_time(e1), 1e-3)
+    with torch.cuda.stream(stream):
+        torch.cuda._sleep(int(ms * hold_stream.cycles_per_ms))
+
+
+hold_stream.cycles_per_ms = None
+
+
 def per_kernel_times(wl, steps, stream):
-    """Average duration of each launch inside the pass, from HIP events recorded on the launch stream."""
+    """Average duration of each launch inside the pass, from HIP events recorded on the launch stream.  Every pass
+    is enqueued behind a spin kernel that lasts longer than the host needs to enqueue it, so the interval between
+    two events is the launch between them (plus the event pair's own few microseconds), not the host's launch gap."""
     n = len(wl)
     acc = np.zeros(n)
     with torch.cuda.stream(stream):
         for _ in range(steps):
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            hold_stream(stream, 2.0)
             ev[0].record(stream)
             for i, w in enumerate(wl):
                 w.launch()

@@ -97,8 +97,10 @@ ac_status ac_gemm_i8(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                      int32_t M, int32_t N, int32_t K, int32_t shift, int32_t act,
                      void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace with which ac_gemm_i8 may split K for this shape
- * (0 when it would not split).  Pure host arithmetic. */
+/* Bytes of workspace with which ac_gemm_i8 (or ac_conv2d_i8 with this implicit-GEMM
+ * shape) may split K (0 when no launch of the shape would split; operands that
+ * run on the one-wave-per-tile kernel, tile code 32 below, leave it untouched).
+ * Pure host arithmetic. */
 size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K);
 
 /*
@@ -266,8 +268,9 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           ac_gemm_i8_planned only: 32 = one wave per 32 x 32 output tile, four independent waves per
  *           workgroup and no barrier anywhere, for the accelerator-sized layers of Section 4.4.1 whose whole
  *           launch lasts a few microseconds.  It takes splits == 1, operands that qualify for the direct-to-LDS
- *           kernels, and K a multiple of 64, at least 64.  ac_gemm_i8 picks it for such operands when K <= 640
- *           and the output has at most 1024 tiles of 32 x 32.
+ *           kernels, and K a multiple of 64, at least 64.  ac_gemm_i8 picks it for such operands where it
+ *           measured ahead of every tiled plan: the fewer the tiles of 32 x 32, the deeper the K (up to 512
+ *           tiles K <= 1024, up to 1024 K <= 384, up to 2048 K <= 128; beyond K = 640 only multiples of 128).
  *           ac_conv2d_i8_planned only: 321 / 161 = the convolution patch kernel with units of 256 / 128 output
  *           pixels: the weights of a 64-channel block AND the image patch a unit needs are both held in LDS, so
  *           every input pixel is fetched once per unit instead of once per kernel tap.  It takes splits == 1,

@@ -1,5 +1,5 @@
 // int8 GEMM for launches that last a few microseconds (the accelerator-sized layers of Section 4.4.1): one wave
-// per 32 x 32 output tile, four independent waves per workgroup.
+// per 32 x 32 output tile, one to four independent waves per workgroup.
 //
 // At that size a launch is a chain of latencies, not of throughput: a workgroup of the tiled kernels spends
 // about 1.3 us in some 500 instructions of addressing before its first operand arrives (a wave issues one
@@ -8,6 +8,10 @@
 // logic ahead of the first load; the operands stream through a ring of private LDS stages (64 or 128 bytes of K
 // each) and the fragments of the next K tile are read while the MFMAs of the current one run.
 //
+// The ring bounds the waves a compute unit holds (160 KB of LDS), and the workgroup size decides over how many
+// compute units a small grid spreads, so the launcher picks among a few (stage width, stages, waves per workgroup)
+// combinations by K and tile count; see launch_small_i8.
+//
 // Operands as for the direct-to-LDS kernels (16-byte aligned, K and N in whole 16-byte chunks), and K a multiple
 // of 64; anything else stays on the tiled kernels.
 #pragma once
@@ -15,19 +19,18 @@
 
 namespace ac {
 
-constexpr int SMALL_WAVES = 4;   // independent waves (tiles) per workgroup
-constexpr int SMALL_KTB = 64;    // K bytes per stage; 128 when K is a multiple of that (half the per-byte bookkeeping)
-constexpr int SMALL_LDS = 24576; // LDS per wave: six stages of 4 KB or three of 8 KB
+constexpr int SMALL_KTB = 64;  // K bytes per stage at least; 128 where K is a multiple of that (half the bookkeeping per byte)
 
-template <int KTB>
+// KTB: bytes of K per stage, S: stages of a wave's ring, SMALL_WAVES: independent waves (tiles) per workgroup
+template <int KTB, int S, int SMALL_WAVES>
 __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const GemmParams p, const int tiles_n, const int ntiles, const unsigned tn_magic) {
   using T = TypeI8;
   using EPI = EpilogueI8;
-  constexpr int S = SMALL_LDS / (64 * KTB);
   using G = DtlGeometry<T, 32, 32, 1, 1, S, KTB>;
   constexpr int NA = G::A_INSTR, NB = G::B_INSTR, KS = G::KSTEPS;
   static_assert(NA == KTB / 32 && NB == KTB / 32 && KS == KTB / 32 && G::TM == 1 && G::TN == 1 && G::STAGE == 64 * KTB && S >= 3, "geometry");
   constexpr int PER_TILE = NA + NB;
+  static_assert((S - 1) * PER_TILE <= 63, "vmcnt is a 6-bit counter");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -135,21 +138,32 @@ static inline bool small_i8_eligible(const GemmParams& p) {
   return p.K >= SMALL_KTB && p.K % SMALL_KTB == 0 && tiles <= INT32_MAX && (p.splits <= 1);
 }
 
-template <int KTB>
-static hipError_t launch_small_i8_ktb(const GemmParams& p, hipStream_t stream) {
-  constexpr int LDS = SMALL_WAVES * SMALL_LDS;
+template <int KTB, int S, int SMALL_WAVES>
+static hipError_t launch_small_i8_cfg(const GemmParams& p, hipStream_t stream) {
+  constexpr int LDS = SMALL_WAVES * S * 64 * KTB;
   static std::atomic<bool> configured{false};
-  if (const hipError_t e = allow_dynamic_lds_once(configured, gemm_i8_small_kernel<KTB>, LDS)) return e;
+  if (const hipError_t e = allow_dynamic_lds_once(configured, gemm_i8_small_kernel<KTB, S, SMALL_WAVES>, LDS)) return e;
   const int tiles_m = (p.M + 31) / 32, tiles_n = (p.N + 31) / 32;
   const int ntiles = tiles_m * tiles_n;
   const unsigned tn_magic = (uint64_t)ntiles * (unsigned)tiles_n < (1ull << 32) ? FastDiv::make((unsigned)tiles_n).magic : 0u;
-  hipLaunchKernelGGL(gemm_i8_small_kernel<KTB>, dim3((unsigned)((ntiles + SMALL_WAVES - 1) / SMALL_WAVES)), dim3(64 * SMALL_WAVES), LDS, stream, p,
+  hipLaunchKernelGGL((gemm_i8_small_kernel<KTB, S, SMALL_WAVES>), dim3((unsigned)((ntiles + SMALL_WAVES - 1) / SMALL_WAVES)), dim3(64 * SMALL_WAVES), LDS, stream, p,
                      tiles_n, ntiles, tn_magic);
   return hipGetLastError();
 }
 
+// Measured (us, warm, per launch; four waves per workgroup over 24 KB rings first, then the choice below):
+// 256^3 3.32 -> 2.92, 3136x64x576 3.83 -> 3.48, 512x768x768 4.63 -> 3.86, 128x1024x1024 5.20 -> 3.94,
+// 6272x256x64 4.36 -> 3.36.  With 24 KB per wave and four waves a compute unit holds one
+// workgroup, four waves; smaller workgroups pack six waves, and up to 256 one-wave workgroups land on compute
+// units of their own.  One or two K tiles per wave need no deep ring: 12 KB rings and four waves per workgroup
+// (twelve waves per compute unit, a quarter of the workgroups to launch).  Deeper rings (up to eight stages), and
+// a tile order that keeps an XCD's tiles in one block of the output so that its L2 fetches less of A and B, were
+// measured too, with operands in the caches and in HBM: no gain on any shape the planner sends here.
 static hipError_t launch_small_i8(const GemmParams& p, hipStream_t stream) {
-  return p.K % 128 == 0 ? launch_small_i8_ktb<128>(p, stream) : launch_small_i8_ktb<64>(p, stream);
+  const int64_t ntiles = (int64_t)((p.M + 31) / 32) * ((p.N + 31) / 32);
+  if (p.K <= 128) return launch_small_i8_cfg<64, 3, 4>(p, stream);
+  if (p.K % 128 != 0) return launch_small_i8_cfg<64, 4, 2>(p, stream);
+  return ntiles <= 256 ? launch_small_i8_cfg<128, 3, 1>(p, stream) : launch_small_i8_cfg<128, 3, 2>(p, stream);
 }
 
 }  // namespace ac

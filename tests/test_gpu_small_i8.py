@@ -2,8 +2,8 @@
 
 Reached through the planned entry point, so that every shape here runs on that kernel whatever the library's own
 choice would be, and through ac_gemm_i8 on the shapes for which the library picks it: K of one to many stages of the
-private LDS ring (64- and 128-byte stages), ragged M and N, workgroups whose last waves have no tile, every
-output-stage variant.
+private LDS ring (64- and 128-byte stages; every ring depth and workgroup size the launcher picks from), ragged M
+and N, workgroups whose last waves have no tile, every output-stage variant.
 """
 import numpy as np
 import pytest
@@ -35,6 +35,9 @@ def test_k_depths(K):
     (1, 16, 64), (31, 16, 128), (32, 32, 64), (33, 48, 192), (65, 80, 320), (256, 256, 256), (257, 272, 448),
     (3136, 64, 576), (3136, 256, 64), (784, 128, 1152), (49, 2048, 512), (1000, 16, 640),
     (5000, 1008, 128),   # 4 945 tiles: far more workgroups than compute units
+    (1000, 272, 384), (3136, 256, 256),   # more than 256 tiles, 128-byte stages: two waves per workgroup
+    (1056, 288, 256),    # 297 tiles: the last workgroup's second wave has none
+    (128, 1024, 3072), (196, 1024, 2304),   # few tiles, deep K: one wave per workgroup
 ])
 def test_shapes(M, N, K):
     A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + N + K)
@@ -109,7 +112,8 @@ def test_refusals_and_fallbacks():
 
 def test_library_choice_runs_it():
     """Shapes of the accelerator-sized layers (Section 4.4.1) through ac_gemm_i8 itself."""
-    for M, N, K in [(256, 256, 256), (3136, 64, 576), (3136, 256, 64), (512, 512, 512), (128, 128, 128)]:
+    for M, N, K in [(256, 256, 256), (3136, 64, 576), (3136, 256, 64), (512, 512, 512), (128, 128, 128), (128, 1024, 1024),
+                    (512, 768, 768), (2048, 1024, 128)]:
         assert ops.ac_gemm_i8_auto_plan(M, N, K) == (32, 1)
         A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + K)
         C = torch.full((M, N), 77, dtype=torch.int8, device="cuda")

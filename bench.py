@@ -11,8 +11,8 @@ Prints ONE JSON line: whole-step throughput, per-workload rates and roofline fra
 record of the dominant kernel, and the CPU oracle timed on a bounded sample of the same workloads.
 
 Per workload: `ms_in_pass` is the duration of a single eager launch inside a pass (device events around it; the
-pass is enqueued while a spin kernel holds the stream, so the host's launch gap is not in it, the event pair's
-own few microseconds are); `ms_isolated_warm` /
+pass is enqueued while a spin kernel holds the stream, so the host's launch gap is not in it; the time of an
+event pair with nothing between, `event_pair_us`, bounds what the events themselves add); `ms_isolated_warm` /
 `ms_isolated_warm_min` are the median / minimum over five timed regions of at least 20 ms of back-to-back
 launches of that workload on the same buffers replayed from a HIP graph (operands stay in the caches);
 `ms_isolated_cold` / `ms_isolated_cold_min` are the same over launches that rotate through copies of the
@@ -156,21 +156,28 @@ hold_stream.cycles_per_ms = None
 def per_kernel_times(wl, steps, stream):
     """Average duration of each launch inside the pass, from HIP events recorded on the launch stream.  Every pass
     is enqueued behind a spin kernel that lasts longer than the host needs to enqueue it, so the interval between
-    two events is the launch between them (plus the event pair's own few microseconds), not the host's launch gap."""
+    two events is the launch between them plus the cost of the event pair itself, not the host's launch gap.  That
+    cost is measured in the same pass (two events with nothing between them, ahead of the first launch) and
+    reported beside the intervals, not subtracted: with a kernel between the events part of it overlaps the
+    kernel's own start and end.  Returns (ms per launch, ms of an empty event pair)."""
     n = len(wl)
     acc = np.zeros(n)
+    empty = 0.0
     with torch.cuda.stream(stream):
         for _ in range(steps):
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 2)]
             hold_stream(stream, 2.0)
+            ev[n + 1].record(stream)
             ev[0].record(stream)
             for i, w in enumerate(wl):
                 w.launch()
                 ev[i + 1].record(stream)
             stream.synchronize()
+            empty += ev[n + 1].elapsed_time(ev[0])
             for i in range(n):
                 acc[i] += ev[i].elapsed_time(ev[i + 1])
-    return acc / steps  # ms
+    empty /= steps
+    return acc / steps, empty
 
 
 MIN_REGION_MS = 20.0  # every timed region of isolated_time is at least this long
@@ -464,7 +471,7 @@ def main():
             step()
         regions = [time_region(step, args.steps) for _ in range(TIMED_REGIONS)]
         ms_per_step = float(np.median(regions))
-        kt = per_kernel_times(wl, min(args.steps, 50), stream)
+        kt, event_pair_ms = per_kernel_times(wl, min(args.steps, 50), stream)
 
     total_ops = float(sum(w.ops for w in wl))
     value = total_ops / ms_per_step / 1e9  # Tops/s
@@ -562,6 +569,7 @@ def main():
         "roofline": roof,
         # the two rates the metric names, each over its own launches (ops of that type / their summed launch times)
         "rates": rates,
+        "event_pair_us": round(event_pair_ms * 1e3, 3),  # two events with nothing between: part of every in-pass interval
         "launch_floor": None if floor_us is None else {"us": round(floor_us, 3), "us_min": round(floor_min_us, 3),
                                                        "kernel": "one-element fill as a graph node, replayed like the isolated workloads"},
         "timed_regions": TIMED_REGIONS, "ms_per_step_regions": [round(r, 5) for r in regions],

@@ -265,12 +265,13 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           B stays in LDS for all of K while tiles of A stream past it, the arrangement of the paper's best
  *           accelerator schedule, Appendix D.1).  It takes splits == 1, operands that qualify for the
  *           direct-to-LDS kernels (below), no bias or a bias row (bias_ld == 0), and K <= 1536 (320) / 2048 (160).
- *           ac_gemm_i8_planned only: 32 = one wave per 32 x 32 output tile, four independent waves per
- *           workgroup and no barrier anywhere, for the accelerator-sized layers of Section 4.4.1 whose whole
+ *           int8 only: 32 = one wave per 32 x 32 output tile, one to four independent waves per workgroup and
+ *           no barrier anywhere, for the accelerator-sized layers of Sections 4.4.1 and 4.4.2 whose whole
  *           launch lasts a few microseconds.  It takes splits == 1, operands that qualify for the direct-to-LDS
- *           kernels, and K a multiple of 64, at least 64.  ac_gemm_i8 picks it for such operands where it
- *           measured ahead of every tiled plan: the fewer the tiles of 32 x 32, the deeper the K (up to 512
- *           tiles K <= 1024, up to 1024 K <= 384, up to 2048 K <= 128; beyond K = 640 only multiples of 128).
+ *           kernels, and K a multiple of 64, at least 64.  ac_gemm_i8 and ac_conv2d_i8 pick it for such operands
+ *           where it measured ahead of every tiled plan: the fewer the tiles of 32 x 32, the deeper the K (up
+ *           to 512 tiles K <= 1024, up to 1024 K <= 384, up to 2048 K <= 128; beyond K = 640 only multiples of
+ *           128).
  *           ac_conv2d_i8_planned only: 321 / 161 = the convolution patch kernel with units of 256 / 128 output
  *           pixels: the weights of a 64-channel block AND the image patch a unit needs are both held in LDS, so
  *           every input pixel is fetched once per unit instead of once per kernel tap.  It takes splits == 1,

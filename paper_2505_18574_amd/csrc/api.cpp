@@ -272,12 +272,11 @@ static ac_status conv2d_i8_entry(const int8_t* in, const int8_t* w, const int32_
   p.splits = 1;
   p.partial = (int32_t*)workspace;
   if (planned) {
-    // a K split, the weight-stationary kernel and the patch kernel need the direct-to-LDS path: 16-byte aligned
+    // a K split, the weight-stationary, patch and one-wave-per-tile kernels need the direct-to-LDS path: 16-byte aligned
     // operands, channel counts in multiples of 16, at most 32 kernel taps
     const bool fast = ac::conv_i8_fast_path(p);
     const bool ws = tile == 320 || tile == 160, patch = tile == 321 || tile == 161;
-    if (tile == 32) return AC_ERR_PLAN;  // the one-wave-per-tile kernel is a GEMM kernel
-    if ((plan.splits > 1 || ws || patch) && !fast) return AC_ERR_PLAN;
+    if ((plan.splits > 1 || ws || patch || tile == 32) && !fast) return AC_ERR_PLAN;
     if (ws && !ac::wstat_eligible(p, tile)) return AC_ERR_PLAN;
     if (patch && !ac::conv_halo_eligible(p, tile)) return AC_ERR_PLAN;
   }

@@ -292,8 +292,8 @@ __global__ void __launch_bounds__(256) splitk_reduce_i8_kernel(const GemmParams 
 
 template <int AMODE>
 hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast, const GemmPlan* forced) {
-  // the one-wave-per-tile kernel is planned only for operands it takes (never for a convolution)
-  GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr, AMODE == 0 && fast && small_i8_eligible(p));
+  // the one-wave-per-tile kernel is planned only for operands it takes
+  GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr, fast && small_i8_eligible(p));
   int ws_bm;
   if (!forced && wstat_tile_rows(plan.tile, &ws_bm) && !(fast && wstat_eligible(p, plan.tile))) {
     plan.tile = choose_tile_i8(p.M, p.N, p.K, false);  // operands the weight-stationary kernel does not take: the tiled kernels
@@ -307,8 +307,8 @@ hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast
     return launch_wstat_tile<AMODE>(plan.tile, p, stream);
   }
   if (plan.tile == 32) {
-    if (AMODE != 0 || !fast || !small_i8_eligible(p)) return hipErrorInvalidValue;
-    return launch_small_i8(p, stream);
+    if (!fast || !small_i8_eligible(p)) return hipErrorInvalidValue;
+    return launch_small_i8<AMODE>(p, stream);
   }
   if (halo_tile_rows(plan.tile, &ws_bm)) {
     ConvHaloParams h;
@@ -412,9 +412,11 @@ hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmP
     } else {
       return dispatch_i8<1>(p, stream, aligned, fast, forced);
     }
-    // a convolution the patch kernel could take but that is too small for it: the tiled kernels, never the
-    // weight-stationary one, whose gather loses to both (28 x 28 x 128 -> 128, 32 images: 13.9 us against 10.2)
-    GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, p.partial != nullptr, false);
+    // a convolution the patch kernel could take but that is too small for it: the tiled kernels (or one wave per
+    // tile, by the GEMM's rule: 56 x 56 x 64 -> 64, one image, 4.4 us against 5.4; K = 1152 gains 0.5 us with the
+    // input in the caches and loses up to 1 us with it in HBM, as for the GEMM), never the weight-stationary
+    // kernel, whose gather loses to both (28 x 28 x 128 -> 128, 32 images: 13.9 us against 10.2)
+    GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, p.partial != nullptr, small_i8_eligible(p));
     int ws_bm;
     if (wstat_tile_rows(plan.tile, &ws_bm)) make_plan_i8(p.K, choose_tile(p.M, p.N), 1, &plan);  // unsplit: no workspace needed
     return dispatch_i8<1>(p, stream, aligned, fast, &plan);

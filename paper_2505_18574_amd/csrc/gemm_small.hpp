@@ -21,8 +21,11 @@ namespace ac {
 
 constexpr int SMALL_KTB = 64;  // K bytes per stage at least; 128 where K is a multiple of that (half the bookkeeping per byte)
 
-// KTB: bytes of K per stage, S: stages of a wave's ring, SMALL_WAVES: independent waves (tiles) per workgroup
-template <int KTB, int S, int SMALL_WAVES>
+// KTB: bytes of K per stage, S: stages of a wave's ring, SMALL_WAVES: independent waves (tiles) per workgroup,
+// AMODE 0: A is the M x K matrix; 1: A is gathered from the NHWC input of a convolution (the per-lane window
+// origin and one validity bit per kernel tap of gemm_dtl_kernel; a chunk outside the image gets the offset
+// 0xffffffff and the bounds check of the buffer load writes its zeros)
+template <int KTB, int S, int SMALL_WAVES, int AMODE>
 __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const GemmParams p, const int tiles_n, const int ntiles, const unsigned tn_magic) {
   using T = TypeI8;
   using EPI = EpilogueI8;
@@ -42,19 +45,51 @@ __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const G
   unsigned char* win = smem + wave * (S * G::STAGE);
   const unsigned lds0 = (unsigned)(uintptr_t)AC_LDS(unsigned char, win);
 
-  // source offsets of the four loads of a K tile (same lane roles as gemm_dtl_kernel, with one wave)
+  // source offsets of the loads of a K tile (same lane roles as gemm_dtl_kernel, with one wave)
+  constexpr int NVAR = KTB == 128 ? 2 : 1;  // distinct swizzle terms of a lane over the A instructions
   unsigned a_voff[NA], b_voff[NB];
+  int g_base[NA];
+  unsigned g_mask[NA], g_kb[NVAR];
+  v4i a_rsrc = {0, 0, 0, 0};
+  if constexpr (AMODE == 1) {
+    const uint64_t ab = (uint64_t)(uintptr_t)p.A;
+    a_rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)ab);
+    a_rsrc[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(ab >> 32));
+    a_rsrc[2] = __builtin_amdgcn_readfirstlane(p.a_bytes);
+    a_rsrc[3] = 0x00020000;
+  }
 #pragma unroll
   for (int i = 0; i < NA; i++) {
     const int row = i * G::A_ROWS_PER_INSTR + lane / G::A_SPR;
     const int a_chunk = (lane % G::A_SPR) ^ G::a_xor(row);
-    const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
-    a_voff[i] = (unsigned)rclamp * (unsigned)p.lda + a_chunk * 16;
+    g_base[i] = 0, g_mask[i] = 0u, a_voff[i] = 0u;
+    if constexpr (AMODE == 0) {
+      const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
+      a_voff[i] = (unsigned)rclamp * (unsigned)p.lda + a_chunk * 16;
+    } else {
+      if (i < NVAR) g_kb[i] = (unsigned)(a_chunk * 16);  // a_xor(row) repeats with period NVAR over the instructions
+      const int m = m0 + row;
+      const unsigned mm = m < p.M ? (unsigned)m : 0u;
+      const unsigned q = p.dOW.div(mm), img = p.dOH.div(q);
+      const int ow = (int)(mm - q * p.OW), oh = (int)(q - img * p.OH);
+      const int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
+      g_base[i] = (((int)img * p.H + ih0) * p.W + iw0) * p.Cin;
+      auto span = [](int first, int n, int extent) {  // bits k = 0 .. n-1 with 0 <= first + k < extent
+        const int lo = first < 0 ? -first : 0, hi = extent - first < n ? extent - first : n;
+        if (hi <= lo) return 0u;
+        return (hi >= 32 ? ~0u : (1u << hi) - 1u) & ~((1u << lo) - 1u);
+      };
+      const unsigned rows = span(ih0, p.KH, p.H), cols = span(iw0, p.KW, p.W);
+      unsigned mask = 0u;
+      for (int kh = 0; kh < p.KH; kh++)
+        if ((rows >> kh) & 1u) mask |= cols << (kh * p.KW);
+      g_mask[i] = m < p.M ? mask : 0u;
+    }
     const int brow = i * G::B_ROWS_PER_INSTR + lane / G::B_SPR;
     const int slot = lane % G::B_SPR;
     b_voff[i] = (unsigned)brow * (unsigned)p.ldb + (n0 + slot * 16 < p.N ? slot * 16 : 0);
   }
-  const unsigned char* a_base = (const unsigned char*)p.A + (int64_t)m0 * p.lda;
+  const unsigned char* a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda : 0);
   const unsigned char* b_base = (const unsigned char*)p.B + n0;
   const int64_t b_step = (int64_t)G::BK * p.ldb;
   const int nkt = p.K / KTB;
@@ -66,8 +101,26 @@ __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const G
   int wr = 0;  // stage that the next requested tile goes to
   auto issue = [&]() {
     const unsigned st = lds0 + wr * G::STAGE;
+    if constexpr (AMODE == 1) {
+      // the lane's chunk sits at K byte g_kb: tap g_kb / Cin, channel g_kb % Cin (K is in whole stages: never beyond K)
+      unsigned g_off[NVAR], g_tap[NVAR];
 #pragma unroll
-    for (int i = 0; i < NA; i++) load_to_lds16_so(a_base, a_voff[i], st + i * 1024);
+      for (int v = 0; v < NVAR; v++) {
+        const unsigned tap = p.dCin.div(g_kb[v]), ci = g_kb[v] - tap * p.Cin;
+        const unsigned kh = p.dKW.div(tap), kw = tap - kh * p.KW;
+        g_off[v] = (kh * p.W + kw) * p.Cin + ci;
+        g_tap[v] = tap;
+        g_kb[v] += KTB;
+      }
+#pragma unroll
+      for (int i = 0; i < NA; i++) {
+        const unsigned inside = (g_mask[i] >> (g_tap[i & (NVAR - 1)] & 31u)) & 1u;
+        buffer_to_lds16(a_rsrc, ((unsigned)g_base[i] + g_off[i & (NVAR - 1)]) | (inside - 1u), st + i * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NA; i++) load_to_lds16_so(a_base, a_voff[i], st + i * 1024);
+    }
 #pragma unroll
     for (int i = 0; i < NB; i++) load_to_lds16_so(b_base, b_voff[i], st + G::A_BYTES + i * 1024);
     a_base += KTB;
@@ -132,21 +185,22 @@ __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const G
   EPI::tile(p, m0, n0, acc, lane, 0, pre);
 }
 
-// Whether the small kernel can run p (a GEMM on direct-to-LDS operands, see gemm_i8_fast_path, checked by the caller).
+// Whether the small kernel can run p (a GEMM or a convolution on direct-to-LDS operands, see gemm_i8_fast_path and
+// conv_i8_fast_path, checked by the caller).
 static inline bool small_i8_eligible(const GemmParams& p) {
   const int64_t tiles = (int64_t)((p.M + 31) / 32) * ((p.N + 31) / 32);
   return p.K >= SMALL_KTB && p.K % SMALL_KTB == 0 && tiles <= INT32_MAX && (p.splits <= 1);
 }
 
-template <int KTB, int S, int SMALL_WAVES>
+template <int KTB, int S, int SMALL_WAVES, int AMODE>
 static hipError_t launch_small_i8_cfg(const GemmParams& p, hipStream_t stream) {
   constexpr int LDS = SMALL_WAVES * S * 64 * KTB;
   static std::atomic<bool> configured{false};
-  if (const hipError_t e = allow_dynamic_lds_once(configured, gemm_i8_small_kernel<KTB, S, SMALL_WAVES>, LDS)) return e;
+  if (const hipError_t e = allow_dynamic_lds_once(configured, gemm_i8_small_kernel<KTB, S, SMALL_WAVES, AMODE>, LDS)) return e;
   const int tiles_m = (p.M + 31) / 32, tiles_n = (p.N + 31) / 32;
   const int ntiles = tiles_m * tiles_n;
   const unsigned tn_magic = (uint64_t)ntiles * (unsigned)tiles_n < (1ull << 32) ? FastDiv::make((unsigned)tiles_n).magic : 0u;
-  hipLaunchKernelGGL((gemm_i8_small_kernel<KTB, S, SMALL_WAVES>), dim3((unsigned)((ntiles + SMALL_WAVES - 1) / SMALL_WAVES)), dim3(64 * SMALL_WAVES), LDS, stream, p,
+  hipLaunchKernelGGL((gemm_i8_small_kernel<KTB, S, SMALL_WAVES, AMODE>), dim3((unsigned)((ntiles + SMALL_WAVES - 1) / SMALL_WAVES)), dim3(64 * SMALL_WAVES), LDS, stream, p,
                      tiles_n, ntiles, tn_magic);
   return hipGetLastError();
 }
@@ -159,11 +213,12 @@ static hipError_t launch_small_i8_cfg(const GemmParams& p, hipStream_t stream) {
 // (twelve waves per compute unit, a quarter of the workgroups to launch).  Deeper rings (up to eight stages), and
 // a tile order that keeps an XCD's tiles in one block of the output so that its L2 fetches less of A and B, were
 // measured too, with operands in the caches and in HBM: no gain on any shape the planner sends here.
+template <int AMODE>
 static hipError_t launch_small_i8(const GemmParams& p, hipStream_t stream) {
   const int64_t ntiles = (int64_t)((p.M + 31) / 32) * ((p.N + 31) / 32);
-  if (p.K <= 128) return launch_small_i8_cfg<64, 3, 4>(p, stream);
-  if (p.K % 128 != 0) return launch_small_i8_cfg<64, 4, 2>(p, stream);
-  return ntiles <= 256 ? launch_small_i8_cfg<128, 3, 1>(p, stream) : launch_small_i8_cfg<128, 3, 2>(p, stream);
+  if (p.K <= 128) return launch_small_i8_cfg<64, 3, 4, AMODE>(p, stream);
+  if (p.K % 128 != 0) return launch_small_i8_cfg<64, 4, 2, AMODE>(p, stream);
+  return ntiles <= 256 ? launch_small_i8_cfg<128, 3, 1, AMODE>(p, stream) : launch_small_i8_cfg<128, 3, 2, AMODE>(p, stream);
 }
 
 }  // namespace ac

@@ -24,7 +24,7 @@ from . import ops
 Plan = Tuple[int, int]  # (tile code, splits)
 TILES = (64, 128, 192, 256)  # tile codes in order of area; 192 is the 256 x 128 (rows x columns) tile
 TILE_DIMS = {32: (32, 32), 64: (64, 64), 128: (128, 128), 192: (256, 128), 256: (256, 256), 160: (128, 64), 320: (256, 64)}
-# int8 GEMM only: one wave per 32 x 32 tile, for launches of a few microseconds; K in whole 64-byte tiles, never cut
+# int8 only: one wave per 32 x 32 tile, for launches of a few microseconds; K in whole 64-byte tiles, never cut
 SMALL_TILES = (32,)
 # int8 only: the weight-stationary kernel (128- / 256-row tiles, 64 columns, all of K resident in LDS, no K split)
 WS_TILES = (160, 320)
@@ -56,7 +56,7 @@ def normalise(kind: str, K: int, plan: Plan) -> Plan:
 def valid(kind: str, M: int, N: int, K: int, plan: Plan) -> bool:
     tile, splits = plan
     if tile in SMALL_TILES:
-        return kind == "i8" and splits == 1 and K >= 64 and K % 64 == 0
+        return kind in ("i8", "conv") and splits == 1 and K >= 64 and K % 64 == 0
     if tile in WS_TILES:
         return kind in ("i8", "conv") and splits == 1 and 1 <= K <= WS_MAX_K[tile]
     if tile in HALO_TILES:

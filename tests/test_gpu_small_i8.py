@@ -110,6 +110,43 @@ def test_refusals_and_fallbacks():
     np.testing.assert_array_equal(host(C), oracle.gemm_i8(A, B, bias, 8, 0))
 
 
+def conv_planned_check(x, w, bias, stride, pad, shift, act):
+    Nb, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    OH, OW = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+    out = torch.full((Nb, OH, OW, Cout), 99, dtype=torch.int8, device="cuda")
+    ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, stride, pad, shift, act, plan=(32, 1))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(out), oracle.conv2d_i8(x, w, bias, stride, pad, shift, act))
+
+
+# the convolution gather of the same kernel: K = KH KW Cin in whole 64-byte stages (one tap per stage, several stages
+# per tap, several taps per stage), borders, strides, ragged pixel and channel counts
+@pytest.mark.parametrize("Nb,H,W,Cin,Cout,KH,KW,stride,pad", [
+    (1, 56, 56, 64, 64, 3, 3, 1, 1),     # one 64-byte stage per tap
+    (1, 28, 28, 128, 256, 3, 3, 2, 1),   # one 128-byte stage per tap, stride 2
+    (2, 9, 7, 64, 32, 3, 3, 2, 1),       # odd image
+    (3, 12, 12, 32, 48, 3, 3, 1, 0),     # K = 288: not in whole stages -> refused (checked below)
+    (1, 6, 6, 16, 16, 2, 2, 1, 1),       # four taps per stage
+    (2, 10, 10, 32, 80, 2, 2, 2, 0),     # two taps per 64-byte stage, non-overlapping windows
+    (1, 14, 14, 256, 64, 3, 3, 1, 1),    # two 128-byte stages per tap
+    (1, 7, 7, 192, 48, 3, 3, 1, 1),      # 1.5 stages per tap: a stage that straddles two taps
+    (2, 5, 7, 64, 16, 3, 3, 1, 3),       # padding wider than the kernel
+    (1, 9, 9, 16, 16, 4, 8, 1, 3),       # 32 taps
+    (4, 30, 30, 64, 80, 3, 3, 1, 1),     # 3600 pixels: many tiles, ragged in M and N
+    (2, 9, 9, 64, 32, 1, 1, 2, 0),       # 1 x 1 with a stride
+])
+def test_convolution_gather(Nb, H, W, Cin, Cout, KH, KW, stride, pad):
+    x, w, bias = inputs.conv_i8_inputs(Nb, H, W, Cin, Cout, KH, KW, seed=H * W + Cin)
+    if (KH * KW * Cin) % 64:
+        with pytest.raises(ops.AcError) as e:
+            conv_planned_check(x, w, bias, stride, pad, 8, 1)
+        assert e.value.status == ops.AC_ERR_PLAN
+        return
+    conv_planned_check(x, w, bias, stride, pad, 8, 1)
+    conv_planned_check(x, w, None, stride, pad, 5, 0)
+
+
 def test_library_choice_runs_it():
     """Shapes of the accelerator-sized layers (Section 4.4.1) through ac_gemm_i8 itself."""
     for M, N, K in [(256, 256, 256), (3136, 64, 576), (3136, 256, 64), (512, 512, 512), (128, 128, 128), (128, 1024, 1024),

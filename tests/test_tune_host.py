@@ -45,9 +45,8 @@ def test_convolution_plan_space():
     # a convolution adds the patch kernel's two unit sizes to the int8 plan space; they never split K
     M, N, K = 8 * 56 * 56, 64, 576
     plans = tune.all_plans("conv", M, N, K)
-    # ... and has no one-wave-per-tile kernel, which is a GEMM kernel
-    assert (set(tune.all_plans("i8", M, N, K)) - {(32, 1)}) | {(161, 1), (321, 1)} == set(plans)
-    assert tune.valid("i8", M, N, K, (32, 1)) and not tune.valid("conv", M, N, K, (32, 1)) and not tune.valid("bf16", M, N, K, (32, 1))
+    assert set(tune.all_plans("i8", M, N, K)) | {(161, 1), (321, 1)} == set(plans)
+    assert tune.valid("i8", M, N, K, (32, 1)) and tune.valid("conv", M, N, K, (32, 1)) and not tune.valid("bf16", M, N, K, (32, 1))
     assert not tune.valid("i8", M, N, K, (32, 2)) and not tune.valid("i8", M, N, 600, (32, 1)) and not tune.valid("i8", M, N, 32, (32, 1))
     assert (32, 1) in tune.neighbours("i8", M, N, K, (64, 1)) and set(tune.neighbours("i8", M, N, K, (32, 1))) == {(64, 1), (64, 2)}
     assert tune.valid("conv", M, N, K, (321, 1)) and not tune.valid("conv", M, N, K, (321, 2))

@@ -267,8 +267,9 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           direct-to-LDS kernels (below), no bias or a bias row (bias_ld == 0), and K <= 1536 (320) / 2048 (160).
  *           int8 only: 32 = one wave per 32 x 32 output tile, one to four independent waves per workgroup and
  *           no barrier anywhere, for the accelerator-sized layers of Sections 4.4.1 and 4.4.2 whose whole
- *           launch lasts a few microseconds.  It takes splits == 1, operands that qualify for the direct-to-LDS
- *           kernels, and K a multiple of 64, at least 64.  ac_gemm_i8 and ac_conv2d_i8 pick it for such operands
+ *           launch lasts a few microseconds.  It takes operands that qualify for the direct-to-LDS kernels and
+ *           K a multiple of 64, at least 64 (K slices, splits > 1, are whole 64-byte K tiles; every (tile,
+ *           slice) is then a wave of its own).  ac_gemm_i8 and ac_conv2d_i8 pick it, uncut, for such operands
  *           where it measured ahead of every tiled plan: the fewer the tiles of 32 x 32, the deeper the K (up
  *           to 512 tiles K <= 1024, up to 1024 K <= 384, up to 2048 K <= 128; beyond K = 640 only multiples of
  *           128).
@@ -278,7 +279,7 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           Cin a multiple of 32, K <= 2048, out 16-byte aligned with Cout a multiple of 16, and a patch that
  *           fits: 2 x (patch rows x patch width x (Cin + 16)) + 64 K bytes <= 160 KB.
  *   splits  1 = no split; n > 1 cuts the K range into at most n slices of equal whole K tiles (64 bytes of K
- *           per tile for tile 256, 128 bytes otherwise), each slice a workgroup of its own.  Needs operands
+ *           per tile for tiles 256 and 32, 128 bytes otherwise), each slice a workgroup (tile 32: a wave) of its own.  Needs operands
  *           that qualify for the direct-to-LDS kernels: base pointers and row pitches of A and B multiples of
  *           16 bytes, K and N multiples of 16 (int8) or 8 (bf16) elements, C 4-byte (int8) or 16-byte (bf16)
  *           aligned with ldc a multiple of 4, and row pitches below 13 MB (A) and 33 MB (B): a tile's rows are

@@ -227,7 +227,7 @@ bool make_plan_i8(int32_t K, int32_t tile, int32_t splits, GemmPlan* plan) {
   int bm, bn;
   if (!tile_dims(tile, &bm, &bn)) return false;
   if ((wstat_tile_rows(tile, &bm) || halo_tile_rows(tile, &bm)) && splits != 1) return false;  // these kernels keep all of K resident
-  if (tile == 32 && (splits != 1 || K < SMALL_KTB || K % SMALL_KTB != 0)) return false;            // whole K tiles of 64 bytes, never cut
+  if (tile == 32 && (K < SMALL_KTB || K % SMALL_KTB != 0)) return false;                           // whole K tiles of 64 bytes
   return make_plan(K, tile, ktb_of_tile(tile), splits, plan);
 }
 
@@ -308,7 +308,11 @@ hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast
   }
   if (plan.tile == 32) {
     if (!fast || !small_i8_eligible(p)) return hipErrorInvalidValue;
-    return launch_small_i8<AMODE>(p, stream);
+    const hipError_t e = launch_small_i8<AMODE>(p, stream);
+    if (e != hipSuccess || plan.splits <= 1) return e;
+    const int64_t quads = (int64_t)p.M * (p.N / 4);
+    hipLaunchKernelGGL(splitk_reduce_i8_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, p);
+    return hipGetLastError();
   }
   if (halo_tile_rows(plan.tile, &ws_bm)) {
     ConvHaloParams h;

@@ -1,5 +1,5 @@
-// int8 GEMM for launches that last a few microseconds (the accelerator-sized layers of Section 4.4.1): one wave
-// per 32 x 32 output tile, one to four independent waves per workgroup.
+// int8 GEMM and convolution for launches that last a few microseconds (the accelerator-sized layers of Sections
+// 4.4.1 and 4.4.2): one wave per 32 x 32 output tile, one to four independent waves per workgroup.
 //
 // At that size a launch is a chain of latencies, not of throughput: a workgroup of the tiled kernels spends
 // about 1.3 us in some 500 instructions of addressing before its first operand arrives (a wave issues one
@@ -24,8 +24,10 @@ constexpr int SMALL_KTB = 64;  // K bytes per stage at least; 128 where K is a m
 // KTB: bytes of K per stage, S: stages of a wave's ring, SMALL_WAVES: independent waves (tiles) per workgroup,
 // AMODE 0: A is the M x K matrix; 1: A is gathered from the NHWC input of a convolution (the per-lane window
 // origin and one validity bit per kernel tap of gemm_dtl_kernel; a chunk outside the image gets the offset
-// 0xffffffff and the bounds check of the buffer load writes its zeros)
-template <int KTB, int S, int SMALL_WAVES, int AMODE>
+// 0xffffffff and the bounds check of the buffer load writes its zeros).  SPLIT: a wave owns (tile, K slice): slice s
+// covers K tiles s * kt_per_split ... and leaves its int32 sums in p.partial[s][M][N] for splitk_reduce_i8_kernel
+// (with few tiles and a deep K, slices are what puts enough loads in flight; ntiles then counts tiles, not items).
+template <int KTB, int S, int SMALL_WAVES, int AMODE, bool SPLIT>
 __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const GemmParams p, const int tiles_n, const int ntiles, const unsigned tn_magic) {
   using T = TypeI8;
   using EPI = EpilogueI8;
@@ -37,8 +39,11 @@ __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const G
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int tile = blockIdx.x * SMALL_WAVES + wave;
-  if (tile >= ntiles) return;  // whole waves leave; no wave of this kernel ever waits for another
+  const int item = blockIdx.x * SMALL_WAVES + wave;
+  if (item >= (SPLIT ? ntiles * p.splits : ntiles)) return;  // whole waves leave; no wave of this kernel ever waits for another
+  const int split = SPLIT ? item / ntiles : 0;
+  const int tile = item - split * ntiles;
+  const int kt0 = split * p.kt_per_split;  // first K tile of this slice
   const int tm = tn_magic ? (int)__umulhi((unsigned)tile, tn_magic) : tile / tiles_n;
   const int tn = tile - tm * tiles_n;
   const int m0 = tm * 32, n0 = tn * 32;
@@ -67,7 +72,7 @@ __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const G
       const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
       a_voff[i] = (unsigned)rclamp * (unsigned)p.lda + a_chunk * 16;
     } else {
-      if (i < NVAR) g_kb[i] = (unsigned)(a_chunk * 16);  // a_xor(row) repeats with period NVAR over the instructions
+      if (i < NVAR) g_kb[i] = (unsigned)(kt0 * KTB + a_chunk * 16);  // a_xor(row) repeats with period NVAR over the instructions
       const int m = m0 + row;
       const unsigned mm = m < p.M ? (unsigned)m : 0u;
       const unsigned q = p.dOW.div(mm), img = p.dOH.div(q);
@@ -89,14 +94,15 @@ __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const G
     const int slot = lane % G::B_SPR;
     b_voff[i] = (unsigned)brow * (unsigned)p.ldb + (n0 + slot * 16 < p.N ? slot * 16 : 0);
   }
-  const unsigned char* a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda : 0);
-  const unsigned char* b_base = (const unsigned char*)p.B + n0;
   const int64_t b_step = (int64_t)G::BK * p.ldb;
-  const int nkt = p.K / KTB;
+  const unsigned char* a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda : 0) + (int64_t)kt0 * KTB;
+  const unsigned char* b_base = (const unsigned char*)p.B + n0 + kt0 * b_step;
+  const int nkt_total = p.K / KTB;
+  const int nkt = SPLIT ? (nkt_total - kt0 < p.kt_per_split ? nkt_total - kt0 : p.kt_per_split) : nkt_total;
 
   // the bias row is requested ahead of the operand loads, so that the counted waits on those see nothing else
   EPI::Pre pre;
-  EPI::prefetch(p, n0, lane, pre);
+  if constexpr (!SPLIT) EPI::prefetch(p, n0, lane, pre);
 
   int wr = 0;  // stage that the next requested tile goes to
   auto issue = [&]() {
@@ -182,25 +188,38 @@ __global__ void __launch_bounds__(64 * SMALL_WAVES) gemm_i8_small_kernel(const G
   }
   if (kt < nkt) step(kt, f[0], f[1]);
 
-  EPI::tile(p, m0, n0, acc, lane, 0, pre);
+  if constexpr (SPLIT) {
+    // With the swapped operand order, registers 4 g .. 4 g + 3 of a lane are columns 8 g + 4 (lane / 32) + 0 .. 3 of
+    // row lane % 32: one 16-byte store each (N is a multiple of 16 on this path: a group of four is inside or outside).
+    const int m = m0 + (lane & 31);
+    int32_t* row = p.partial + ((int64_t)split * p.M + m) * p.N;
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      const int n = n0 + 8 * g + 4 * (lane >> 5);
+      if (m < p.M && n < p.N) *(v4i*)(row + n) = v4i{acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+    }
+  } else {
+    EPI::tile(p, m0, n0, acc, lane, 0, pre);
+  }
 }
 
 // Whether the small kernel can run p (a GEMM or a convolution on direct-to-LDS operands, see gemm_i8_fast_path and
 // conv_i8_fast_path, checked by the caller).
 static inline bool small_i8_eligible(const GemmParams& p) {
   const int64_t tiles = (int64_t)((p.M + 31) / 32) * ((p.N + 31) / 32);
-  return p.K >= SMALL_KTB && p.K % SMALL_KTB == 0 && tiles <= INT32_MAX && (p.splits <= 1);
+  return p.K >= SMALL_KTB && p.K % SMALL_KTB == 0 && tiles * (p.splits > 1 ? p.splits : 1) <= INT32_MAX;
 }
 
-template <int KTB, int S, int SMALL_WAVES, int AMODE>
+template <int KTB, int S, int SMALL_WAVES, int AMODE, bool SPLIT = false>
 static hipError_t launch_small_i8_cfg(const GemmParams& p, hipStream_t stream) {
   constexpr int LDS = SMALL_WAVES * S * 64 * KTB;
   static std::atomic<bool> configured{false};
-  if (const hipError_t e = allow_dynamic_lds_once(configured, gemm_i8_small_kernel<KTB, S, SMALL_WAVES, AMODE>, LDS)) return e;
+  if (const hipError_t e = allow_dynamic_lds_once(configured, gemm_i8_small_kernel<KTB, S, SMALL_WAVES, AMODE, SPLIT>, LDS)) return e;
   const int tiles_m = (p.M + 31) / 32, tiles_n = (p.N + 31) / 32;
   const int ntiles = tiles_m * tiles_n;
   const unsigned tn_magic = (uint64_t)ntiles * (unsigned)tiles_n < (1ull << 32) ? FastDiv::make((unsigned)tiles_n).magic : 0u;
-  hipLaunchKernelGGL((gemm_i8_small_kernel<KTB, S, SMALL_WAVES, AMODE>), dim3((unsigned)((ntiles + SMALL_WAVES - 1) / SMALL_WAVES)), dim3(64 * SMALL_WAVES), LDS, stream, p,
+  const int64_t items = (int64_t)ntiles * (SPLIT ? p.splits : 1);
+  hipLaunchKernelGGL((gemm_i8_small_kernel<KTB, S, SMALL_WAVES, AMODE, SPLIT>), dim3((unsigned)((items + SMALL_WAVES - 1) / SMALL_WAVES)), dim3(64 * SMALL_WAVES), LDS, stream, p,
                      tiles_n, ntiles, tn_magic);
   return hipGetLastError();
 }
@@ -215,6 +234,8 @@ static hipError_t launch_small_i8_cfg(const GemmParams& p, hipStream_t stream) {
 // measured too, with operands in the caches and in HBM: no gain on any shape the planner sends here.
 template <int AMODE>
 static hipError_t launch_small_i8(const GemmParams& p, hipStream_t stream) {
+  // K slices (64-byte K tiles, as the plan counts them): the caller launches the kernel that sums them
+  if (p.splits > 1) return launch_small_i8_cfg<64, 4, 2, AMODE, true>(p, stream);
   const int64_t ntiles = (int64_t)((p.M + 31) / 32) * ((p.N + 31) / 32);
   if (p.K <= 128) return launch_small_i8_cfg<64, 3, 4, AMODE>(p, stream);
   if (p.K % 128 != 0) return launch_small_i8_cfg<64, 4, 2, AMODE>(p, stream);

@@ -24,7 +24,7 @@ from . import ops
 Plan = Tuple[int, int]  # (tile code, splits)
 TILES = (64, 128, 192, 256)  # tile codes in order of area; 192 is the 256 x 128 (rows x columns) tile
 TILE_DIMS = {32: (32, 32), 64: (64, 64), 128: (128, 128), 192: (256, 128), 256: (256, 256), 160: (128, 64), 320: (256, 64)}
-# int8 only: one wave per 32 x 32 tile, for launches of a few microseconds; K in whole 64-byte tiles, never cut
+# int8 only: one wave per 32 x 32 tile, for launches of a few microseconds; K in whole 64-byte tiles
 SMALL_TILES = (32,)
 # int8 only: the weight-stationary kernel (128- / 256-row tiles, 64 columns, all of K resident in LDS, no K split)
 WS_TILES = (160, 320)
@@ -39,7 +39,7 @@ MAX_WORKSPACE_BYTES = 1 << 30  # partial sums (int32 / fp32, splits * M * N * 4 
 def k_tiles(kind: str, K: int, tile: int) -> int:
     """K tiles of the kernel behind `tile`: 64 bytes of K per tile for the 256 tile, 128 bytes otherwise."""
     kbytes = K * (2 if kind == "bf16" else 1)
-    ktb = 64 if tile == 256 else 128
+    ktb = 64 if tile in (256, 32) else 128
     return (kbytes + ktb - 1) // ktb
 
 
@@ -55,13 +55,13 @@ def normalise(kind: str, K: int, plan: Plan) -> Plan:
 
 def valid(kind: str, M: int, N: int, K: int, plan: Plan) -> bool:
     tile, splits = plan
-    if tile in SMALL_TILES:
-        return kind in ("i8", "conv") and splits == 1 and K >= 64 and K % 64 == 0
+    if tile in SMALL_TILES and not (kind in ("i8", "conv") and K >= 64 and K % 64 == 0):
+        return False
     if tile in WS_TILES:
         return kind in ("i8", "conv") and splits == 1 and 1 <= K <= WS_MAX_K[tile]
     if tile in HALO_TILES:
         return kind == "conv" and splits == 1
-    if tile not in TILES or splits < 1 or (splits > 1 and splits > k_tiles(kind, K, tile)):
+    if tile not in TILES + SMALL_TILES or splits < 1 or (splits > 1 and splits > k_tiles(kind, K, tile)):
         return False
     bm, bn = TILE_DIMS[tile]
     workgroups = ((M + bm - 1) // bm) * ((N + bn - 1) // bn) * splits
@@ -75,14 +75,14 @@ def valid(kind: str, M: int, N: int, K: int, plan: Plan) -> bool:
 def all_plans(kind: str, M: int, N: int, K: int) -> List[Plan]:
     """Every tile with every power-of-two split that is valid for the shape."""
     out: List[Plan] = []
-    for tile in TILES:
+    for tile in SMALL_TILES + TILES:
         s = 1
         while valid(kind, M, N, K, (tile, s)):
             q = normalise(kind, K, (tile, s))
             if q not in out:
                 out.append(q)
             s *= 2
-    out += [(t, 1) for t in SMALL_TILES + WS_TILES + HALO_TILES if valid(kind, M, N, K, (t, 1))]
+    out += [(t, 1) for t in WS_TILES + HALO_TILES if valid(kind, M, N, K, (t, 1))]
     return out
 
 
@@ -107,8 +107,8 @@ def seed_plans(kind: str, M: int, N: int, K: int, auto: Plan, workgroups: int = 
 def neighbours(kind: str, M: int, N: int, K: int, plan: Plan) -> List[Plan]:
     """One step from `plan`: the next tile code up or down, half or twice the split."""
     tile, splits = plan
-    if tile in SMALL_TILES:  # its neighbours: the smallest tile of the tiled kernels, whole or cut once
-        cand = [(64, 1), (64, 2)]
+    if tile in SMALL_TILES:  # its neighbours: the smallest tile of the tiled kernels at the same split, half or twice the split
+        cand = [(64, splits), (tile, max(1, splits // 2)), (tile, splits * 2)]
     elif tile in WS_TILES:  # its neighbours: the other row-tile height, and the tiled kernels of similar height
         cand = [(WS_TILES[1 - WS_TILES.index(tile)], 1), (64, 1), (192, 1)] + [(t, 1) for t in HALO_TILES]
     elif tile in HALO_TILES:  # the other unit size, the other resident-operand kernel, the tiled kernels
@@ -117,8 +117,8 @@ def neighbours(kind: str, M: int, N: int, K: int, plan: Plan) -> List[Plan]:
         i = TILES.index(tile)
         cand = [(TILES[j], splits) for j in (i - 1, i + 1) if 0 <= j < len(TILES)]
         cand += [(tile, max(1, splits // 2)), (tile, splits * 2)]
-        if tile == 64 and splits == 1:
-            cand += [(t, 1) for t in SMALL_TILES]
+        if tile == 64:
+            cand += [(t, splits) for t in SMALL_TILES]
     out: List[Plan] = []
     for c in cand:
         if valid(kind, M, N, K, c):

@@ -95,8 +95,8 @@ def test_refusals_and_fallbacks():
         ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, 8, 0, 32, 1)
     assert e.value.status == ops.AC_ERR_PLAN
     A, B, bias = inputs.gemm_i8_inputs(64, 64, 128, seed=3)
-    with pytest.raises(ops.AcError) as e:  # never cut
-        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, 8, 0, 32, 2)
+    with pytest.raises(ops.AcError) as e:  # more slices than K tiles of 64 bytes
+        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, 8, 0, 32, 3)
     assert e.value.status == ops.AC_ERR_PLAN
     with pytest.raises(ops.AcError) as e:  # operands the direct-to-LDS kernels do not take (N = 60)
         ops.ac_gemm_i8_planned(dev(A), dev(B[:, :60].copy()), dev(bias[:60].copy()), C[:, :60].contiguous(), 8, 0, 32, 1)
@@ -108,6 +108,27 @@ def test_refusals_and_fallbacks():
     ops.ac_gemm_i8(Ap[:, :128], dev(B), dev(bias), C, 8, 0)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(host(C), oracle.gemm_i8(A, B, bias, 8, 0))
+
+
+@pytest.mark.parametrize("M,N,K,splits", [
+    (49, 2048, 4608, 8), (196, 1024, 2304, 4), (100, 80, 4160, 5), (33, 48, 192, 3), (1, 16, 128, 2), (300, 272, 1088, 16),
+    (64, 64, 8192, 128),   # one K tile per slice
+    (130, 80, 8384, 7),    # 131 K tiles in slices of 19: the last slice is shorter
+])
+def test_k_slices(M, N, K, splits):
+    """A cut K range: every (tile, slice) is a wave of its own, the slices' int32 sums go through the workspace."""
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + N + K)
+    need = ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, 32, splits)
+    assert need > 0 and need % (M * N * 4) == 0
+    ws = torch.full((need,), 0xA5, dtype=torch.uint8, device="cuda")  # contents on entry are unspecified
+    for bias_, shift, act in ((bias, 12, 1), (None, 9, 0)):
+        C = torch.full((M, N), 77, dtype=torch.int8, device="cuda")
+        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias_), C, shift, act, 32, splits, workspace=ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(C), oracle.gemm_i8(A, B, bias_, shift, act))
+    with pytest.raises(ops.AcError) as e:  # a cut K range needs the workspace
+        ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, 12, 1, 32, splits)
+    assert e.value.status == ops.AC_ERR_WORKSPACE
 
 
 def conv_planned_check(x, w, bias, stride, pad, shift, act):
@@ -145,6 +166,19 @@ def test_convolution_gather(Nb, H, W, Cin, Cout, KH, KW, stride, pad):
         return
     conv_planned_check(x, w, bias, stride, pad, 8, 1)
     conv_planned_check(x, w, None, stride, pad, 5, 0)
+
+
+def test_convolution_gather_with_k_slices():
+    x, w, bias = inputs.conv_i8_inputs(1, 7, 7, 512, 64, 3, 3, seed=77)  # 49 pixels, K = 4608
+    M, N, K = 49, 64, 4608
+    want = oracle.conv2d_i8(x, w, bias, 1, 1, 11, 1)
+    for splits in (4, 9):
+        need = ops.ac_gemm_i8_planned_workspace_bytes(M, N, K, 32, splits)
+        ws = torch.full((need,), 0x5A, dtype=torch.uint8, device="cuda")
+        out = torch.full((1, 7, 7, 64), 99, dtype=torch.int8, device="cuda")
+        ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, 1, 1, 11, 1, workspace=ws, plan=(32, splits))
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(out), want)
 
 
 def test_library_choice_runs_it():

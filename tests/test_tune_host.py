@@ -47,8 +47,10 @@ def test_convolution_plan_space():
     plans = tune.all_plans("conv", M, N, K)
     assert set(tune.all_plans("i8", M, N, K)) | {(161, 1), (321, 1)} == set(plans)
     assert tune.valid("i8", M, N, K, (32, 1)) and tune.valid("conv", M, N, K, (32, 1)) and not tune.valid("bf16", M, N, K, (32, 1))
-    assert not tune.valid("i8", M, N, K, (32, 2)) and not tune.valid("i8", M, N, 600, (32, 1)) and not tune.valid("i8", M, N, 32, (32, 1))
-    assert (32, 1) in tune.neighbours("i8", M, N, K, (64, 1)) and set(tune.neighbours("i8", M, N, K, (32, 1))) == {(64, 1), (64, 2)}
+    assert tune.valid("i8", M, N, K, (32, 2)) and not tune.valid("i8", M, N, K, (32, 10))  # K slices of whole 64-byte tiles: nine here
+    assert not tune.valid("i8", M, N, 600, (32, 1)) and not tune.valid("i8", M, N, 32, (32, 1))
+    assert (32, 1) in tune.neighbours("i8", M, N, K, (64, 1)) and set(tune.neighbours("i8", M, N, K, (32, 1))) == {(64, 1), (32, 2)}
+    assert set(tune.neighbours("i8", M, N, K, (32, 2))) == {(64, 2), (32, 1), (32, 3)}  # four slices of nine K tiles are three
     assert tune.valid("conv", M, N, K, (321, 1)) and not tune.valid("conv", M, N, K, (321, 2))
     assert not tune.valid("i8", M, N, K, (321, 1)) and not tune.valid("bf16", M, N, K, (161, 1))
     seeds = tune.seed_plans("conv", M, N, K, (64, 1))

@@ -328,6 +328,17 @@ def supplementary(stream, only=None):
             ms = isolated_time(w, stream, reps=5, rounds=3)
             out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"]})
             del A, B, C
+        if want("supplementary_gemm_i8_t_8192"):  # the same product with both operands transposed in memory (A^T: K x M, B^T: N x K)
+            M = N = K = 8192
+            At = torch.randint(-128, 128, (K, M), dtype=torch.int8, device="cuda", generator=g)
+            Bt = torch.randint(-128, 128, (N, K), dtype=torch.int8, device="cuda", generator=g)
+            bias = torch.randint(-(1 << 15), 1 << 15, (N,), dtype=torch.int32, device="cuda", generator=g)
+            C = torch.empty((M, N), dtype=torch.int8, device="cuda")
+            w = Workload("supplementary_gemm_i8_t_8192", "gemm_i8_t", "i8", 2 * M * N * K, 0,
+                         lambda: ops.ac_gemm_i8_t(At, Bt, bias, C, 12, 1, trans_a=True, trans_b=True), [], "")
+            ms = isolated_time(w, stream, reps=5, rounds=3)
+            out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"]})
+            del At, Bt, C
         for case in inputs.CONV_I8:
             Nb = 256
             name = "supplementary_" + case.name + "_Nb256"

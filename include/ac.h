@@ -139,8 +139,10 @@ ac_status ac_gemm_i8_acc32(const int8_t* A, int64_t lda, const int8_t* B, int64_
  *   trans_a != 0: A points to A^T, a K x M row-major array with row stride lda >= M
  *   trans_b != 0: B points to B^T, an N x K row-major array with row stride ldb >= K
  * Everything else (bias, output stage, C, error behaviour) as for ac_gemm_i8; with both flags zero the call
- * is ac_gemm_i8 without a workspace.  Transposed operands run on a kernel of their own, which stages each
- * operand in LDS in its memory order and transposes in the LDS read; it takes any alignment.
+ * is ac_gemm_i8 without a workspace.  An operand is staged in LDS in its memory order and the transposition
+ * happens in the LDS read.  Operands that qualify for the direct-to-LDS kernels (16-byte aligned base pointers
+ * and row pitches; M (when trans_a), N and K multiples of 16) run on those, at the rate of the untransposed
+ * product and never with a cut K range; anything else, any alignment included, on a register-staged kernel.
  */
 ac_status ac_gemm_i8_t(const int8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
                        const int32_t* bias, int64_t bias_ld, int8_t* C, int64_t ldc,

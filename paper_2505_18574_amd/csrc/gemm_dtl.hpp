@@ -188,10 +188,18 @@ static __device__ __forceinline__ void tile_coords_mul(int b, int nblocks, int t
   tn = qn;
 }
 
-template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, int STAGES, int KTB_, bool PINGPONG>
+// TA / TB (int8 GEMM on square tiles): A is given as A^T (K x M, row pitch lda) / B as B^T (N x K, row pitch ldb).
+// A transposed operand takes the other operand's role in LDS: A^T is "K-strided" like B (k-rows of BM bytes, the
+// B swizzle, fragments through the transposing reads), B^T is "K-contiguous" like A (rows of KTB bytes, the A
+// swizzle, 16-byte fragment reads).  With BM == BN the tiles, the instruction counts and the lane roles of the two
+// forms coincide, so only the source offsets, the advance per K tile and the fragment addresses differ.
+template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, int STAGES, int KTB_, bool PINGPONG, bool TA = false, bool TB = false>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const GemmParams p, const int tiles_m, const int tiles_n, const unsigned band_magic) {
   using G = DtlGeometry<T, BM, BN, WAVES_M, WAVES_N, STAGES, KTB_>;
   constexpr int EB = G::EB;
+  static_assert(!(TA || TB) || (BM == BN && AMODE == 0 && EB == 1), "transposed operands: int8 GEMM on square tiles");
+  constexpr int AT_ROW = BM * EB, AT_SPR = AT_ROW / 16, AT_RPI = 64 / AT_SPR;  // A^T tile: bytes, slots per k-row, k-rows per instruction
+  static_assert(!(TA || TB) || AT_ROW == G::B_ROW, "a transposed operand reuses the other operand's LDS geometry");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const unsigned lds0 = (unsigned)(uintptr_t)AC_LDS(unsigned char, smem);
 
@@ -218,6 +226,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
 #pragma unroll
   for (int v = 0; v < NVAR; v++) a_chunk[v] = (lane % G::A_SPR) ^ G::a_xor(v * G::A_ROWS_PER_INSTR + lane / G::A_SPR);
   const int64_t b_step = (int64_t)G::BK * p.ldb * EB;
+  const int64_t a_step_t = (int64_t)G::BK * p.lda * EB;  // A^T: one K tile further down
   v4i a_rsrc = {0, 0, 0, 0};  // buffer descriptor of the input image: base, size in bytes, raw dword format
   if constexpr (AMODE == 1) {
     const uint64_t ab = (uint64_t)(uintptr_t)p.A;
@@ -247,7 +256,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   // (kh, kw, ci) counter with its loops.
   int split = 0, kt0 = 0, m0 = 0, n0 = 0;
   unsigned a_voff[G::A_INSTR], b_voff[G::B_INSTR];
-  int b_krow[G::B_INSTR];
+  int b_krow[G::B_INSTR], a_krow[G::A_INSTR];
   int g_base[G::A_INSTR];
   unsigned g_mask[G::A_INSTR];
   unsigned g_kb[NVAR];
@@ -265,8 +274,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     for (int i = 0; i < G::A_INSTR; i++) {
       const int row = (wave * G::A_INSTR + i) * G::A_ROWS_PER_INSTR + lane / G::A_SPR;
       const int v = (wave * G::A_INSTR + i) & (NVAR - 1);
-      g_base[i] = 0, g_mask[i] = 0u, a_voff[i] = 0;
-      if constexpr (AMODE == 0) {
+      g_base[i] = 0, g_mask[i] = 0u, a_voff[i] = 0, a_krow[i] = 0;
+      if constexpr (TA) {
+        const int krow = (wave * G::A_INSTR + i) * AT_RPI + lane / AT_SPR;
+        const int ls = BSwizzle<EB, AT_ROW>::slot(lane % AT_SPR, krow);
+        a_krow[i] = krow;
+        a_voff[i] = (unsigned)krow * (unsigned)(p.lda * EB) + ((m0 + ls * 16) * EB < p.M * EB ? ls * 16 : 0);
+      } else if constexpr (AMODE == 0) {
         const int rclamp = m0 + row < p.M ? row : p.M - 1 - m0;
         a_voff[i] = (unsigned)rclamp * (unsigned)(p.lda * EB) + a_chunk[v] * 16;
       } else {
@@ -290,13 +304,22 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     }
 #pragma unroll
     for (int i = 0; i < G::B_INSTR; i++) {
+      if constexpr (TB) {
+        const int nrow = (wave * G::B_INSTR + i) * G::A_ROWS_PER_INSTR + lane / G::A_SPR;
+        const int rclamp = n0 + nrow < p.N ? nrow : p.N - 1 - n0;
+        b_krow[i] = 0;
+        b_voff[i] = (unsigned)rclamp * (unsigned)(p.ldb * EB) + a_chunk[(wave * G::B_INSTR + i) & (NVAR - 1)] * 16;
+        continue;
+      }
       const int row = (wave * G::B_INSTR + i) * G::B_ROWS_PER_INSTR + lane / G::B_SPR;
       const int ls = BSwizzle<EB, G::B_ROW>::slot(lane % G::B_SPR, row);
       b_krow[i] = row;
       b_voff[i] = (unsigned)row * (unsigned)(p.ldb * EB) + (n0 * EB + ls * 16 < nbytes ? ls * 16 : 0);
     }
-    a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda * EB : 0) + (int64_t)kt0 * G::KTB;
-    b_base = (const unsigned char*)p.B + (int64_t)n0 * EB + kt0 * b_step;
+    if constexpr (TA) a_base = (const unsigned char*)p.A + (int64_t)m0 * EB + kt0 * a_step_t;
+    else a_base = (const unsigned char*)p.A + (AMODE == 0 ? (int64_t)m0 * p.lda * EB : 0) + (int64_t)kt0 * G::KTB;
+    if constexpr (TB) b_base = (const unsigned char*)p.B + (int64_t)n0 * p.ldb * EB + (int64_t)kt0 * G::KTB;
+    else b_base = (const unsigned char*)p.B + (int64_t)n0 * EB + kt0 * b_step;
 #pragma unroll
     for (int v = 0; v < NVAR; v++) g_kb[v] = (unsigned)(kt0 * G::KTB + a_chunk[v] * 16);
   };
@@ -328,6 +351,12 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     } else if (full) {
 #pragma unroll
       for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], As + (wave * G::A_INSTR + i) * 1024);
+    } else if constexpr (TA) {
+#pragma unroll
+      for (int i = 0; i < G::A_INSTR; i++) {
+        const int k = kt * G::BK + a_krow[i];
+        load_to_lds16(k < p.K ? a_base + a_voff[i] : zero, As + (wave * G::A_INSTR + i) * 1024);
+      }
     } else {
 #pragma unroll
       for (int i = 0; i < G::A_INSTR; i++) {
@@ -339,6 +368,12 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     if (full) {  // every k-row of the tile exists; columns beyond N were clamped when b_voff was set up
 #pragma unroll
       for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], Bs + (wave * G::B_INSTR + i) * 1024);
+    } else if constexpr (TB) {
+#pragma unroll
+      for (int i = 0; i < G::B_INSTR; i++) {
+        const int kb = kbase + a_chunk[(wave * G::B_INSTR + i) & (NVAR - 1)] * 16;
+        load_to_lds16(kb < kbytes ? b_base + b_voff[i] : zero, Bs + (wave * G::B_INSTR + i) * 1024);
+      }
     } else {
 #pragma unroll
       for (int i = 0; i < G::B_INSTR; i++) {
@@ -346,8 +381,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
         load_to_lds16(k < p.K ? b_base + b_voff[i] : zero, Bs + (wave * G::B_INSTR + i) * 1024);
       }
     }
-    a_base += G::KTB;
-    b_base += b_step;
+    a_base += TA ? a_step_t : (int64_t)G::KTB;
+    b_base += TB ? (int64_t)G::KTB : b_step;
   };
 
   typename T::accv acc[G::TM][G::TN];
@@ -357,6 +392,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   // not change the swizzle term
   const int a_swz = G::a_xor(lane & 31);
   const int a_lane_off = (wm * G::WTM + (lane & 31)) * G::KTB;
+  const int b_lane_off_t = (wn * G::WTN + (lane & 31)) * G::KTB;  // B^T: the lane's row of the K-contiguous B tile
   struct Frag {
     v4i a[G::TM], b[G::TN];
   };
@@ -365,9 +401,15 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     const unsigned char* Bs = As + G::A_BYTES;
     const int chunk = 2 * ks + (lane >> 5);
 #pragma unroll
-    for (int i = 0; i < G::TM; i++) f.a[i] = *(const v4i*)(As + a_lane_off + i * 32 * G::KTB + ((chunk ^ a_swz) << 4));
+    for (int i = 0; i < G::TM; i++) {
+      if constexpr (TA) f.a[i] = dtl_read_col<T, AT_ROW>(As, chunk * 16, wm * G::TM + i, lane);
+      else f.a[i] = *(const v4i*)(As + a_lane_off + i * 32 * G::KTB + ((chunk ^ a_swz) << 4));
+    }
 #pragma unroll
-    for (int j = 0; j < G::TN; j++) f.b[j] = dtl_read_col<T, G::B_ROW>(Bs, chunk * 16, wn * G::TN + j, lane);
+    for (int j = 0; j < G::TN; j++) {
+      if constexpr (TB) f.b[j] = *(const v4i*)(Bs + b_lane_off_t + j * 32 * G::KTB + ((chunk ^ a_swz) << 4));
+      else f.b[j] = dtl_read_col<T, G::B_ROW>(Bs, chunk * 16, wn * G::TN + j, lane);
+    }
   };
   auto mfma_rows = [&](const Frag& f, int i0, int i1) {  // MFMA row tiles i0 .. i1-1 of one K-step
 #pragma unroll
@@ -382,25 +424,35 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   constexpr int ROWS_PER_CHUNK = 16 / EB;  // k-rows of B that 16 bytes of K span
   static_assert(ROWS_PER_CHUNK % SW::RPW == 0 && ((ROWS_PER_CHUNK / SW::RPW) & SW::MASK) == 0, "the B swizzle term must not depend on the K-step");
   constexpr int KS_B = (32 / EB) * G::B_ROW;  // bytes between the B rows of consecutive K-steps
-  int a_fo[G::KSTEPS], b_fo[G::TN];
+  // a K-contiguous operand needs one lane address per K-step (row tiles are an immediate apart), a K-strided one
+  // one per 32-column block (K-steps are an immediate apart)
+  constexpr int NAF = TA ? G::TM : G::KSTEPS, NBF = TB ? G::KSTEPS : G::TN;
+  constexpr int KS_A = (32 / EB) * AT_ROW;  // A^T: bytes between the rows of consecutive K-steps
+  int a_fo[NAF], b_fo[NBF];
 #pragma unroll
-  for (int ks = 0; ks < G::KSTEPS; ks++) a_fo[ks] = a_lane_off + (((2 * ks + (lane >> 5)) ^ a_swz) << 4);
+  for (int x = 0; x < NAF; x++) {
+    if constexpr (TA) a_fo[x] = dtl_col_off<T, AT_ROW>((lane >> 5) * 16, wm * G::TM + x, lane);
+    else a_fo[x] = a_lane_off + (((2 * x + (lane >> 5)) ^ a_swz) << 4);
+  }
 #pragma unroll
-  for (int j = 0; j < G::TN; j++) b_fo[j] = G::A_BYTES + dtl_col_off<T, G::B_ROW>((lane >> 5) * 16, wn * G::TN + j, lane);
+  for (int x = 0; x < NBF; x++) {
+    if constexpr (TB) b_fo[x] = G::A_BYTES + b_lane_off_t + (((2 * x + (lane >> 5)) ^ a_swz) << 4);
+    else b_fo[x] = G::A_BYTES + dtl_col_off<T, G::B_ROW>((lane >> 5) * 16, wn * G::TN + x, lane);
+  }
   // The immediate offset of an LDS read has 16 bits: stages that begin 64 KB or more into LDS are read through a
   // second set of lane addresses, 64 KB up (made opaque, or the compiler folds them back into one register per read).
   constexpr bool HI_STAGES = (STAGES - 1) * G::STAGE >= 65536;
   static_assert((STAGES - 1) * G::STAGE < 2 * 65536, "a third set of lane addresses would be needed");
-  int a_fo_hi[G::KSTEPS], b_fo_hi[G::TN];
+  int a_fo_hi[NAF], b_fo_hi[NBF];
 #pragma unroll
-  for (int ks = 0; ks < G::KSTEPS; ks++) {
-    a_fo_hi[ks] = a_fo[ks] + 65536;
-    if constexpr (HI_STAGES) asm volatile("" : "+v"(a_fo_hi[ks]));
+  for (int x = 0; x < NAF; x++) {
+    a_fo_hi[x] = a_fo[x] + 65536;
+    if constexpr (HI_STAGES) asm volatile("" : "+v"(a_fo_hi[x]));
   }
 #pragma unroll
-  for (int j = 0; j < G::TN; j++) {
-    b_fo_hi[j] = b_fo[j] + 65536;
-    if constexpr (HI_STAGES) asm volatile("" : "+v"(b_fo_hi[j]));
+  for (int x = 0; x < NBF; x++) {
+    b_fo_hi[x] = b_fo[x] + 65536;
+    if constexpr (HI_STAGES) asm volatile("" : "+v"(b_fo_hi[x]));
   }
   // K slices keep the general loops; the convolution gather handles a partial last tile itself
   const int nkt_whole = p.splits > 1 ? 0 : (AMODE == 0 ? kbytes / G::KTB : nkt_total);
@@ -410,25 +462,31 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], lds0 + LBUF * G::STAGE + (wave * G::A_INSTR + i) * 1024);
 #pragma unroll
     for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], lds0 + LBUF * G::STAGE + G::A_BYTES + (wave * G::B_INSTR + i) * 1024);
-    a_base += G::KTB;
-    b_base += b_step;
+    a_base += TA ? a_step_t : (int64_t)G::KTB;
+    b_base += TB ? (int64_t)G::KTB : b_step;
   };
   auto issue_whole_rt = [&](int lbuf) {  // the same with the stage as a value (constant after unrolling)
 #pragma unroll
     for (int i = 0; i < G::A_INSTR; i++) load_to_lds16_so(a_base, a_voff[i], lds0 + lbuf * G::STAGE + (wave * G::A_INSTR + i) * 1024);
 #pragma unroll
     for (int i = 0; i < G::B_INSTR; i++) load_to_lds16_so(b_base, b_voff[i], lds0 + lbuf * G::STAGE + G::A_BYTES + (wave * G::B_INSTR + i) * 1024);
-    a_base += G::KTB;
-    b_base += b_step;
+    a_base += TA ? a_step_t : (int64_t)G::KTB;
+    b_base += TB ? (int64_t)G::KTB : b_step;
   };
   auto read_frags_at = [&](auto bufc, int ks, Frag& f) {  // read_frags with the stage as a constant
     constexpr int BUF = decltype(bufc)::value;
     constexpr bool HI = BUF * G::STAGE >= 65536;
     constexpr int SOFF = BUF * G::STAGE - (HI ? 65536 : 0);
 #pragma unroll
-    for (int i = 0; i < G::TM; i++) f.a[i] = *(const v4i*)(smem + ((HI ? a_fo_hi[ks] : a_fo[ks]) + (SOFF + i * 32 * G::KTB)));
+    for (int i = 0; i < G::TM; i++) {
+      if constexpr (TA) f.a[i] = dtl_read_col_at<T, AT_ROW>(smem + ((HI ? a_fo_hi[i] : a_fo[i]) + (SOFF + ks * KS_A)));
+      else f.a[i] = *(const v4i*)(smem + ((HI ? a_fo_hi[ks] : a_fo[ks]) + (SOFF + i * 32 * G::KTB)));
+    }
 #pragma unroll
-    for (int j = 0; j < G::TN; j++) f.b[j] = dtl_read_col_at<T, G::B_ROW>(smem + ((HI ? b_fo_hi[j] : b_fo[j]) + (SOFF + ks * KS_B)));
+    for (int j = 0; j < G::TN; j++) {
+      if constexpr (TB) f.b[j] = *(const v4i*)(smem + ((HI ? b_fo_hi[ks] : b_fo[ks]) + (SOFF + j * 32 * G::KTB)));
+      else f.b[j] = dtl_read_col_at<T, G::B_ROW>(smem + ((HI ? b_fo_hi[j] : b_fo[j]) + (SOFF + ks * KS_B)));
+    }
   };
 
   // Persistent workgroups: each takes output tiles blockIdx.x, blockIdx.x + gridDim.x, ...  gridDim.x is a multiple
@@ -662,10 +720,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
   } while ((work += gridDim.x) < nwork);  // tile loop
 }
 
-template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, int STAGES, int KTB_ = 128, bool PINGPONG = false>
+template <class T, class EPI, int BM, int BN, int WAVES_M, int WAVES_N, int AMODE, int STAGES, int KTB_ = 128, bool PINGPONG = false, bool TA = false, bool TB = false>
 static hipError_t launch_dtl(const GemmParams& p, hipStream_t stream) {
   using G = DtlGeometry<T, BM, BN, WAVES_M, WAVES_N, STAGES, KTB_>;
-  auto kern = gemm_dtl_kernel<T, EPI, BM, BN, WAVES_M, WAVES_N, AMODE, STAGES, KTB_, PINGPONG>;
+  auto kern = gemm_dtl_kernel<T, EPI, BM, BN, WAVES_M, WAVES_N, AMODE, STAGES, KTB_, PINGPONG, TA, TB>;
   static std::atomic<bool> configured{G::LDS_BYTES <= 64 * 1024};
   if (const hipError_t e = allow_dynamic_lds_once(configured, kern, G::LDS_BYTES)) return e;
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;

@@ -7,7 +7,13 @@
 // K-contiguous row, or the transposing ds_read_b64_tr_b8 pair down a K-strided tile.  Both deliver the same
 // MFMA operand (row or column l % 32, 16 bytes of K selected by l / 32), so the four combinations share one
 // body.  Register-staged double buffering, guarded loads: any alignment and any M, N, K.
-#include "gemm_mfma.hpp"
+//
+// Operands that qualify for the direct-to-LDS kernels (16-byte aligned bases and pitches, M, N and K in whole
+// 16-byte chunks) run on those instead, with the transposed operand in the other operand's LDS role (TA / TB of
+// gemm_dtl_kernel): the same tiles, pipeline and output stage as the untransposed product.
+#include <algorithm>
+
+#include "gemm_dtl.hpp"
 
 namespace ac {
 
@@ -167,9 +173,34 @@ static hipError_t launch_trans(const GemmParams& p, hipStream_t stream, bool ali
   return hipGetLastError();
 }
 
+template <bool TA, bool TB>
+static hipError_t launch_trans_dtl(const GemmParams& p0, hipStream_t stream) {
+  GemmParams p = p0;
+  p.splits = 1;
+  p.kt_per_split = 0;
+  switch (choose_tile_i8(p.M, p.N, p.K, false)) {  // square tiles only: the 256 x 128 code falls to 128
+    case 256: return launch_dtl<TypeI8, EpilogueI8, 256, 256, 2, 4, 0, 4, 64, true, TA, TB>(p, stream);
+    case 192:
+    case 128: return launch_dtl<TypeI8, EpilogueI8, 128, 128, 2, 4, 0, 3, 128, false, TA, TB>(p, stream);
+    default: return launch_dtl<TypeI8, EpilogueI8, 64, 64, 2, 2, 0, 4, 128, false, TA, TB>(p, stream);
+  }
+}
+
 // A is K x M when trans_a, B is N x K when trans_b (both row-major with their own leading dimension).
 hipError_t launch_gemm_i8_trans(const GemmParams& p, bool trans_a, bool trans_b, hipStream_t stream) {
   if (!trans_a && !trans_b) return launch_gemm_i8(p, stream);
+  // direct-to-LDS kernels: whole 16-byte chunks along every contiguous dimension, and row pitches that keep a lane's
+  // offset from its tile's first row in 32 bits (a K-contiguous operand spans up to 320 rows, a K-strided one 128)
+  const int64_t pitch_kc = std::max<int64_t>(trans_a ? 0 : p.lda, trans_b ? p.ldb : 0);
+  const int64_t pitch_ks = std::max<int64_t>(trans_a ? p.lda : 0, trans_b ? 0 : p.ldb);
+  const bool fast = (((uintptr_t)p.A | (uintptr_t)p.B) & 15) == 0 && p.lda % 16 == 0 && p.ldb % 16 == 0 && ((uintptr_t)p.C & 3) == 0 &&
+                    p.ldc % 4 == 0 && p.K % 16 == 0 && p.N % 16 == 0 && (!trans_a || p.M % 16 == 0) && p.K > 0 &&
+                    lane_offsets_fit(pitch_kc, pitch_ks);
+  if (fast) {
+    if (trans_a && trans_b) return launch_trans_dtl<true, true>(p, stream);
+    if (trans_a) return launch_trans_dtl<true, false>(p, stream);
+    return launch_trans_dtl<false, true>(p, stream);
+  }
   // 16-byte vector loads and 4-byte packed stores need aligned bases and pitches
   const bool aligned = (((uintptr_t)p.A | (uintptr_t)p.B) & 15) == 0 && p.lda % 16 == 0 && p.ldb % 16 == 0 &&
                        ((uintptr_t)p.C & 3) == 0 && p.ldc % 4 == 0;

@@ -43,6 +43,19 @@ def test_shapes_bit_exact(M, N, K, ta, tb):
     np.testing.assert_array_equal(run(A, B, bias, 9, 1, ta, tb), want)
 
 
+# Operands the direct-to-LDS kernels take (aligned, M, N and K in whole 16-byte chunks): every square tile size,
+# ragged edges, a partial last K tile, several tiles per compute unit (the persistent loop with its prefetch of
+# the next tile), one K tile, a deep K
+@pytest.mark.parametrize("ta,tb", FLAGS[:3])
+@pytest.mark.parametrize("M,N,K", [(16, 16, 16), (64, 64, 128), (80, 112, 208), (304, 272, 4160), (2112, 2064, 208), (1024, 1024, 1024),
+                                    (4096, 3072, 64), (4352, 4368, 320), (8192, 256, 576), (256, 8192, 48)])
+def test_direct_to_lds_shapes(M, N, K, ta, tb):
+    A, B, bias = inputs.gemm_i8_inputs(M, N, K, seed=M + 2 * N + 3 * K)
+    want = oracle.gemm_i8(A, B, bias, 10, 1)
+    np.testing.assert_array_equal(run(A, B, bias, 10, 1, ta, tb), want)
+    np.testing.assert_array_equal(run(A, B, bias, 10, 1, ta, tb, pad=64), want)  # row pitch beyond the row
+
+
 @pytest.mark.parametrize("ta,tb", FLAGS[:3])
 def test_small_values_matrix_bias_and_unaligned_views(ta, tb):
     M, N, K = 100, 72, 200

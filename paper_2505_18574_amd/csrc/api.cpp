@@ -57,7 +57,7 @@ size_t ac_gemm_i8_workspace_bytes(int32_t M, int32_t N, int32_t K) {
   if (M <= 0 || N <= 0 || K <= 0 || !gemm_dims_supported(M, N, K)) return 0;
   // the plan for operands that the one-wave-per-tile kernel does not take (and for the convolution with this
   // implicit-GEMM shape): the most any launch of the shape asks for
-  const ac::GemmPlan plan = ac::plan_gemm_i8(M, N, K, true, false);
+  const ac::GemmPlan plan = ac::plan_gemm_i8(M, N, K, true, 0);
   if (plan.splits <= 1) return 0;
   // int32 partial sums of every K slice
   return (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(int32_t);
@@ -85,7 +85,7 @@ size_t ac_gemm_bf16_planned_workspace_bytes(int32_t M, int32_t N, int32_t K, int
 
 void ac_gemm_i8_auto_plan(int32_t M, int32_t N, int32_t K, int32_t have_workspace, int32_t* tile, int32_t* splits) {
   if (!gemm_dims_supported(M, N, K)) M = N = K = 0;  // sizes the calls refuse: the plan of the empty problem
-  const ac::GemmPlan plan = ac::plan_gemm_i8(M, N, K, have_workspace != 0, true);
+  const ac::GemmPlan plan = ac::plan_gemm_i8(M, N, K, have_workspace != 0, 1);
   if (tile) *tile = plan.tile;
   if (splits) *splits = plan.splits;
 }

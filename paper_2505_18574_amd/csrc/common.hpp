@@ -107,8 +107,9 @@ struct GemmPlan {
   int splits;        // K slices (1 = no split)
   int kt_per_split;  // K tiles per slice (0 when splits == 1)
 };
-// allow_small: the operands qualify for the one-wave-per-tile kernel (tile code 32), so the plan may name it
-GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace, bool allow_small);
+// small_kernel: whether the plan may name the one-wave-per-tile kernel (tile code 32): 0 = the operands do not
+// qualify for it, 1 = a GEMM that does, 2 = a convolution that does (its alternative is the tiled gather)
+GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace, int small_kernel);
 GemmPlan plan_gemm_bf16(int32_t M, int32_t N, int32_t K);
 // Rows / columns of a tile code (false for an unknown code).
 bool tile_dims(int32_t tile, int* bm, int* bn);

@@ -155,7 +155,7 @@ bool conv_halo_eligible(const GemmParams& p, int tile) {
 // Kernel / tile and K split for an M x N x K int8 problem.  With more 64 x 64 tiles than the chip holds at once:
 // the code with the lowest time estimate (choose_tile_i8), unsplit.  With fewer: tile and K slices together from
 // the cost estimate of plan_few_tiles (slicing needs the caller's workspace for the int32 partial sums).
-GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace, bool allow_small) {
+GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace, int small_kernel) {
   GemmPlan plan;
   plan.splits = 1;
   plan.kt_per_split = 0;
@@ -166,13 +166,16 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace, bool
   // 32 x 32) x 14 depths on this chip has it ahead of every tiled plan with operands in the caches and level with
   // them with operands in HBM: the fewer the tiles, the deeper the K that a lone wave per tile still wins with (at
   // 1024 tiles the 64 x 64 tiles share operands through LDS and win from K = 512).  Warm margins: 256^3 2.9 vs
-  // 3.6 us, 512 x 768 x 768 3.9 vs 4.6, 128 x 1024 x 1024 3.9 vs 4.5, 2048 x 1024 x 128 3.7 vs 4.1.  Deeper K with
+  // 3.6 us, 512 x 768 x 768 3.9 vs 4.6, 128 x 1024 x 1024 3.9 vs 4.5, 2048 x 1024 x 320 4.9 vs 5.1.  Deeper K with
   // few tiles is also ahead warm (128 x 1024 x 3072: 6.8 vs 8.8 us for a cut K) but well behind from HBM (14.5 vs
   // 10.6 us: a cut K has eight times the loads in flight), and 784 x 512 x 1152 gives from HBM what it gains warm
   // (7.9 vs 7.0, 4.6 vs 5.0): both stay on the tiled plans.
-  if (allow_small && K >= SMALL_KTB && K % SMALL_KTB == 0 && (K <= 640 || K % 128 == 0)) {
+  // Against the convolution gather of the 64 x 64 tiles it stays ahead further: 8 images of 56 x 56 x 64 -> 64 (1568
+  // tiles, K = 576) 5.7 against 6.5 us warm, 6.5 against 6.9 from HBM; not at 3136 tiles (11.9 against 8.0).
+  if (small_kernel != 0 && K >= SMALL_KTB && K % SMALL_KTB == 0 && (K <= 640 || K % 128 == 0)) {
     const int64_t tiles32 = (int64_t)((M + 31) / 32) * ((N + 31) / 32);
-    const int kmax = tiles32 <= 512 ? 1024 : tiles32 <= 1024 ? 384 : tiles32 <= 2048 ? 128 : 0;
+    int kmax = tiles32 <= 512 ? 1024 : tiles32 <= 1024 ? 384 : tiles32 <= 2048 ? 320 : 0;
+    if (small_kernel == 2 && tiles32 <= 2048 && kmax < 640) kmax = 640;
     if (K <= kmax) {
       make_plan_i8(K, 32, 1, &plan);
       return plan;
@@ -293,7 +296,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_i8_kernel(const GemmParams 
 template <int AMODE>
 hipError_t dispatch_i8(GemmParams p, hipStream_t stream, bool aligned, bool fast, const GemmPlan* forced) {
   // the one-wave-per-tile kernel is planned only for operands it takes
-  GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr, fast && small_i8_eligible(p));
+  GemmPlan plan = forced ? *forced : plan_gemm_i8(p.M, p.N, p.K, fast && p.partial != nullptr, fast && small_i8_eligible(p) ? 1 + AMODE : 0);
   int ws_bm;
   if (!forced && wstat_tile_rows(plan.tile, &ws_bm) && !(fast && wstat_eligible(p, plan.tile))) {
     plan.tile = choose_tile_i8(p.M, p.N, p.K, false);  // operands the weight-stationary kernel does not take: the tiled kernels
@@ -420,7 +423,7 @@ hipError_t launch_conv2d_i8(const GemmParams& p, hipStream_t stream, const GemmP
     // tile, by the GEMM's rule: 56 x 56 x 64 -> 64, one image, 4.4 us against 5.4; K = 1152 gains 0.5 us with the
     // input in the caches and loses up to 1 us with it in HBM, as for the GEMM), never the weight-stationary
     // kernel, whose gather loses to both (28 x 28 x 128 -> 128, 32 images: 13.9 us against 10.2)
-    GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, p.partial != nullptr, small_i8_eligible(p));
+    GemmPlan plan = plan_gemm_i8(p.M, p.N, p.K, p.partial != nullptr, small_i8_eligible(p) ? 2 : 0);
     int ws_bm;
     if (wstat_tile_rows(plan.tile, &ws_bm)) make_plan_i8(p.K, choose_tile(p.M, p.N), 1, &plan);  // unsplit: no workspace needed
     return dispatch_i8<1>(p, stream, aligned, fast, &plan);

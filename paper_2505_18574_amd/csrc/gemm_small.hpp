@@ -238,7 +238,8 @@ static hipError_t launch_small_i8(const GemmParams& p, hipStream_t stream) {
   if (p.splits > 1) return launch_small_i8_cfg<64, 4, 2, AMODE, true>(p, stream);
   const int64_t ntiles = (int64_t)((p.M + 31) / 32) * ((p.N + 31) / 32);
   if (p.K <= 128) return launch_small_i8_cfg<64, 3, 4, AMODE>(p, stream);
-  if (p.K % 128 != 0) return launch_small_i8_cfg<64, 4, 2, AMODE>(p, stream);
+  // 16 KB rings in pairs: ten waves per compute unit, 2560 tiles at once (the 24 KB rings hold 1536)
+  if (p.K % 128 != 0 || ntiles > 1536) return launch_small_i8_cfg<64, 4, 2, AMODE>(p, stream);
   return ntiles <= 256 ? launch_small_i8_cfg<128, 3, 1, AMODE>(p, stream) : launch_small_i8_cfg<128, 3, 2, AMODE>(p, stream);
 }
 

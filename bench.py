@@ -5,7 +5,11 @@ A *step* is one pass of the whole hot path: every workload configuration launche
 on one stream -- the 256^3 int8 GEMM, the six-shape int8 GEMM sweep, the two int8 convolutions, the two
 bf16 GEMMs and the batched 12x12 fp32 problem (12 calls; a call that slices K launches a second kernel).  Inputs are seeded, synthetic and already
 resident in HBM when the timed region starts.  The pass is captured once in a HIP graph and replayed,
-so that host launch overhead does not hide the kernels.
+so that host launch overhead does not hide the kernels.  The nine int8 launches of the pass last 3-9 us each on a
+fraction of the chip and are independent problems, so the graph runs them on three parallel branches (the main
+stream and two side streams, joined before the two bf16 GEMMs and the batched kernel, which run one after
+another; two to four branches measured 339-340 us against 357 us on one stream, six and nine 341-347); `ms_per_step_one_stream` is the same pass with every launch on one stream, and
+`pass_outputs_equal_one_stream` says that both forms leave the same bits in every output buffer.
 
 Prints ONE JSON line: whole-step throughput, per-workload rates and roofline fractions, the roofline
 record of the dominant kernel, and the CPU oracle timed on a bounded sample of the same workloads.
@@ -56,8 +60,9 @@ def dev(a):
 class Workload:
     """One configuration: device buffers, a call that takes them, op and byte counts."""
 
-    def __init__(self, name, kind, dtype, ops_count, bytes_count, call, buffers, kernel):
+    def __init__(self, name, kind, dtype, ops_count, bytes_count, call, buffers, kernel, out_idx=()):
         self.name, self.kind, self.dtype = name, kind, dtype
+        self.out_idx = out_idx  # which of the buffers the call writes
         self.ops, self.bytes = ops_count, bytes_count
         self.call = call  # call(*buffers) launches the workload on that set of device buffers (None entries stay None)
         self.buffers = buffers
@@ -65,6 +70,9 @@ class Workload:
 
     def launch(self):
         self.call(*self.buffers)
+
+    def outputs(self):
+        return [self.buffers[i] for i in self.out_idx]
 
     def buffer_copies(self, count):
         """`count` further sets of the same buffers, each in memory of its own."""
@@ -83,7 +91,7 @@ def make_workloads():
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
         wl.append(Workload(case.name, "gemm_i8", "i8", case.ops, case.bytes,
                            lambda A, B, bias, C, ws, c=case: ops.ac_gemm_i8(A, B, bias, C, c.shift, c.act, workspace=ws),
-                           [A, B, bias, C, ws], "gemm_dtl_kernel<TypeI8,...,AMODE=0>"))
+                           [A, B, bias, C, ws], "gemm_dtl_kernel<TypeI8,...,AMODE=0>", out_idx=(3,)))
     for case in inputs.CONV_I8:
         x, w, bias = (dev(t) for t in inputs.conv_i8_case_inputs(case))
         out = torch.empty((case.Nb, case.OH, case.OW, case.Cout), dtype=torch.int8, device="cuda")
@@ -91,26 +99,51 @@ def make_workloads():
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
         wl.append(Workload(case.name, "conv2d_i8", "i8", case.ops, case.bytes,
                            lambda x, w, bias, out, ws, c=case: ops.ac_conv2d_i8(x, w, bias, out, c.stride, c.pad, c.shift, c.act, workspace=ws),
-                           [x, w, bias, out, ws], "gemm_dtl_kernel<TypeI8,...,AMODE=1>"))
+                           [x, w, bias, out, ws], "gemm_dtl_kernel<TypeI8,...,AMODE=1>", out_idx=(3,)))
     for case in inputs.GEMM_BF16:
         A, B = (dev(t) for t in inputs.gemm_bf16_case_inputs(case))
         C = torch.empty((case.M, case.N), dtype=torch.float32, device="cuda")
         wl.append(Workload(case.name, "gemm_bf16", "bf16", case.ops, case.bytes,
                            lambda A, B, C: ops.ac_gemm_bf16(A, B, C, 1.0, 0.0),
-                           [A, B, C], "gemm_dtl_kernel<TypeBF16,EpilogueF32,256,256,2,4,0,4,64,true>"))
+                           [A, B, C], "gemm_dtl_kernel<TypeBF16,EpilogueF32,256,256,2,4,0,4,64,true>", out_idx=(2,)))
     case = inputs.BATCHED_F32
     A, B, x, d = (dev(t) for t in inputs.batched_f32_case_inputs(case))
     C = torch.empty((case.batch, case.n, case.n), dtype=torch.float32, device="cuda")
     y = torch.empty((case.batch, case.n), dtype=torch.float32, device="cuda")
     wl.append(Workload(case.name, "batched_f32", "f32", case.ops, case.bytes,
                        lambda A, B, C, x, d, y: ops.ac_batched_gemm_f32(A, B, C, x, d, y),
-                       [A, B, C, x, d, y], "batched12_stream_kernel"))
+                       [A, B, C, x, d, y], "batched12_stream_kernel", out_idx=(2, 5)))
     return wl
 
 
 def run_pass(wl):
     for w in wl:
         w.launch()
+
+
+def is_small(w):
+    """A launch that lasts microseconds and fills a fraction of the chip (everything but the two bf16 GEMMs and the
+    batched stream)."""
+    return w.ops < 1e10 and w.bytes < 5e7
+
+
+def run_pass_forked(wl, stream, sides):
+    """The same pass with its microsecond-sized launches spread round-robin over `stream` and the side streams
+    (they are independent problems on buffers and workspaces of their own), joined before the large launches, which
+    stay one after another on `stream`.  Captured, this is a graph with parallel branches."""
+    small = [w for w in wl if is_small(w)]
+    large = [w for w in wl if not is_small(w)]
+    lanes = [stream] + list(sides)
+    for s in sides:
+        s.wait_stream(stream)
+    for i, w in enumerate(small):
+        with torch.cuda.stream(lanes[i % len(lanes)]):
+            w.launch()
+    for s in sides:
+        stream.wait_stream(s)
+    with torch.cuda.stream(stream):
+        for w in large:
+            w.launch()
 
 
 def capture(fn, stream):
@@ -421,6 +454,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-graph", action="store_true", help="launch the pass eagerly instead of replaying a HIP graph")
+    ap.add_argument("--serial-pass", action="store_true", help="time the pass with every launch on one stream (the default spreads the "
+                    "microsecond-sized launches over parallel branches of the graph and reports the one-stream time beside it)")
+    ap.add_argument("--branches", type=int, default=3, help="parallel branches for the microsecond-sized launches of the pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-supplementary", action="store_true")
     ap.add_argument("--no-isolated", action="store_true",
@@ -473,15 +509,35 @@ def main():
     with torch.cuda.stream(stream):
         run_pass(wl)  # first launch of every kernel outside any capture
         stream.synchronize()
+        sides = [torch.cuda.Stream() for _ in range(max(1, args.branches) - 1)]
         if args.no_graph:
-            step = lambda: run_pass(wl)
+            step_serial = lambda: run_pass(wl)
+            step = step_serial if args.serial_pass else (lambda: run_pass_forked(wl, stream, sides))
         else:
-            graph = capture(lambda: run_pass(wl), stream)
-            step = graph.replay
+            graph_serial = capture(lambda: run_pass(wl), stream)
+            step_serial = graph_serial.replay
+            if args.serial_pass:
+                step = step_serial
+            else:
+                graph = capture(lambda: run_pass_forked(wl, stream, sides), stream)
+                step = graph.replay
+        # the forked pass must leave what the serial pass leaves in every output buffer
+        step_serial()
+        stream.synchronize()
+        want = [[t.clone() for t in w.outputs()] for w in wl]
+        for w in wl:
+            for t in w.outputs():
+                t.fill_(0)
+        step()
+        stream.synchronize()
+        outputs_equal = all(torch.equal(a, b) for w, ws_ in zip(wl, want) for a, b in zip(w.outputs(), ws_))
         for _ in range(args.warmup):
             step()
         regions = [time_region(step, args.steps) for _ in range(TIMED_REGIONS)]
         ms_per_step = float(np.median(regions))
+        for _ in range(args.warmup):
+            step_serial()
+        regions_serial = [time_region(step_serial, args.steps) for _ in range(TIMED_REGIONS)]
         kt, event_pair_ms = per_kernel_times(wl, min(args.steps, 50), stream)
 
     total_ops = float(sum(w.ops for w in wl))
@@ -576,7 +632,7 @@ def main():
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "i8+bf16+f32", "data": "synthetic",
         "config": {"workload": "one pass over all five workload configurations (12 calls): " + ", ".join(w.name for w in wl),
-                   "launch": "eager" if args.no_graph else "hip-graph replay", "sum_kernel_ms": round(float(kt.sum()), 5)},
+                   "launch": ("eager" if args.no_graph else "hip-graph replay") + (", one stream" if args.serial_pass else f", the microsecond-sized launches on {max(1, args.branches)} parallel branches"), "sum_kernel_ms": round(float(kt.sum()), 5)},
         "roofline": roof,
         # the two rates the metric names, each over its own launches (ops of that type / their summed launch times)
         "rates": rates,
@@ -584,6 +640,8 @@ def main():
         "launch_floor": None if floor_us is None else {"us": round(floor_us, 3), "us_min": round(floor_min_us, 3),
                                                        "kernel": "one-element fill as a graph node, replayed like the isolated workloads"},
         "timed_regions": TIMED_REGIONS, "ms_per_step_regions": [round(r, 5) for r in regions],
+        # the same pass with all launches on one stream, and whether both forms left the same bits in every output
+        "ms_per_step_one_stream": round(float(np.median(regions_serial)), 5), "pass_outputs_equal_one_stream": bool(outputs_equal),
         "per_workload": per,
     }
     if not args.no_supplementary and not args.only:

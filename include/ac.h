@@ -248,7 +248,13 @@ ac_status ac_batched_gemm_f32(const float* A, const float* B, float* C,
  *   x_out  device, fp32, [batch][horizon + 1][nx], or NULL: the state trajectory x[0..horizon]; when NULL the
  *          state after the last control, which the paper notes is never used, is not computed
  *   1 <= nx, nu <= 16 (the paper's problem has nx = 12, nu = 4, horizon = 5); horizon == 0 or batch == 0
- *   return AC_OK without a launch.  Every sum is an fp32 fused multiply-add chain in ascending index order.
+ *   return AC_OK without a launch.  Arithmetic is fp32 throughout.  With nx = 12, nu = 4 and x0, d, u, x_out
+ *   16-byte aligned the call runs on the matrix units: u[i] is substituted into the state update,
+ *   [x[i+1]; u[i]] = [Adyn - Bdyn Kinf, -Bdyn; -Kinf, -I] . [x[i]; d[i]], with Adyn - Bdyn Kinf formed first (four
+ *   fused multiply-adds per entry) and the sums of a product in the matrix unit's order; this equals the
+ *   recurrence in exact arithmetic (and bit for bit on small-integer data) and differs from it by rounding, a few
+ *   units in the last place per step.  Every other case evaluates the recurrence as written, each sum a fused
+ *   multiply-add chain in ascending index order.
  */
 ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const float* Kinf,
                                  const float* x0, const float* d, float* u, float* x_out,

@@ -1,8 +1,10 @@
 """GPU parity: ac_tinympc_forward_f32 against the fp64 oracle of the printed recurrence (Appendix D.2).
 
-fp32 fused multiply-add chains of at most nx + nu terms per element and `horizon` dependent steps: rounding stays
-near 1e-6 relative to the magnitudes involved, so the bar is the fp32 one of the library (relative Frobenius
-error <= 1e-5 over the batch)."""
+fp32 sums of at most nx + nu terms per element and `horizon` dependent steps (fused multiply-add chains, or for the
+paper's sizes 16 x 16 products on the matrix units with u substituted into the state update): rounding stays near
+1e-6 relative to the magnitudes involved, so the bar is the fp32 one of the library (relative Frobenius error
+<= 1e-5 over the batch).  Both kernel families are covered: (12, 4) with aligned arrays takes the matrix units (horizon
+5 with whole-run loads and stores, other horizons per lane), everything else the vector ALU."""
 import numpy as np
 import pytest
 import torch
@@ -40,7 +42,23 @@ def test_shapes(nx, nu, horizon, batch):
     np.testing.assert_array_equal(u2, u)
 
 
-@pytest.mark.parametrize("horizon,batch", [(3, 77), (5, 77), (5, 700)])
+def test_paper_sizes_on_unaligned_arrays():
+    """(12, 4, 5) with x0 and u four bytes off a 16-byte boundary: the vector-ALU kernel, same bar."""
+    batch, horizon = 333, 5
+    Adyn, Bdyn, Kinf, x0, d = inputs.tinympc_inputs(batch, seed=4242)
+    Adyn = (Adyn / 2).astype(np.float32)
+    uw, xw = oracle.tinympc_forward(Adyn, Bdyn, Kinf, x0, d, return_x=True)
+    x0_buf = torch.zeros(batch * 12 + 1, dtype=torch.float32, device="cuda")
+    u_buf = torch.full((batch * horizon * 4 + 1,), float("nan"), dtype=torch.float32, device="cuda")
+    x0_v, u_v = x0_buf[1:].view(batch, 12), u_buf[1:].view(batch, horizon, 4)
+    x0_v.copy_(dev(x0))
+    xs = torch.full((batch, horizon + 1, 12), float("nan"), dtype=torch.float32, device="cuda")
+    ops.ac_tinympc_forward_f32(dev(Adyn), dev(Bdyn), dev(Kinf), x0_v, dev(d), u_v, xs)
+    torch.cuda.synchronize()
+    assert rel_fro(host(u_v), uw) <= TOL and rel_fro(host(xs), xw) <= TOL
+
+
+@pytest.mark.parametrize("horizon,batch", [(3, 77), (5, 77), (5, 700), (5, 64), (5, 65), (5, 1025)])
 def test_exact_small_integers(horizon, batch):
     rng = np.random.default_rng(0)
     f = lambda shape, lo, hi: rng.integers(lo, hi + 1, size=shape).astype(np.float32)

@@ -127,7 +127,9 @@ __global__ void __launch_bounds__(256) tinympc_forward_mfma_kernel(const TinyMpc
   }
 
   // inputs of a block: d as one contiguous run, 16 bytes per lane and instruction (HC > 0), and per column block the
-  // lane's 16 bytes of x0 (lanes past the end re-read the last problem and store nothing)
+  // lane's 16 bytes of x0 (lanes past the end re-read the last problem and store nothing).  Every byte is read once
+  // and every result written once, so loads and stores carry the non-temporal hint (262144 problems: 27.0 -> 26.3 us
+  // with the trajectory, 18.7 -> 16.0 us without)
   v4f din[HC > 0 ? HC : 1], xin[4];
   auto request = [&](int64_t k) {
     const int left = p.batch - k * 64 < 64 ? (int)(p.batch - k * 64) : 64;
@@ -136,13 +138,13 @@ __global__ void __launch_bounds__(256) tinympc_forward_mfma_kernel(const TinyMpc
 #pragma unroll
       for (int j = 0; j < HC; j++) {
         const int q = j * 64 + lane;
-        din[j] = q < left * HC ? src[q] : (v4f){0.f, 0.f, 0.f, 0.f};
+        din[j] = q < left * HC ? __builtin_nontemporal_load(src + q) : (v4f){0.f, 0.f, 0.f, 0.f};
       }
     }
 #pragma unroll
     for (int b = 0; b < 4; b++) {
       const int64_t q = k * 64 + 16 * b + n;
-      xin[b] = g < 3 ? *(const v4f*)(p.x0 + (q < p.batch ? q : p.batch - 1) * NX + 4 * g) : (v4f){0.f, 0.f, 0.f, 0.f};
+      xin[b] = g < 3 ? __builtin_nontemporal_load((const v4f*)(p.x0 + (q < p.batch ? q : p.batch - 1) * NX + 4 * g)) : (v4f){0.f, 0.f, 0.f, 0.f};
     }
   };
   request(blk);
@@ -213,7 +215,7 @@ __global__ void __launch_bounds__(256) tinympc_forward_mfma_kernel(const TinyMpc
 #pragma unroll
       for (int k = 0; k < HC; k++) {
         const int q = k * 64 + lane;
-        if (q < pieces) dst[q] = *(const v4f*)(dwin + 16 * q);
+        if (q < pieces) __builtin_nontemporal_store(*(const v4f*)(dwin + 16 * q), dst + q);
       }
     }
     if constexpr (WITH_X) {
@@ -231,7 +233,7 @@ __global__ void __launch_bounds__(256) tinympc_forward_mfma_kernel(const TinyMpc
 #pragma unroll
         for (int k = 0; k < (16 * PPB + 63) / 64; k++) {
           const int q = k * 64 + lane;  // piece q of the block: problem q / PPB, piece q % PPB of its rows
-          if (q < pieces) dst[q] = *(const v4f*)(xwin + (q / PPB) * TMPC_XPITCH + (q % PPB) * 16);
+          if (q < pieces) __builtin_nontemporal_store(*(const v4f*)(xwin + (q / PPB) * TMPC_XPITCH + (q % PPB) * 16), dst + q);
         }
       }
     }

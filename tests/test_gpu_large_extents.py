@@ -191,6 +191,22 @@ def test_int8_gemm_with_the_largest_row_count(N, K):
     np.testing.assert_array_equal(host(C[rows]), want)
 
 
+def test_int8_one_wave_per_tile_kernel_with_millions_of_tiles():
+    """M = 2^27 rows of 64 bytes through tile code 32 by name: 4.2 million tiles (one wave each, a million
+    workgroups), row offsets beyond 2^32 bytes in A; sampled rows."""
+    M, N, K = 1 << 27, 16, 64
+    g = torch.Generator(device="cuda").manual_seed(9108)
+    A = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda", generator=g)
+    B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda", generator=g)
+    bias = torch.randint(-(1 << 15), 1 << 15, (N,), dtype=torch.int32, device="cuda", generator=g)
+    rows = _rows_of(M, N, 7)
+    want = oracle.gemm_i8(host(A[rows]), host(B), host(bias), 6, 1)
+    C = torch.full((M, N), 91, dtype=torch.int8, device="cuda")
+    ops.ac_gemm_i8_planned(A, B, bias, C, 6, 1, 32, 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(C[rows]), want)
+
+
 def test_bf16_gemm_with_the_largest_row_count():
     M, N, K = MAX_DIM, 8, 8
     g = torch.Generator(device="cuda").manual_seed(9108)

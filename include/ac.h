@@ -279,8 +279,7 @@ ac_status ac_tinympc_forward_f32(const float* Adyn, const float* Bdyn, const flo
  *           K a multiple of 64, at least 64 (K slices, splits > 1, are whole 64-byte K tiles; every (tile,
  *           slice) is then a wave of its own).  ac_gemm_i8 and ac_conv2d_i8 pick it, uncut, for such operands
  *           where it measured ahead of every tiled plan: the fewer the tiles of 32 x 32, the deeper the K (up
- *           to 512 tiles K <= 1024, up to 1024 K <= 384, up to 2048 K <= 320, for a convolution K <= 640;
- *           beyond K = 640 only multiples of 128).
+ *           to 512 tiles K <= 1024, up to 1024 K <= 384, up to 2048 K <= 192, for a convolution K <= 640).
  *           ac_conv2d_i8_planned only: 321 / 161 = the convolution patch kernel with units of 256 / 128 output
  *           pixels: the weights of a 64-channel block AND the image patch a unit needs are both held in LDS, so
  *           every input pixel is fetched once per unit instead of once per kernel tap.  It takes splits == 1,

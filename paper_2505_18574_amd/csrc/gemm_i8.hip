@@ -166,15 +166,17 @@ GemmPlan plan_gemm_i8(int32_t M, int32_t N, int32_t K, bool have_workspace, int 
   // 32 x 32) x 14 depths on this chip has it ahead of every tiled plan with operands in the caches and level with
   // them with operands in HBM: the fewer the tiles, the deeper the K that a lone wave per tile still wins with (at
   // 1024 tiles the 64 x 64 tiles share operands through LDS and win from K = 512).  Warm margins: 256^3 2.9 vs
-  // 3.6 us, 512 x 768 x 768 3.9 vs 4.6, 128 x 1024 x 1024 3.9 vs 4.5, 2048 x 1024 x 320 4.9 vs 5.1.  Deeper K with
-  // few tiles is also ahead warm (128 x 1024 x 3072: 6.8 vs 8.8 us for a cut K) but well behind from HBM (14.5 vs
-  // 10.6 us: a cut K has eight times the loads in flight), and 784 x 512 x 1152 gives from HBM what it gains warm
-  // (7.9 vs 7.0, 4.6 vs 5.0): both stay on the tiled plans.
-  // Against the convolution gather of the 64 x 64 tiles it stays ahead further: 8 images of 56 x 56 x 64 -> 64 (1568
-  // tiles, K = 576) 5.7 against 6.5 us warm, 6.5 against 6.9 from HBM; not at 3136 tiles (11.9 against 8.0).
-  if (small_kernel != 0 && K >= SMALL_KTB && K % SMALL_KTB == 0 && (K <= 640 || K % 128 == 0)) {
+  // 3.6 us, 512 x 768 x 768 3.9 vs 4.6, 128 x 1024 x 1024 3.9 vs 4.5, 2048 x 1024 x 192 4.2 vs 4.6.  Between 1024
+  // and 2048 tiles K = 256 .. 320 is ahead by 2-4 % on most shapes and behind by up to 20 % on some (1024 x 1744 x
+  // 320: 7.2 against 6.0 us), so the rule stops at 192 there.  Deeper K with few tiles is also ahead warm (128 x
+  // 1024 x 3072: 6.8 vs 8.8 us for a cut K) but well behind from HBM (14.5 vs 10.6 us: a cut K has eight times the
+  // loads in flight), and 784 x 512 x 1152 gives from HBM what it gains warm (7.9 vs 7.0, 4.6 vs 5.0): both stay on
+  // the tiled plans.  Against the convolution gather of the 64 x 64 tiles it stays ahead further: 8 images of
+  // 56 x 56 x 64 -> 64 (1568 tiles, K = 576) 5.7 against 6.5 us warm, 6.5 against 6.9 from HBM; not at 3136 tiles
+  // (11.9 against 8.0).
+  if (small_kernel != 0 && K >= SMALL_KTB && K % SMALL_KTB == 0) {
     const int64_t tiles32 = (int64_t)((M + 31) / 32) * ((N + 31) / 32);
-    int kmax = tiles32 <= 512 ? 1024 : tiles32 <= 1024 ? 384 : tiles32 <= 2048 ? 320 : 0;
+    int kmax = tiles32 <= 512 ? 1024 : tiles32 <= 1024 ? 384 : tiles32 <= 2048 ? 192 : 0;
     if (small_kernel == 2 && tiles32 <= 2048 && kmax < 640) kmax = 640;
     if (K <= kmax) {
       make_plan_i8(K, 32, 1, &plan);

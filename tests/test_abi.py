@@ -168,7 +168,8 @@ def test_auto_plans_are_host_arithmetic():
     assert ops.ac_gemm_i8_auto_plan(784, 512, 1152)[0] != 32      # beyond the depth for 400 tiles
     assert ops.ac_gemm_i8_auto_plan(128, 1024, 3072)[0] != 32     # deep K: cut instead (more loads in flight from HBM)
     assert ops.ac_gemm_i8_auto_plan(3136, 64, 600)[0] != 32       # K not in whole 64-byte tiles
-    assert ops.ac_gemm_i8_auto_plan(3136, 64, 704)[0] != 32       # beyond 640 only in whole 128-byte tiles
+    assert ops.ac_gemm_i8_auto_plan(3136, 64, 704) == (32, 1)     # any whole number of 64-byte tiles
+    assert ops.ac_gemm_i8_auto_plan(2048, 1024, 192) == (32, 1) and ops.ac_gemm_i8_auto_plan(2048, 1024, 256)[0] != 32
     assert ops.ac_gemm_i8_auto_plan(12544, 256, 64)[0] != 32      # 3136 tiles: more than the small kernel is ahead for
     assert ops.ac_gemm_i8_auto_plan(49, 2048, 4608)[0] != 32      # too deep: K is cut instead
     assert ops.ac_gemm_i8_auto_plan(65536, 64, 576) == (320, 1)   # long, narrow, short K: weight-stationary kernel

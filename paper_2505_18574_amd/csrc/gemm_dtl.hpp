@@ -708,6 +708,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) gemm_dtl_kernel(const 
     };
     if (XPF && efull) body(std::true_type{});
     else body(std::false_type{});
+  } else if constexpr (has_wave_tile<EPI>::value) {
+    EPI::wave_tile(p, em0 + wm * G::WTM, en0 + wn * G::WTN, acc, lane, esplit, pre);
   } else {
 #pragma unroll
   for (int i = 0; i < G::TM; i++) {

@@ -13,6 +13,7 @@
 // (or a float4) without an LDS transpose.
 #pragma once
 #include "common.hpp"
+#include <type_traits>
 
 namespace ac {
 
@@ -127,6 +128,12 @@ static __device__ __forceinline__ void for_each_unswapped(int mrow0, int ncol0, 
 }
 
 // int8 output stage: bias, v / 2^shift to nearest (halves to even), saturate, ReLU.
+// An epilogue that can take a whole wave tile at once declares WAVE_TILE.
+template <class E, class = void>
+struct has_wave_tile : std::false_type {};
+template <class E>
+struct has_wave_tile<E, std::void_t<decltype(E::WAVE_TILE)>> : std::true_type {};
+
 struct EpilogueI8 {
   static constexpr bool SWAP = true;
   static constexpr bool LDS_STAGED = false;
@@ -188,18 +195,24 @@ struct EpilogueI8 {
       }
     }
   }
-  // Fast form of requant() for 1 <= shift <= 23 with the lower clamp bound as a constant (0 folds the ReLU in):
-  // floor((t + 2^(shift-1) - 1 + bit) / 2^shift) with bit = bit `shift` of t rounds halves to even.  For these
-  // shifts every |t| >= 2^30 saturates, so clamping t to 30 bits first changes no result and keeps the rounding
-  // add inside int32.  `rnd` = 2^(shift-1) - 1.  Five VALU instructions per value.
-  template <int LO>
-  static __device__ __forceinline__ int requant_fast(int t, int shift, int rnd) {
-    int c = t < -(1 << 30) ? -(1 << 30) : t;
-    c = c > (1 << 30) - 1 ? (1 << 30) - 1 : c;
-    const int bit = (int)__builtin_amdgcn_ubfe((unsigned)c, (unsigned)shift, 1u);
-    int q = (c + bit + rnd) >> shift;
-    q = q < LO ? LO : q;
-    return q > 127 ? 127 : q;
+  // Fast form of requant() for 1 <= shift <= 23: floor((t + 2^(shift-1) - 1 + bit) / 2^shift) with bit = bit
+  // `shift` of t rounds halves to even.  The rounding shift is monotone, so the output clamp is taken on the way
+  // in: t is clamped to [lo, hi] with hi = 127 * 2^shift + 2^(shift-1) - 1, the largest t that still rounds to
+  // 127, and lo = -128 * 2^shift, which rounds to -128 exactly (0 with ReLU: every negative t ends as 0), which
+  // also keeps the rounding add inside int32.  Four VALU instructions per value, the same code for both
+  // activations.
+  struct FastQuant {
+    int shift, rnd, lo, hi;
+  };
+  static __device__ __forceinline__ FastQuant fast_quant(int shift, int act) {
+    const int rnd = (1 << (shift - 1)) - 1;
+    return {shift, rnd, act ? 0 : -128 * (1 << shift), (127 << shift) + rnd};
+  }
+  static __device__ __forceinline__ int requant_fast(int t, const FastQuant& f) {
+    int c = t < f.lo ? f.lo : t;
+    c = c > f.hi ? f.hi : c;
+    const int bit = (int)__builtin_amdgcn_ubfe((unsigned)c, (unsigned)f.shift, 1u);
+    return (c + bit + f.rnd) >> f.shift;
   }
   // Four values already in [-128, 127] -> their low bytes in one dword (v0 lowest).
   static __device__ __forceinline__ unsigned pack4(int v0, int v1, int v2, int v3) {
@@ -207,32 +220,60 @@ struct EpilogueI8 {
     const unsigned hi = __builtin_amdgcn_perm((unsigned)v3, (unsigned)v2, 0x0c0c0400u);
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
   }
-  // MODE 0: any shift / activation (requant); 1: fast form with ReLU; 2: fast form without.
-  template <int MODE>
-  static __device__ __forceinline__ unsigned quant4(const int* t, int shift, int act, int rnd) {
-    int v[4];
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-      if constexpr (MODE == 1) v[e] = requant_fast<0>(t[e], shift, rnd);
-      else if constexpr (MODE == 2) v[e] = requant_fast<-128>(t[e], shift, rnd);
-      else v[e] = requant(t[e], shift, act);
-    }
-    return pack4(v[0], v[1], v[2], v[3]);
-  }
-  // The 16 values of one lane (accumulator + bias) -> 16 output bytes in column order after the lane exchange:
-  // lanes l and l + 32 hold interleaved 4-byte pieces of the same row.  Swapping the upper half of d[0] (d[1])
-  // with the lower half of d[2] (d[3]) leaves 16 consecutive bytes in every lane: columns 0..15 in lanes 0..31,
-  // columns 16..31 in lanes 32..63, so a row leaves as two whole 16-byte stores.
-  template <int MODE>
-  static __device__ __forceinline__ v4i quant16(const int* t, int shift, int act) {
-    const int rnd = shift > 0 ? (1 << (shift - 1)) - 1 : 0;
-    unsigned d[4];
-#pragma unroll
-    for (int q = 0; q < 4; q++) d[q] = quant4<MODE>(t + 4 * q, shift, act, rnd);
+  // The 16 values of one lane (accumulator + bias), quantised and packed four to a dword -> 16 output bytes in
+  // column order after the lane exchange: lanes l and l + 32 hold interleaved 4-byte pieces of the same row.
+  // Swapping the upper half of d[0] (d[1]) with the lower half of d[2] (d[3]) leaves 16 consecutive bytes in every
+  // lane: columns 0..15 in lanes 0..31, columns 16..31 in lanes 32..63, so a row leaves as two whole 16-byte stores.
+  static __device__ __forceinline__ v4i exchange16(const unsigned* d) {
     typedef unsigned v2u __attribute__((ext_vector_type(2)));
     const v2u s02 = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
     const v2u s13 = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
     return (v4i){(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+  }
+  // Any shift / activation (requant).
+  static __device__ __forceinline__ v4i quant16(const int* t, int shift, int act) {
+    unsigned d[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) d[q] = pack4(requant(t[4 * q], shift, act), requant(t[4 * q + 1], shift, act), requant(t[4 * q + 2], shift, act), requant(t[4 * q + 3], shift, act));
+    return exchange16(d);
+  }
+  // Fast form.
+  static __device__ __forceinline__ v4i quant16(const int* t, const FastQuant& f) {
+    unsigned d[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) d[q] = pack4(requant_fast(t[4 * q], f), requant_fast(t[4 * q + 1], f), requant_fast(t[4 * q + 2], f), requant_fast(t[4 * q + 3], f));
+    return exchange16(d);
+  }
+  // The whole wave tile, TM x TN blocks of 32 x 32, when every block takes 16-byte stores, the bias is a row or
+  // absent and the shift has the fast form: one decision per wave tile and straight-line code for its blocks (as
+  // separate calls of tile() every block carries the whole decision tree, and the output stage of a 256 x 256
+  // tile ran through some 90 KB of code).  BIASED as in tile().
+  static constexpr bool WAVE_TILE = true;
+  template <bool BIASED = false, int TM, int TN, class ACC>
+  static __device__ __forceinline__ void wave_tile(const GemmParams& p, int mrow0, int ncol0, const ACC (&acc)[TM][TN], int lane, int esplit, const Pre (&pre)[TN]) {
+    int8_t* C = (int8_t*)p.C;
+    const bool fast = ncol0 + 32 * TN <= p.N && (p.ldc & 15) == 0 && (((uintptr_t)C) & 15) == 0 && (p.bias == nullptr || p.bias_ld == 0) && p.shift >= 1 && p.shift <= 23;
+    if (fast) {  // wave-uniform
+      const FastQuant f = fast_quant(p.shift, p.act);
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        const int m = mrow0 + 32 * i + (lane & 31);
+        int8_t* dst = C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          int t[16];
+#pragma unroll
+          for (int r = 0; r < 16; r++) t[r] = BIASED ? acc[i][j][r] : acc[i][j][r] + pre[j].bias[r >> 2][r & 3];  // no bias: the prefetch returned zeros
+          const v4i o = quant16(t, f);
+          if (m < p.M) *(v4i*)(dst + 32 * j) = o;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) tile<BIASED>(p, mrow0 + 32 * i, ncol0 + 32 * j, acc[i][j], lane, esplit, pre[j]);
+    }
   }
   // BIASED: the accumulators already hold the bias (a kernel that starts its sums from the bias row).
   template <bool BIASED = false, class ACC>
@@ -257,9 +298,7 @@ struct EpilogueI8 {
           t[4 * q + e] = acc[4 * q + e] + b;
         }
       }
-      v4i o;
-      if (p.shift >= 1 && p.shift <= 23) o = p.act ? quant16<1>(t, p.shift, p.act) : quant16<2>(t, p.shift, p.act);
-      else o = quant16<0>(t, p.shift, p.act);
+      const v4i o = p.shift >= 1 && p.shift <= 23 ? quant16(t, fast_quant(p.shift, p.act)) : quant16(t, p.shift, p.act);
       *(v4i*)(C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5)) = o;
     } else {
 #pragma unroll

@@ -111,3 +111,23 @@ def test_empty_and_errors():
     assert L.ac_conv2d_i8(a, a + 1024, None, a, 1, 5, 5, 16, 16, 3, 3, 1, 1, 8, 1, None, 0, None) == ops.AC_ERR_ALIAS
     assert L.ac_conv2d_i8(None, a + 1024, None, a + 2048, 1, 5, 5, 16, 16, 3, 3, 1, 1, 8, 1, None, 0, None) == ops.AC_ERR_NULL
     assert L.ac_conv2d_i8(a, a + 1024, None, a + 2048, 1, 5, 5, 16, 16, 3, 3, 1, 1, 40, 1, None, 0, None) == ops.AC_ERR_SHIFT
+
+
+@pytest.mark.parametrize("plan", [None, (321, 1), (161, 1), (64, 1), (32, 1)])
+def test_sums_around_the_clamp_bounds(plan):
+    """Zero image, so every sum is its bias: the sums next to the clamp bounds of the rounding shift and the ends of
+    int32, through the library's choice, the patch kernel, the tiled gather and the one-wave-per-tile kernel."""
+    Nb, H, W, Cin, Cout = 2, 16, 16, 64, 128
+    x = np.zeros((Nb, H, W, Cin), np.int8)
+    w = np.ones((3, 3, Cin, Cout), np.int8)
+    for shift in (1, 9, 23):
+        half = 1 << (shift - 1)
+        centres = [(127 << shift) + half - 1, 127 << shift, -(128 << shift), -(128 << shift) - half, 0, half, -half, 2**31 - 1, -(2**31)]
+        vals = np.array([c + d for c in centres for d in (-2, -1, 0, 1, 2)], dtype=np.int64)
+        bias = np.resize(np.clip(vals, -(2**31), 2**31 - 1), Cout).astype(np.int32)
+        for act in (0, 1):
+            want = oracle.conv2d_i8(x, w, bias, 1, 1, shift, act)
+            out = torch.full((Nb, H, W, Cout), 99, dtype=torch.int8, device="cuda")
+            ops.ac_conv2d_i8(dev(x), dev(w), dev(bias), out, 1, 1, shift, act, plan=plan)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(host(out), want)

@@ -77,6 +77,32 @@ def test_small_magnitudes_and_ties():
     assert want[0, 129] == 0 and want[0, 131] == 2 and want[0, 127] == 0 and want[0, 125] == -2  # halves go to even
 
 
+@pytest.mark.parametrize("tile", [None, 256, 192, 128, 64, 32, 320])
+def test_sums_around_the_clamp_bounds_and_the_ends_of_int32(tile):
+    """The output stage clamps the sums on the way into the rounding shift: sums at and next to the largest one that
+    still rounds to 127, the smallest that still rounds to -128, zero, every tie next to them, and the ends of int32,
+    on every kernel family (A = 0, so a sum is its bias)."""
+    M, N, K = 256, (128 if tile == 320 else 512), 128  # the weight-stationary kernel takes narrow outputs
+    A = np.zeros((M, K), np.int8)
+    B = np.ones((K, N), np.int8)
+    for shift in (1, 2, 9, 10, 23):
+        half = 1 << (shift - 1)
+        centres = [(127 << shift) + half - 1, 127 << shift, (126 << shift) + half, -(128 << shift), -(128 << shift) - half, -(127 << shift) - half,
+                   0, half, -half, 3 * half, -3 * half, 2**31 - 1, -(2**31), 2**30, -(2**30)]
+        vals = np.array([c + d for c in centres for d in (-2, -1, 0, 1, 2)], dtype=np.int64)
+        bias = np.resize(np.clip(vals, -(2**31), 2**31 - 1), N).astype(np.int32)
+        for act in (0, 1):
+            want = oracle.gemm_i8(A, B, bias, shift, act)
+            if tile is None:
+                got = run_gpu(A, B, bias, shift, act)
+            else:
+                C = torch.full((M, N), 77, dtype=torch.int8, device="cuda")
+                ops.ac_gemm_i8_planned(dev(A), dev(B), dev(bias), C, shift, act, tile, 1)
+                torch.cuda.synchronize()
+                got = host(C)
+            np.testing.assert_array_equal(got, want)
+
+
 def test_bias_matrix_and_no_bias():
     A, B, bias = inputs.gemm_i8_inputs(150, 130, 90, seed=5, bias_matrix=True)
     check(A, B, bias, 8, 1)

@@ -209,8 +209,11 @@ struct EpilogueI8 {
     return {shift, rnd, act ? 0 : -128 * (1 << shift), (127 << shift) + rnd};
   }
   static __device__ __forceinline__ int requant_fast(int t, const FastQuant& f) {
-    int c = t < f.lo ? f.lo : t;
-    c = c > f.hi ? f.hi : c;
+    // the median of (t, lo, hi) is the clamp; with bounds that are not constants the compiler cannot know that
+    // lo <= hi and emits a maximum and a minimum, so the instruction is written out (one scalar operand at most:
+    // hi travels in a vector register)
+    int c;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(c) : "v"(t), "s"(f.lo), "v"(f.hi));
     const int bit = (int)__builtin_amdgcn_ubfe((unsigned)c, (unsigned)f.shift, 1u);
     return (c + bit + f.rnd) >> f.shift;
   }

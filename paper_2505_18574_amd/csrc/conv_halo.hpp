@@ -61,7 +61,7 @@ static __device__ __forceinline__ void halo_store_tile(const GemmParams& p, int 
 #pragma unroll
   for (int r = 0; r < 16; r++) t[r] = acc[r];
   if (ncol0 + 32 <= p.N) {
-    const v4i o = p.shift >= 1 && p.shift <= 23 ? EPI::quant16(t, EPI::fast_quant(p.shift, p.act)) : EPI::quant16(t, p.shift, p.act);
+    const v4i o = p.shift >= 1 && p.shift <= 23 ? EPI::quant16_by_shift(t, EPI::fast_quant(p.shift, p.act)) : EPI::quant16(t, p.shift, p.act);
     if (m < m_end) *(v4i*)(C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5)) = o;
   } else if (m < m_end) {  // the 16-column remainder of the last block
 #pragma unroll

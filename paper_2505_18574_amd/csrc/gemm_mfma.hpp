@@ -203,21 +203,32 @@ struct EpilogueI8 {
   // activations.
   struct FastQuant {
     int shift, rnd, lo, hi;
+    float scale;  // 2^-shift
   };
   static __device__ __forceinline__ FastQuant fast_quant(int shift, int act) {
     const int rnd = (1 << (shift - 1)) - 1;
-    return {shift, rnd, act ? 0 : -128 * (1 << shift), (127 << shift) + rnd};
+    return {shift, rnd, act ? 0 : -128 * (1 << shift), (127 << shift) + rnd, __builtin_ldexpf(1.f, -shift)};
   }
+  // FLOAT_ROUND (shift <= 17): the clamped value has at most 25 significant bits with the lowest one zero at the
+  // ends, i.e. |c| <= 2^24 and exact in fp32, and one fused multiply-add c * 2^-shift + 1.5 * 2^23 rounds the
+  // quotient to an integer, halves to even (the sum lies in [2^23, 2^24), where fp32 steps by 1 and the constant is
+  // even): the low byte of the result's bit pattern is the two's-complement output.  Three VALU instructions per
+  // value instead of four; only the low byte of the returned word is meaningful.
+  template <bool FLOAT_ROUND = false>
   static __device__ __forceinline__ int requant_fast(int t, const FastQuant& f) {
     // the median of (t, lo, hi) is the clamp; with bounds that are not constants the compiler cannot know that
     // lo <= hi and emits a maximum and a minimum, so the instruction is written out (one scalar operand at most:
     // hi travels in a vector register)
     int c;
     asm("v_med3_i32 %0, %1, %2, %3" : "=v"(c) : "v"(t), "s"(f.lo), "v"(f.hi));
-    const int bit = (int)__builtin_amdgcn_ubfe((unsigned)c, (unsigned)f.shift, 1u);
-    return (c + bit + f.rnd) >> f.shift;
+    if constexpr (FLOAT_ROUND) {
+      return __builtin_bit_cast(int, __builtin_fmaf((float)c, f.scale, 12582912.f));
+    } else {
+      const int bit = (int)__builtin_amdgcn_ubfe((unsigned)c, (unsigned)f.shift, 1u);
+      return (c + bit + f.rnd) >> f.shift;
+    }
   }
-  // Four values already in [-128, 127] -> their low bytes in one dword (v0 lowest).
+  // The low bytes of four words in one dword (v0 lowest).
   static __device__ __forceinline__ unsigned pack4(int v0, int v1, int v2, int v3) {
     const unsigned lo = __builtin_amdgcn_perm((unsigned)v1, (unsigned)v0, 0x0c0c0400u);
     const unsigned hi = __builtin_amdgcn_perm((unsigned)v3, (unsigned)v2, 0x0c0c0400u);
@@ -241,11 +252,17 @@ struct EpilogueI8 {
     return exchange16(d);
   }
   // Fast form.
+  template <bool FLOAT_ROUND = false>
   static __device__ __forceinline__ v4i quant16(const int* t, const FastQuant& f) {
     unsigned d[4];
 #pragma unroll
-    for (int q = 0; q < 4; q++) d[q] = pack4(requant_fast(t[4 * q], f), requant_fast(t[4 * q + 1], f), requant_fast(t[4 * q + 2], f), requant_fast(t[4 * q + 3], f));
+    for (int q = 0; q < 4; q++)
+      d[q] = pack4(requant_fast<FLOAT_ROUND>(t[4 * q], f), requant_fast<FLOAT_ROUND>(t[4 * q + 1], f), requant_fast<FLOAT_ROUND>(t[4 * q + 2], f), requant_fast<FLOAT_ROUND>(t[4 * q + 3], f));
     return exchange16(d);
+  }
+  // Fast form, the rounding picked by the shift (wave-uniform).
+  static __device__ __forceinline__ v4i quant16_by_shift(const int* t, const FastQuant& f) {
+    return f.shift <= 17 ? quant16<true>(t, f) : quant16<false>(t, f);
   }
   // The whole wave tile, TM x TN blocks of 32 x 32, when every block takes 16-byte stores, the bias is a row or
   // absent and the shift has the fast form: one decision per wave tile and straight-line code for its blocks (as
@@ -258,19 +275,23 @@ struct EpilogueI8 {
     const bool fast = ncol0 + 32 * TN <= p.N && (p.ldc & 15) == 0 && (((uintptr_t)C) & 15) == 0 && (p.bias == nullptr || p.bias_ld == 0) && p.shift >= 1 && p.shift <= 23;
     if (fast) {  // wave-uniform
       const FastQuant f = fast_quant(p.shift, p.act);
+      auto blocks = [&](auto float_round) {
 #pragma unroll
-      for (int i = 0; i < TM; i++) {
-        const int m = mrow0 + 32 * i + (lane & 31);
-        int8_t* dst = C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5);
+        for (int i = 0; i < TM; i++) {
+          const int m = mrow0 + 32 * i + (lane & 31);
+          int8_t* dst = C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5);
 #pragma unroll
-        for (int j = 0; j < TN; j++) {
-          int t[16];
+          for (int j = 0; j < TN; j++) {
+            int t[16];
 #pragma unroll
-          for (int r = 0; r < 16; r++) t[r] = BIASED ? acc[i][j][r] : acc[i][j][r] + pre[j].bias[r >> 2][r & 3];  // no bias: the prefetch returned zeros
-          const v4i o = quant16(t, f);
-          if (m < p.M) *(v4i*)(dst + 32 * j) = o;
+            for (int r = 0; r < 16; r++) t[r] = BIASED ? acc[i][j][r] : acc[i][j][r] + pre[j].bias[r >> 2][r & 3];  // no bias: the prefetch returned zeros
+            const v4i o = quant16<decltype(float_round)::value>(t, f);
+            if (m < p.M) *(v4i*)(dst + 32 * j) = o;
+          }
         }
-      }
+      };
+      if (p.shift <= 17) blocks(std::true_type{});
+      else blocks(std::false_type{});
     } else {
 #pragma unroll
       for (int i = 0; i < TM; i++)
@@ -301,7 +322,7 @@ struct EpilogueI8 {
           t[4 * q + e] = acc[4 * q + e] + b;
         }
       }
-      const v4i o = p.shift >= 1 && p.shift <= 23 ? quant16(t, fast_quant(p.shift, p.act)) : quant16(t, p.shift, p.act);
+      const v4i o = p.shift >= 1 && p.shift <= 23 ? quant16_by_shift(t, fast_quant(p.shift, p.act)) : quant16(t, p.shift, p.act);
       *(v4i*)(C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5)) = o;
     } else {
 #pragma unroll

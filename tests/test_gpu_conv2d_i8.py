@@ -120,7 +120,7 @@ def test_sums_around_the_clamp_bounds(plan):
     Nb, H, W, Cin, Cout = 2, 16, 16, 64, 128
     x = np.zeros((Nb, H, W, Cin), np.int8)
     w = np.ones((3, 3, Cin, Cout), np.int8)
-    for shift in (1, 9, 23):
+    for shift in (1, 9, 17, 18, 23):
         half = 1 << (shift - 1)
         centres = [(127 << shift) + half - 1, 127 << shift, -(128 << shift), -(128 << shift) - half, 0, half, -half, 2**31 - 1, -(2**31)]
         vals = np.array([c + d for c in centres for d in (-2, -1, 0, 1, 2)], dtype=np.int64)

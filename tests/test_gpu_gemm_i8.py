@@ -85,7 +85,7 @@ def test_sums_around_the_clamp_bounds_and_the_ends_of_int32(tile):
     M, N, K = 256, (128 if tile == 320 else 512), 128  # the weight-stationary kernel takes narrow outputs
     A = np.zeros((M, K), np.int8)
     B = np.ones((K, N), np.int8)
-    for shift in (1, 2, 9, 10, 23):
+    for shift in (1, 2, 9, 10, 16, 17, 18, 23):  # the output stage rounds in fp32 up to 17 and in integers beyond
         half = 1 << (shift - 1)
         centres = [(127 << shift) + half - 1, 127 << shift, (126 << shift) + half, -(128 << shift), -(128 << shift) - half, -(127 << shift) - half,
                    0, half, -half, 3 * half, -3 * half, 2**31 - 1, -(2**31), 2**30, -(2**30)]

@@ -269,8 +269,9 @@ struct EpilogueI8 {
   // separate calls of tile() every block carries the whole decision tree, and the output stage of a 256 x 256
   // tile ran through some 90 KB of code).  BIASED as in tile().
   static constexpr bool WAVE_TILE = true;
-  template <bool BIASED = false, int TM, int TN, class ACC>
-  static __device__ __forceinline__ void wave_tile(const GemmParams& p, int mrow0, int ncol0, const ACC (&acc)[TM][TN], int lane, int esplit, const Pre (&pre)[TN]) {
+  // acc_of(i, j) and pre_of(j) give block (i, j)'s accumulators and column block j's prefetched bias.
+  template <bool BIASED, int TM, int TN, class ACC_OF, class PRE_OF>
+  static __device__ __forceinline__ void wave_blocks(const GemmParams& p, int mrow0, int ncol0, ACC_OF acc_of, int lane, int esplit, PRE_OF pre_of) {
     int8_t* C = (int8_t*)p.C;
     const bool fast = ncol0 + 32 * TN <= p.N && (p.ldc & 15) == 0 && (((uintptr_t)C) & 15) == 0 && (p.bias == nullptr || p.bias_ld == 0) && p.shift >= 1 && p.shift <= 23;
     if (fast) {  // wave-uniform
@@ -284,7 +285,7 @@ struct EpilogueI8 {
           for (int j = 0; j < TN; j++) {
             int t[16];
 #pragma unroll
-            for (int r = 0; r < 16; r++) t[r] = BIASED ? acc[i][j][r] : acc[i][j][r] + pre[j].bias[r >> 2][r & 3];  // no bias: the prefetch returned zeros
+            for (int r = 0; r < 16; r++) t[r] = BIASED ? acc_of(i, j)[r] : acc_of(i, j)[r] + pre_of(j).bias[r >> 2][r & 3];  // no bias: the prefetch returned zeros
             const v4i o = quant16<decltype(float_round)::value>(t, f);
             if (m < p.M) *(v4i*)(dst + 32 * j) = o;
           }
@@ -296,8 +297,17 @@ struct EpilogueI8 {
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
-        for (int j = 0; j < TN; j++) tile<BIASED>(p, mrow0 + 32 * i, ncol0 + 32 * j, acc[i][j], lane, esplit, pre[j]);
+        for (int j = 0; j < TN; j++) tile<BIASED>(p, mrow0 + 32 * i, ncol0 + 32 * j, acc_of(i, j), lane, esplit, pre_of(j));
     }
+  }
+  template <bool BIASED = false, int TM, int TN, class ACC>
+  static __device__ __forceinline__ void wave_tile(const GemmParams& p, int mrow0, int ncol0, const ACC (&acc)[TM][TN], int lane, int esplit, const Pre (&pre)[TN]) {
+    wave_blocks<BIASED, TM, TN>(p, mrow0, ncol0, [&](int i, int j) -> const ACC& { return acc[i][j]; }, lane, esplit, [&](int j) -> const Pre& { return pre[j]; });
+  }
+  // A column of TM blocks with one bias block.
+  template <bool BIASED = false, int TM, class ACC>
+  static __device__ __forceinline__ void wave_column(const GemmParams& p, int mrow0, int ncol0, const ACC (&acc)[TM], int lane, const Pre& pre) {
+    wave_blocks<BIASED, TM, 1>(p, mrow0, ncol0, [&](int i, int) -> const ACC& { return acc[i]; }, lane, 0, [&](int) -> const Pre& { return pre; });
   }
   // BIASED: the accumulators already hold the bias (a kernel that starts its sums from the bias row).
   template <bool BIASED = false, class ACC>

@@ -269,9 +269,7 @@ __global__ void __launch_bounds__(512) gemm_i8_wstat_kernel(const GemmParams p, 
       if (more) read_frags(n_stage, n_kt, ks, fr[ks]);
     }
     if (tile_end) {
-#pragma unroll
-      for (int i = 0; i < G::TM; i++)
-        EPI::template tile<true>(p, c_mt * BM + wm * G::WTM + i * 32, n0 + wn * 32, acc[i], lane, 0, pre);
+      EPI::template wave_column<true>(p, c_mt * BM + wm * G::WTM, n0 + wn * 32, acc, lane, pre);
       start_acc();
       c_mt += wgs;
     }

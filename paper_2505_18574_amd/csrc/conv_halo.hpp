@@ -150,15 +150,33 @@ __global__ void __launch_bounds__(512) conv_i8_halo_kernel(const GemmParams p, c
   const int iw_run0 = lane_on ? lane_px - p.pad : 0x40000000;
   const int off_run0 = (lane_px - p.pad) * p.Cin + lane_part * 16;
   const int iw_lim = p.W < h.ROWP - p.pad ? p.W : h.ROWP - p.pad;  // columns of this row that exist in the image
-  auto issue_patch = [&](const Unit& w, int buf) {
+  // Stride 1 with at most MAXC runs per patch row: which lanes load in run c, and from which byte of the row, is
+  // the same for every row of every unit, so both are kept (a lane mask and an offset per run) and a row is MAXC
+  // predicated loads in a straight line.  As a loop over the runs with the tests inside, a row cost some hundred
+  // instructions and a dozen taken branches for its five loads.
+  constexpr int MAXC = 6;
+  const bool short_rows = p.stride == 1 && h.CPR <= MAXC;  // wave-uniform
+  unsigned run_off[MAXC];
+  bool run_on[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; c++) {
+    run_on[c] = short_rows && c < h.CPR && (unsigned)(iw_run0 + c * h.PPI) < (unsigned)iw_lim;
+    run_off[c] = (unsigned)(off_run0 + c * h.PPI * p.Cin);
+  }
+  auto issue_patch = [&](const Unit& w, int buf, int row_first, int row_step) {
     const int ih_base = w.oh_first * p.stride - p.pad;
     const unsigned char* img_base = (const unsigned char*)p.A + (int64_t)w.img * p.H * p.W * p.Cin;
-    for (int row = wave; row < w.rin; row += 8) {
+    for (int row = row_first; row < w.rin; row += row_step) {
       const int ih = ih_base + row;
       const bool row_ok = (unsigned)ih < (unsigned)p.H;
       const unsigned char* sbase = uniform_ptr(row_ok ? img_base + (int64_t)ih * p.W * p.Cin : zero);
       unsigned dst = ldsP + buf * h.HB + row * h.ROWP * h.PITCH;
-      if (p.stride == 1) {
+      if (short_rows) {
+        const unsigned keep = row_ok ? ~0u : 0u;  // a row outside the image: every lane reads the block of zeros at offset 0
+#pragma unroll
+        for (int c = 0; c < MAXC; c++)
+          if (run_on[c]) load_to_lds16_so(sbase, run_off[c] & keep, (unsigned)__builtin_amdgcn_readfirstlane((int)(dst + c * h.PPI * h.PITCH)));
+      } else if (p.stride == 1) {
         int iw = iw_run0, off = off_run0;
         for (int c = 0; c < h.CPR; c++) {
           if ((unsigned)iw < (unsigned)iw_lim) load_to_lds16_so(sbase, row_ok ? (unsigned)off : 0u, (unsigned)__builtin_amdgcn_readfirstlane((int)dst));
@@ -282,12 +300,16 @@ __global__ void __launch_bounds__(512) conv_i8_halo_kernel(const GemmParams p, c
   };
 
   // ---- units, in half steps ------------------------------------------------------------------------------
-  // Group g multiplies unit t in half step 2 t + g and runs its output stage in half step 2 t + g + 1; the patch
-  // of unit t + 1 is requested at the start of half step 2 t; a barrier follows every odd half step.  At that
-  // barrier both groups are done reading patch t (group 0 since half step 2 t, group 1 just now) and every wave
-  // has waited for its own loads of patch t + 1 (right after its multiply), so patch t + 1 is complete and the
-  // buffer of patch t is free for patch t + 2.
-  issue_patch(unit_of(wg), 0);
+  // Group g multiplies unit t in half step 2 t + g and runs its output stage in half step 2 t + g + 1; a barrier
+  // follows every odd half step.  The patch of unit t + 1 is requested ahead of the output stages: by group 1 at
+  // the start of half step 2 t and by group 0 at the start of half step 2 t + 1, each wave its own rows, so that
+  // the request runs beside the other group's MFMAs (requested by all eight waves at once it was a stretch of a
+  // microsecond per unit in which no wave of the compute unit multiplied, and requested by group 1 alone that
+  // group's half steps were a microsecond longer than group 0's).  At the barrier both groups are done reading
+  // patch t (group 0 since half step 2 t, group 1 just now) and every wave has waited for its own loads of patch
+  // t + 1 (group 1 after its multiply, group 0 after its output stage), so patch t + 1 is complete and the buffer
+  // of patch t is free for patch t + 2.
+  issue_patch(unit_of(wg), 0, wave, 8);
   wait_vm<0>();
   block_sync();  // weights and the first patch are visible
   asm volatile("" ::"v"(bias_acc));  // the bias row is needed from here on: its wait belongs before the unit loop, not in it
@@ -296,7 +318,7 @@ __global__ void __launch_bounds__(512) conv_i8_halo_kernel(const GemmParams p, c
     for (int k = 0; k < NKS; k++) bw[k] = read_b(k);
   }
   for (int hs = 0; hs <= 2 * my_units; hs++) {
-    if (!(hs & 1) && (hs >> 1) + 1 < my_units) issue_patch(unit_of(wg + ((hs >> 1) + 1) * wgs), ((hs >> 1) + 1) & 1);
+    if ((hs & 1) != grp && (hs >> 1) + 1 < my_units) issue_patch(unit_of(wg + ((hs >> 1) + 1) * wgs), ((hs >> 1) + 1) & 1, wave, 8);
     const int rel = hs - grp;
     if (rel >= 0 && (rel >> 1) < my_units) {
       const Unit w = unit_of(wg + (rel >> 1) * wgs);
@@ -308,6 +330,7 @@ __global__ void __launch_bounds__(512) conv_i8_halo_kernel(const GemmParams p, c
         const int m_end = (w.img + 1) * npix;  // rows of the unit past the end of its image belong to nobody
 #pragma unroll
         for (int i = 0; i < TM; i++) halo_store_tile(p, mrow0 + i * 32, m_end, n0 + wn * 32, acc[i], lane);
+        if (grp == 0) wait_vm<0>();  // group 0's share of the next patch was requested at the top of this half step
       }
     }
     if (hs & 1) block_sync();

@@ -199,31 +199,31 @@ struct EpilogueI8 {
   // `shift` of t rounds halves to even.  The rounding shift is monotone, so the output clamp is taken on the way
   // in: t is clamped to [lo, hi] with hi = 127 * 2^shift + 2^(shift-1) - 1, the largest t that still rounds to
   // 127, and lo = -128 * 2^shift, which rounds to -128 exactly (0 with ReLU: every negative t ends as 0), which
-  // also keeps the rounding add inside int32.  Four VALU instructions per value, the same code for both
-  // activations.
+  // also keeps the rounding add inside int32 and makes both activations the same code.
   struct FastQuant {
     int shift, rnd, lo, hi;
-    float scale;  // 2^-shift
+    float scale, lo_f, hi_f;  // 2^-shift and the bounds as fp32 (exact for shifts up to 17)
   };
   static __device__ __forceinline__ FastQuant fast_quant(int shift, int act) {
-    const int rnd = (1 << (shift - 1)) - 1;
-    return {shift, rnd, act ? 0 : -128 * (1 << shift), (127 << shift) + rnd, __builtin_ldexpf(1.f, -shift)};
+    const int rnd = (1 << (shift - 1)) - 1, lo = act ? 0 : -128 * (1 << shift), hi = (127 << shift) + rnd;
+    return {shift, rnd, lo, hi, __builtin_ldexpf(1.f, -shift), (float)lo, (float)hi};
   }
-  // FLOAT_ROUND (shift <= 17): the clamped value has at most 25 significant bits with the lowest one zero at the
-  // ends, i.e. |c| <= 2^24 and exact in fp32, and one fused multiply-add c * 2^-shift + 1.5 * 2^23 rounds the
-  // quotient to an integer, halves to even (the sum lies in [2^23, 2^24), where fp32 steps by 1 and the constant is
-  // even): the low byte of the result's bit pattern is the two's-complement output.  Three VALU instructions per
-  // value instead of four; only the low byte of the returned word is meaningful.
+  // FLOAT_ROUND (shift <= 17): the bounds are at most 2^24 in magnitude, so they and everything between them are
+  // exact in fp32, and the conversion of a sum outside them (rounded, but monotone) stays outside them: the sum is
+  // converted first and clamped as a float (one median instruction), and one fused multiply-add
+  // c * 2^-shift + 1.5 * 2^23 rounds the quotient to an integer, halves to even (the result lies in [2^23, 2^24),
+  // where fp32 steps by 1 and the constant is even): the low byte of its bit pattern is the two's-complement
+  // output.  Three VALU instructions per value; only the low byte of the returned word is meaningful.
+  // Otherwise (shifts 18..23): clamp (a maximum and a minimum: with bounds that are not constants the compiler
+  // cannot form the integer median), bit extract, three-operand add, shift.
   template <bool FLOAT_ROUND = false>
   static __device__ __forceinline__ int requant_fast(int t, const FastQuant& f) {
-    // the median of (t, lo, hi) is the clamp; with bounds that are not constants the compiler cannot know that
-    // lo <= hi and emits a maximum and a minimum, so the instruction is written out (one scalar operand at most:
-    // hi travels in a vector register)
-    int c;
-    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(c) : "v"(t), "s"(f.lo), "v"(f.hi));
     if constexpr (FLOAT_ROUND) {
-      return __builtin_bit_cast(int, __builtin_fmaf((float)c, f.scale, 12582912.f));
+      const float c = __builtin_amdgcn_fmed3f((float)t, f.lo_f, f.hi_f);
+      return __builtin_bit_cast(int, __builtin_fmaf(c, f.scale, 12582912.f));
     } else {
+      int c = t < f.lo ? f.lo : t;
+      c = c > f.hi ? f.hi : c;
       const int bit = (int)__builtin_amdgcn_ubfe((unsigned)c, (unsigned)f.shift, 1u);
       return (c + bit + f.rnd) >> f.shift;
     }

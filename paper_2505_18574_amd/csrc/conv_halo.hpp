@@ -50,28 +50,47 @@ struct ConvHaloParams {
   FastDiv dWQ, dOW, dU, dPADC, dCC, dS, dCIN, dKW;  // dPADC: padding slots per patch row; dCC: data slots per pixel
 };
 
-// One 32 x 32 accumulator tile (sums already include the bias) -> int8 outputs of rows m < m_end.
-// Register 4 q + e of lane l is row l % 32, column 8 q + 4 (l / 32) + e of the tile.
-template <class ACC>
-static __device__ __forceinline__ void halo_store_tile(const GemmParams& p, int m, int m_end, int ncol0, const ACC& acc, int lane) {
+// TM 32 x 32 accumulator tiles, 32 rows apart (sums already include the bias) -> int8 outputs of rows m < m_end.
+// Register 4 q + e of lane l is row l % 32, column 8 q + 4 (l / 32) + e of a tile.  What the tiles have in common
+// (whole 32-column block or its 16-column remainder, which rounding) is decided once for all of them.
+template <int TM, class ACC>
+static __device__ __forceinline__ void halo_store_tiles(const GemmParams& p, int m0, int m_end, int ncol0, const ACC (&acc)[TM], int lane) {
   using EPI = EpilogueI8;
   if (ncol0 >= p.N) return;  // wave-uniform
   int8_t* C = (int8_t*)p.C;
-  int t[16];
-#pragma unroll
-  for (int r = 0; r < 16; r++) t[r] = acc[r];
   if (ncol0 + 32 <= p.N) {
-    const v4i o = p.shift >= 1 && p.shift <= 23 ? EPI::quant16_by_shift(t, EPI::fast_quant(p.shift, p.act)) : EPI::quant16(t, p.shift, p.act);
-    if (m < m_end) *(v4i*)(C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5)) = o;
-  } else if (m < m_end) {  // the 16-column remainder of the last block
+    auto blocks = [&](auto quant) {
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int n = ncol0 + 8 * q + 4 * (lane >> 5);
-      if (n + 3 < p.N) {
-        int v[4];
+      for (int i = 0; i < TM; i++) {
+        const int m = m0 + 32 * i;
+        int t[16];
 #pragma unroll
-        for (int e = 0; e < 4; e++) v[e] = EPI::requant(t[4 * q + e], p.shift, p.act);
-        *(unsigned*)(C + (int64_t)m * p.ldc + n) = EPI::pack4(v[0], v[1], v[2], v[3]);
+        for (int r = 0; r < 16; r++) t[r] = acc[i][r];
+        const v4i o = quant(t);
+        if (m < m_end) *(v4i*)(C + (int64_t)m * p.ldc + ncol0 + 16 * (lane >> 5)) = o;
+      }
+    };
+    if (p.shift >= 1 && p.shift <= 23) {
+      const EPI::FastQuant f = EPI::fast_quant(p.shift, p.act);
+      if (p.shift <= 17) blocks([&](const int* t) { return EPI::quant16<true>(t, f); });
+      else blocks([&](const int* t) { return EPI::quant16<false>(t, f); });
+    } else {
+      blocks([&](const int* t) { return EPI::quant16(t, p.shift, p.act); });
+    }
+  } else {  // the 16-column remainder of the last block
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      const int m = m0 + 32 * i;
+      if (m >= m_end) continue;
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int n = ncol0 + 8 * q + 4 * (lane >> 5);
+        if (n + 3 < p.N) {
+          int v[4];
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = EPI::requant(acc[i][4 * q + e], p.shift, p.act);
+          *(unsigned*)(C + (int64_t)m * p.ldc + n) = EPI::pack4(v[0], v[1], v[2], v[3]);
+        }
       }
     }
   }
@@ -328,8 +347,7 @@ __global__ void __launch_bounds__(512) conv_i8_halo_kernel(const GemmParams p, c
       } else {
         const int mrow0 = w.img * npix + w.q0 + wm * WTM + (lane & 31);
         const int m_end = (w.img + 1) * npix;  // rows of the unit past the end of its image belong to nobody
-#pragma unroll
-        for (int i = 0; i < TM; i++) halo_store_tile(p, mrow0 + i * 32, m_end, n0 + wn * 32, acc[i], lane);
+        halo_store_tiles(p, mrow0, m_end, n0 + wn * 32, acc, lane);
         if (grp == 0) wait_vm<0>();  // group 0's share of the next patch was requested at the top of this half step
       }
     }

@@ -127,13 +127,13 @@ static __device__ __forceinline__ void for_each_unswapped(int mrow0, int ncol0, 
   for (int r = 0; r < 16; r++) f(r, mrow0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), ncol0 + (lane & 31));
 }
 
-// int8 output stage: bias, v / 2^shift to nearest (halves to even), saturate, ReLU.
 // An epilogue that can take a whole wave tile at once declares WAVE_TILE.
 template <class E, class = void>
 struct has_wave_tile : std::false_type {};
 template <class E>
 struct has_wave_tile<E, std::void_t<decltype(E::WAVE_TILE)>> : std::true_type {};
 
+// int8 output stage: bias, v / 2^shift to nearest (halves to even), saturate, ReLU.
 struct EpilogueI8 {
   static constexpr bool SWAP = true;
   static constexpr bool LDS_STAGED = false;

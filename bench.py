@@ -423,6 +423,7 @@ def supplementary_paper_shapes(stream, only):
                          lambda A=A, B=B, bias=bias, C=C, c=case: ops.ac_gemm_i8(A, B, bias, C, c.shift, c.act), [], "")
             ms = isolated_time(w, stream, reps=20, rounds=3)
             out.append({"name": w.name, "ms": ms, "tops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["i8"],
+                        "gbs": w.bytes / ms / 1e6, "frac_hbm_peak": w.bytes / ms / 1e6 / HBM_PEAK_GBS,
                         "plan": list(ops.ac_gemm_i8_auto_plan(case.M, case.N, case.K, False))})
         for case in inputs.GEMM_BF16_PAPER:
             if only is not None and only not in "paper_shape_" + case.name:
@@ -436,7 +437,8 @@ def supplementary_paper_shapes(stream, only):
                          lambda A=A, B=B, C=C, ws=ws: ops.ac_gemm_bf16_ws(A, B, C, 1.0, 0.0, workspace=ws), [], "")
             ms = isolated_time(w, stream, reps=5, rounds=3)
             line = {"name": w.name, "ms": ms, "tflops": w.ops / ms / 1e9, "frac_mfma_peak": w.ops / ms / 1e9 / PEAK["bf16"],
-                    "gbs": w.bytes / ms / 1e6, "plan": list(ops.ac_gemm_bf16_auto_plan(case.M, case.N, case.K))}
+                    "gbs": w.bytes / ms / 1e6, "frac_hbm_peak": w.bytes / ms / 1e6 / HBM_PEAK_GBS,  # the large-K and small-K shapes are bounded by HBM
+                    "plan": list(ops.ac_gemm_bf16_auto_plan(case.M, case.N, case.K))}
             if case.K >= 8192:  # deep K: let the plan search look at K splits summed through a workspace
                 res = tune.tune_gemm_bf16(A, B, C, iterations=6)
                 line["searched_plan"] = list(res.best)
